@@ -1,0 +1,146 @@
+/*
+ * nvfp4.h -- C ABI of the MI355X (gfx950) NVFP4 hot-path library.
+ *
+ * The library implements the W4A4 NVFP4 linear-layer path of the paper:
+ * the quantizer of Sec. 2.2 ("NVFP4 Preliminaries", Eq. 2 and the scale
+ * definitions that follow it; Appendix "Scale Search NVFP4 Quantization",
+ * Eq. 12), the block-scaled FP4 GEMM used for forward, input-gradient and
+ * weight-gradient products (Sec. 2.2 "Multi-Shot AR NVFP4 Training",
+ * Sec. 3.1, Appendix "Implementation Details"), the NVFP4 KV cache of
+ * Sec. 3.2 (Eq. 5), and a fused activation + re-quantize GEMM epilogue.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or reads results back; scratch memory comes in
+ *     through the workspace argument (size from nvfp4_workspace_bytes()).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Every call only enqueues work on that stream and returns.
+ *   - An nvfp4_tensor is a HOST struct holding device pointers.
+ *   - Return value: NVFP4_OK or a negative nvfp4_status.  Arguments are
+ *     validated on the host before anything is launched; a call that returns
+ *     an error has launched nothing.  Non-finite inputs are outside the
+ *     contract.
+ *
+ * NVFP4 tensor format (Eq. 2):  x^ = code * block_scale * global_scale
+ *   codes   [rows, K/2]  two E2M1 codes per byte; element 2j in bits 3:0 and
+ *                        element 2j+1 in bits 7:4; a code is s|e1 e0|m with the
+ *                        magnitudes {0, .5, 1, 1.5, 2, 3, 4, 6} at indices 0..7
+ *   scales  [rows, K/16] one E4M3 byte (1-4-3, bias 7, max 448) per 16
+ *                        consecutive elements along K, plain row-major
+ *   global_scale [1]     FP32, one per tensor
+ * Rounding: global_scale = RN_fp32(amax / (448*6)) (1.0 for an all-zero
+ * tensor); block scale = E4M3 nearest to blockmax / (6*global_scale); code =
+ * E2M1 nearest to x / (block_scale*global_scale); all three decided in exact
+ * arithmetic, ties to the even mantissa, saturating at the format maximum.
+ * The sign bit of a code copies the sign bit of the input.
+ */
+#ifndef NVFP4_H
+#define NVFP4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum nvfp4_status {
+    NVFP4_OK = 0,
+    NVFP4_ERR_NULL = -1,       /* a required pointer is NULL */
+    NVFP4_ERR_SHAPE = -2,      /* non-positive size, K not a multiple of 16, K mismatch, bad enum */
+    NVFP4_ERR_ALIGN = -3,      /* pointer not 16-byte aligned, or ld not a multiple of 8 elements */
+    NVFP4_ERR_WORKSPACE = -4,  /* workspace NULL or smaller than nvfp4_workspace_bytes() */
+    NVFP4_ERR_LAUNCH = -5      /* the HIP runtime refused a launch */
+} nvfp4_status;
+
+typedef struct nvfp4_tensor {
+    uint8_t *codes;        /* device, [rows, K/2], 16-byte aligned */
+    uint8_t *scales;       /* device, [rows, K/16], 16-byte aligned */
+    float   *global_scale; /* device, [1] */
+    int64_t  rows;
+    int64_t  K;            /* multiple of 16 */
+} nvfp4_tensor;
+
+enum { NVFP4_OUT_F32 = 0, NVFP4_OUT_BF16 = 1 };
+enum { NVFP4_ACT_NONE = 0, NVFP4_ACT_GELU_TANH = 1 };
+enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2 };
+
+/*
+ * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
+ * x_bf16: device, bf16 [R, C], row stride ld elements (ld >= C, ld % 8 == 0).
+ * block_axis 0: blocks of 16 run along C; out has rows = R, K = C.
+ * block_axis 1: blocks run along R; out has rows = C, K = R (the operand
+ *               re-quantized along its other axis, emitted K-contiguous, as
+ *               the backward GEMMs need it).
+ * global_scale_in: device pointer to one float, or NULL.  NULL: the scale is
+ *               derived from the tensor's amax (one extra pass over x).
+ * out: rows/K must already describe the result; codes/scales/global_scale are
+ *      written (global_scale receives the scale that was used).
+ * workspace: nvfp4_workspace_bytes(NVFP4_OP_QUANTIZE, R, C, 0) bytes; contents
+ *      need no initialisation and are garbage afterwards.
+ */
+int nvfp4_quantize(const void *x_bf16, int64_t R, int64_t C, int64_t ld, int block_axis,
+                   const float *global_scale_in, nvfp4_tensor *out,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Block-scaled FP4 GEMM, FP32 accumulation (Sec. 2.2 / 3.1; Appendix
+ * "Implementation Details": forward, backward and weight-gradient GEMM
+ * operands are all NVFP4):
+ *   Y[m,n] = gsA*gsW * sum_b sA[m,b] sW[n,b] * sum_{j in b} cA[m,j] cW[n,j]
+ * A: [M, K], W: [N, K], both K-contiguous ("NT").  Y: device [M, N], row
+ * stride ldy elements, fp32 (NVFP4_OUT_F32) or bf16 (NVFP4_OUT_BF16, the fp32
+ * result rounded to nearest even).  dgrad and wgrad are this same call on
+ * operands produced by nvfp4_quantize with the matching block_axis.
+ */
+int nvfp4_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y, int64_t ldy,
+               int out_dtype, void *stream);
+
+/*
+ * GEMM with fused activation and re-quantization of the result along N
+ * (the "fused" W4A4 kernels of Sec. 3.1): H = bf16(act(A W^T)), out =
+ * quantize(H).  The result is byte-identical to nvfp4_gemm(BF16) followed by
+ * the activation in fp32, rounding to bf16, and nvfp4_quantize.
+ * global_scale_in != NULL: single pass, H is never written unless h_bf16_opt
+ *   is given.  NULL: H's amax is only known when the GEMM ends, so H is staged
+ *   in the workspace (or h_bf16_opt) and packed by a second light kernel.
+ * out: rows = M, K = N (N % 16 == 0).  h_bf16_opt: NULL or device bf16 [M, N].
+ * workspace: nvfp4_workspace_bytes(NVFP4_OP_GEMM_ACT_QUANT, M, N, 0).
+ */
+int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
+                         const float *global_scale_in, nvfp4_tensor *out, void *h_bf16_opt,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * KV-cache quantization (Sec. 3.2, Eq. 5): a chunk [T, H, d] (contiguous bf16)
+ * is viewed as [(T*H), d] and quantized with 16-element blocks along d and one
+ * global scale per call.  out: rows = T*H, K = d.
+ * workspace: nvfp4_workspace_bytes(NVFP4_OP_KV_QUANT, T, H, d).
+ */
+int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * KV-cache reconstruction (Sec. 3.2): kv_bf16_out[t,h,:] = RN_bf16(code *
+ * block_scale * global_scale), the product taken exactly and rounded once.
+ */
+int nvfp4_kv_dequant(const nvfp4_tensor *in, void *kv_bf16_out, int64_t T, int64_t H, int64_t d,
+                     void *stream);
+
+/* Workspace size in bytes for `op` (NVFP4_OP_*) at the given sizes; 0 on a bad op. */
+size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c);
+
+/* Static, human-readable text for a status code. */
+const char *nvfp4_status_string(int status);
+
+/* Launch durations: when enabled, every entry point brackets its kernels with
+ * HIP events on the caller's stream and nvfp4_last_kernel_ms() returns the
+ * duration of the most recent call's kernels (it synchronises on that call's
+ * end event).  Off by default; meant for benchmarks. */
+void  nvfp4_set_timing(int enabled);
+float nvfp4_last_kernel_ms(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NVFP4_H */

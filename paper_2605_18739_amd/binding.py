@@ -1,0 +1,189 @@
+"""ctypes binding of the NVFP4 HIP library: argument marshalling only.
+
+Function names mirror the C ABI in include/nvfp4.h.  torch supplies device
+memory and the current stream; every step of the path runs in the library's
+kernels.  There is no CPU fallback: if the shared library is missing, importing
+this module's entry points raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libnvfp4_hip.so")
+_lib = None
+
+OUT_F32, OUT_BF16 = 0, 1
+ACT_NONE, ACT_GELU_TANH = 0, 1
+OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT = 0, 1, 2
+
+
+class _CTensor(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("global_scale", ctypes.c_void_p), ("rows", ctypes.c_int64), ("K", ctypes.c_int64)]
+
+
+class NVFP4Error(RuntimeError):
+    pass
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise NVFP4Error(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2605_18739_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(_LIB_PATH)
+        c = ctypes
+        vp, i64, sz = c.c_void_p, c.c_int64, c.c_size_t
+        tp = c.POINTER(_CTensor)
+        L.nvfp4_quantize.restype = c.c_int
+        L.nvfp4_quantize.argtypes = [vp, i64, i64, i64, c.c_int, vp, tp, vp, sz, vp]
+        L.nvfp4_gemm.restype = c.c_int
+        L.nvfp4_gemm.argtypes = [tp, tp, vp, i64, c.c_int, vp]
+        L.nvfp4_gemm_act_quant.restype = c.c_int
+        L.nvfp4_gemm_act_quant.argtypes = [tp, tp, c.c_int, vp, tp, vp, vp, sz, vp]
+        L.nvfp4_kv_quant.restype = c.c_int
+        L.nvfp4_kv_quant.argtypes = [vp, i64, i64, i64, tp, vp, sz, vp]
+        L.nvfp4_kv_dequant.restype = c.c_int
+        L.nvfp4_kv_dequant.argtypes = [tp, vp, i64, i64, i64, vp]
+        L.nvfp4_workspace_bytes.restype = sz
+        L.nvfp4_workspace_bytes.argtypes = [c.c_int, i64, i64, i64]
+        L.nvfp4_status_string.restype = c.c_char_p
+        L.nvfp4_status_string.argtypes = [c.c_int]
+        L.nvfp4_set_timing.restype = None
+        L.nvfp4_set_timing.argtypes = [c.c_int]
+        L.nvfp4_last_kernel_ms.restype = c.c_float
+        L.nvfp4_last_kernel_ms.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise NVFP4Error(f"nvfp4 status {rc}: {lib().nvfp4_status_string(rc).decode()}")
+
+
+def _stream(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class NVFP4Tensor:
+    """Device NVFP4 tensor: codes [rows, K/2] u8, scales [rows, K/16] u8, global_scale [1] f32."""
+
+    def __init__(self, rows, K, device="cuda", codes=None, scales=None, global_scale=None):
+        self.rows, self.K = int(rows), int(K)
+        self.codes = codes if codes is not None else torch.empty((rows, K // 2), dtype=torch.uint8, device=device)
+        self.scales = scales if scales is not None else torch.empty((rows, K // 16), dtype=torch.uint8, device=device)
+        self.global_scale = (global_scale if global_scale is not None
+                             else torch.empty(1, dtype=torch.float32, device=device))
+
+    def c(self):
+        return _CTensor(self.codes.data_ptr(), self.scales.data_ptr(), self.global_scale.data_ptr(),
+                        self.rows, self.K)
+
+    @staticmethod
+    def from_host(codes_np, scales_np, global_scale, device="cuda"):
+        codes = torch.from_numpy(codes_np).to(device)
+        scales = torch.from_numpy(scales_np).to(device)
+        gs = torch.tensor([float(global_scale)], dtype=torch.float32, device=device)
+        return NVFP4Tensor(codes.shape[0], codes.shape[1] * 2, device, codes, scales, gs)
+
+
+def nvfp4_workspace_bytes(op, a, b=0, c=0):
+    return int(lib().nvfp4_workspace_bytes(op, a, b, c))
+
+
+def _workspace(nbytes, device):
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def nvfp4_quantize(x, block_axis=0, global_scale_in=None, out=None, workspace=None, stream=None):
+    """x: bf16 [R, C] device tensor with unit stride along C. Returns an NVFP4Tensor."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1
+    R, C = x.shape
+    ld = x.stride(0)
+    rows, K = (R, C) if block_axis == 0 else (C, R)
+    if out is None:
+        out = NVFP4Tensor(rows, K, x.device)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_QUANTIZE, R, C), x.device)
+    ct = out.c()
+    _check(lib().nvfp4_quantize(_ptr(x), R, C, ld, block_axis, _ptr(global_scale_in), ctypes.byref(ct),
+                                _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def nvfp4_gemm(A, W, out_dtype=OUT_F32, Y=None, stream=None):
+    M, N = A.rows, W.rows
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.float32 if out_dtype == OUT_F32 else torch.bfloat16,
+                        device=A.codes.device)
+    ca, cw = A.c(), W.c()
+    _check(lib().nvfp4_gemm(ctypes.byref(ca), ctypes.byref(cw), _ptr(Y), Y.stride(0), out_dtype,
+                            _stream(stream)))
+    return Y
+
+
+def nvfp4_gemm_act_quant(A, W, act=ACT_GELU_TANH, global_scale_in=None, out=None, h_bf16=None,
+                         workspace=None, stream=None):
+    M, N = A.rows, W.rows
+    dev = A.codes.device
+    if out is None:
+        out = NVFP4Tensor(M, N, dev)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_GEMM_ACT_QUANT, M, N, 1 if h_bf16 is not None else 0), dev)
+    ca, cw, co = A.c(), W.c(), out.c()
+    _check(lib().nvfp4_gemm_act_quant(ctypes.byref(ca), ctypes.byref(cw), act, _ptr(global_scale_in),
+                                      ctypes.byref(co), _ptr(h_bf16), _ptr(workspace), workspace.numel(),
+                                      _stream(stream)))
+    return out
+
+
+def nvfp4_kv_quant(kv, out=None, workspace=None, stream=None):
+    """kv: contiguous bf16 [T, H, d]."""
+    assert kv.dtype == torch.bfloat16 and kv.dim() == 3 and kv.is_contiguous()
+    T, H, d = kv.shape
+    if out is None:
+        out = NVFP4Tensor(T * H, d, kv.device)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_KV_QUANT, T, H, d), kv.device)
+    ct = out.c()
+    _check(lib().nvfp4_kv_quant(_ptr(kv), T, H, d, ctypes.byref(ct), _ptr(workspace), workspace.numel(),
+                                _stream(stream)))
+    return out
+
+
+def nvfp4_kv_dequant(q, T, H, d, out=None, stream=None):
+    if out is None:
+        out = torch.empty((T, H, d), dtype=torch.bfloat16, device=q.codes.device)
+    ct = q.c()
+    _check(lib().nvfp4_kv_dequant(ctypes.byref(ct), _ptr(out), T, H, d, _stream(stream)))
+    return out
+
+
+def nvfp4_set_timing(enabled):
+    lib().nvfp4_set_timing(1 if enabled else 0)
+
+
+def nvfp4_last_kernel_ms():
+    return float(lib().nvfp4_last_kernel_ms())
+
+
+def bf16_from_bits(bits_np, device="cuda"):
+    """uint16 numpy bit patterns -> bf16 device tensor (a copy, no arithmetic)."""
+    import numpy as np
+    t = torch.from_numpy(np.ascontiguousarray(bits_np).view(np.int16)).to(device)
+    return t.view(torch.bfloat16)
+
+
+def bits_from_bf16(t):
+    import numpy as np
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)

@@ -1,0 +1,237 @@
+// C ABI of the NVFP4 library: argument validation on the host, workspace
+// carving, kernel launches on the caller's stream.  See include/nvfp4.h for the
+// contract of every entry point.
+#include "../../include/nvfp4.h"
+#include "nvfp4_kernels.h"
+
+#include <algorithm>
+#include <mutex>
+
+using namespace nvfp4;
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_tensor(const nvfp4_tensor *t)
+{
+    if (!t || !t->codes || !t->scales || !t->global_scale) return NVFP4_ERR_NULL;
+    if (t->rows <= 0 || t->K <= 0 || (t->K & 15) != 0) return NVFP4_ERR_SHAPE;
+    if (!aligned16(t->codes) || !aligned16(t->scales)) return NVFP4_ERR_ALIGN;
+    return NVFP4_OK;
+}
+
+// ---- optional launch timing (benchmarks) -----------------------------------
+std::mutex g_mu;
+bool g_timing = false;
+hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
+bool g_have_interval = false;
+
+struct Timed {
+    hipStream_t s;
+    bool on;
+    explicit Timed(hipStream_t st) : s(st), on(g_timing)
+    {
+        if (!on) return;
+        if (!g_ev0) {
+            if (hipEventCreate(&g_ev0) != hipSuccess || hipEventCreate(&g_ev1) != hipSuccess) {
+                on = false;
+                return;
+            }
+        }
+        (void)hipEventRecord(g_ev0, s);
+    }
+    ~Timed()
+    {
+        if (!on) return;
+        (void)hipEventRecord(g_ev1, s);
+        g_have_interval = true;
+    }
+};
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+constexpr size_t kPartialBytes = (size_t)kMaxPartials * sizeof(uint32_t);
+
+int quantize_impl(const void *x, int64_t R, int64_t C, int64_t ld, int block_axis,
+                  const float *gs_in, nvfp4_tensor *out, void *ws, size_t ws_bytes, hipStream_t s)
+{
+    if (!x || !out) return NVFP4_ERR_NULL;
+    if (int rc = check_tensor(out)) return rc;
+    if (block_axis != 0 && block_axis != 1) return NVFP4_ERR_SHAPE;
+    if (R <= 0 || C <= 0 || ld < C) return NVFP4_ERR_SHAPE;
+    const int64_t rows = block_axis == 0 ? R : C, K = block_axis == 0 ? C : R;
+    if ((K & 15) != 0 || (C & 7) != 0) return NVFP4_ERR_SHAPE;
+    if (out->rows != rows || out->K != K) return NVFP4_ERR_SHAPE;
+    if (!aligned16(x) || (ld & 7) != 0) return NVFP4_ERR_ALIGN;
+    if (!gs_in && (!ws || ws_bytes < kPartialBytes)) return NVFP4_ERR_WORKSPACE;
+    if (ws && (reinterpret_cast<uintptr_t>(ws) & 3u)) return NVFP4_ERR_ALIGN;
+
+    const uint16_t *xb = static_cast<const uint16_t *>(x);
+    uint32_t *partial = static_cast<uint32_t *>(ws);
+    int n_partial = 0;
+    if (!gs_in) {
+        if (launch_amax(xb, R, C, ld, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
+    }
+    hipError_t e = block_axis == 0
+                       ? launch_quantize_rows(xb, R, C, ld, gs_in, partial, n_partial, out->codes,
+                                              out->scales, out->global_scale, s)
+                       : launch_quantize_cols(xb, R, C, ld, gs_in, partial, n_partial, out->codes,
+                                              out->scales, out->global_scale, s);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
+int check_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W)
+{
+    if (int rc = check_tensor(A)) return rc;
+    if (int rc = check_tensor(W)) return rc;
+    if (A->K != W->K) return NVFP4_ERR_SHAPE;
+    return NVFP4_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int nvfp4_quantize(const void *x_bf16, int64_t R, int64_t C, int64_t ld, int block_axis,
+                   const float *global_scale_in, nvfp4_tensor *out, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    Timed t(static_cast<hipStream_t>(stream));
+    int rc = quantize_impl(x_bf16, R, C, ld, block_axis, global_scale_in, out, workspace, workspace_bytes,
+                           static_cast<hipStream_t>(stream));
+    return rc;
+}
+
+int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (T <= 0 || H <= 0 || d <= 0) return NVFP4_ERR_SHAPE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Timed t(static_cast<hipStream_t>(stream));
+    return quantize_impl(kv_bf16, T * H, d, d, 0, nullptr, out, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(stream));
+}
+
+int nvfp4_kv_dequant(const nvfp4_tensor *in, void *kv_bf16_out, int64_t T, int64_t H, int64_t d,
+                     void *stream)
+{
+    if (!kv_bf16_out) return NVFP4_ERR_NULL;
+    if (int rc = check_tensor(in)) return rc;
+    if (T <= 0 || H <= 0 || d <= 0 || in->rows != T * H || in->K != d) return NVFP4_ERR_SHAPE;
+    if (!aligned16(kv_bf16_out)) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Timed t(static_cast<hipStream_t>(stream));
+    hipError_t e = launch_dequant_bf16(in->codes, in->scales, in->global_scale, in->rows, in->K,
+                                       static_cast<uint16_t *>(kv_bf16_out), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
+int nvfp4_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y, int64_t ldy, int out_dtype,
+               void *stream)
+{
+    if (!Y) return NVFP4_ERR_NULL;
+    if (int rc = check_gemm(A, W)) return rc;
+    if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16) return NVFP4_ERR_SHAPE;
+    if (ldy < W->rows) return NVFP4_ERR_SHAPE;
+    if (!aligned16(Y) || (ldy & 3) != 0) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Timed t(static_cast<hipStream_t>(stream));
+    GemmEpilogue ep{};
+    ep.out_dtype = out_dtype;
+    ep.act = NVFP4_ACT_NONE;
+    ep.Y = Y;
+    ep.ldy = ldy;
+    hipError_t e = launch_gemm(A->codes, A->scales, A->global_scale, W->codes, W->scales, W->global_scale,
+                               A->rows, W->rows, A->K, ep, nullptr, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
+int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
+                         const float *global_scale_in, nvfp4_tensor *out, void *h_bf16_opt,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_gemm(A, W)) return rc;
+    if (int rc = check_tensor(out)) return rc;
+    if (act != NVFP4_ACT_NONE && act != NVFP4_ACT_GELU_TANH) return NVFP4_ERR_SHAPE;
+    const int64_t M = A->rows, N = W->rows;
+    if (out->rows != M || out->K != N) return NVFP4_ERR_SHAPE;
+    if (h_bf16_opt && !aligned16(h_bf16_opt)) return NVFP4_ERR_ALIGN;
+    const size_t need = nvfp4_workspace_bytes(NVFP4_OP_GEMM_ACT_QUANT, M, N, h_bf16_opt ? 1 : 0);
+    if (!workspace || workspace_bytes < need) return NVFP4_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return NVFP4_ERR_ALIGN;
+
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timed t(s);
+    // workspace: [partials][H if not supplied]
+    uint32_t *partial = static_cast<uint32_t *>(workspace);
+    const size_t part_bytes = align_up((size_t)std::max(kMaxPartials, gemm_workgroups(M, N)) * 4, 256);
+    uint16_t *H = h_bf16_opt ? static_cast<uint16_t *>(h_bf16_opt)
+                             : reinterpret_cast<uint16_t *>(static_cast<uint8_t *>(workspace) + part_bytes);
+    GemmEpilogue ep{};
+    ep.out_dtype = NVFP4_OUT_BF16;
+    ep.act = act;
+    ep.Y = H;
+    ep.ldy = N;
+    ep.amax_partial = global_scale_in ? nullptr : partial;
+    int n_wg = 0;
+    if (launch_gemm(A->codes, A->scales, A->global_scale, W->codes, W->scales, W->global_scale, M, N,
+                    A->K, ep, &n_wg, s) != hipSuccess)
+        return NVFP4_ERR_LAUNCH;
+    int n_partial = n_wg;
+    if (!global_scale_in && n_wg == 0) {   // shape went to the untiled kernel: ordinary amax pass over H
+        if (launch_amax(H, M, N, N, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
+    }
+    hipError_t e = launch_quantize_rows(H, M, N, N, global_scale_in, partial, n_partial, out->codes,
+                                        out->scales, out->global_scale, s);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
+size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
+{
+    switch (op) {
+    case NVFP4_OP_QUANTIZE:
+    case NVFP4_OP_KV_QUANT:
+        return kPartialBytes;
+    case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c != 0: caller supplies H
+        if (a <= 0 || b <= 0) return 0;
+        size_t part = align_up((size_t)std::max(kMaxPartials, gemm_workgroups(a, b)) * 4, 256);
+        return part + (c ? 0 : align_up((size_t)a * (size_t)b * 2, 256));
+    }
+    default:
+        return 0;
+    }
+}
+
+const char *nvfp4_status_string(int status)
+{
+    switch (status) {
+    case NVFP4_OK: return "ok";
+    case NVFP4_ERR_NULL: return "a required pointer is NULL";
+    case NVFP4_ERR_SHAPE: return "bad shape: sizes must be positive, K a multiple of 16, operands must agree";
+    case NVFP4_ERR_ALIGN: return "bad alignment: pointers 16-byte aligned, leading dimensions multiples of 8 (4 for outputs)";
+    case NVFP4_ERR_WORKSPACE: return "workspace missing or too small (see nvfp4_workspace_bytes)";
+    case NVFP4_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    default: return "unknown status";
+    }
+}
+
+void nvfp4_set_timing(int enabled)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_timing = enabled != 0;
+    g_have_interval = false;
+}
+
+float nvfp4_last_kernel_ms(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_have_interval) return -1.0f;
+    float ms = -1.0f;
+    if (hipEventSynchronize(g_ev1) != hipSuccess) return -1.0f;
+    if (hipEventElapsedTime(&ms, g_ev0, g_ev1) != hipSuccess) return -1.0f;
+    return ms;
+}
+
+}  // extern "C"

@@ -1,0 +1,39 @@
+// Host-side launchers of the gfx950 NVFP4 kernels (internal to the library).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nvfp4 {
+
+constexpr int kMaxPartials = 1024;   // workgroups of the amax pass = partial maxima in the workspace
+
+hipError_t launch_amax(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t *partial,
+                       int *n_partial, hipStream_t s);
+hipError_t launch_quantize_rows(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
+                                const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
+                                float *gs_out, hipStream_t s);
+hipError_t launch_quantize_cols(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
+                                const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
+                                float *gs_out, hipStream_t s);
+hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, const float *gs, int64_t rows,
+                               int64_t K, uint16_t *out, hipStream_t s);
+
+// Epilogue of the GEMM
+struct GemmEpilogue {
+    int out_dtype;            // 0 fp32, 1 bf16, 2 none (quantized output only)
+    int act;                  // 0 none, 1 gelu-tanh
+    void *Y;                  // [M, N] fp32 or bf16, or nullptr
+    int64_t ldy;
+    uint32_t *amax_partial;   // per-workgroup |bf16(H)| maxima, or nullptr
+    const float *q_scale;     // global scale for the fused quantizer, or nullptr (no fused quantize)
+    uint8_t *q_codes;         // [M, N/2]
+    uint8_t *q_scales;        // [M, N/16]
+};
+
+hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const float *gsA,
+                       const uint8_t *codesW, const uint8_t *scalesW, const float *gsW, int64_t M,
+                       int64_t N, int64_t K, const GemmEpilogue &ep, int *n_wg, hipStream_t s);
+int gemm_workgroups(int64_t M, int64_t N);
+
+}  // namespace nvfp4

@@ -1,0 +1,287 @@
+// NVFP4 quantizer and KV-cache kernels for gfx950 (Sec. 2.2, Eq. 2; Appendix
+// on scale search, Eq. 12 with target 6; Sec. 3.2, Eq. 5).  All of them are
+// streaming kernels bound by HBM: 2 B read + 0.5625 B written per element
+// (quantize), 0.5625 B read + 2 B written (KV reconstruction).
+#include "nvfp4_device.h"
+#include "nvfp4_kernels.h"
+
+namespace nvfp4 {
+
+// --------------------------------------------------------------------------
+// Pass 1: per-workgroup partial amax (largest |bf16| bit pattern).
+// x is [R, C] with row stride ld; C % 8 == 0.  partial[blockIdx.x] is written
+// by every workgroup (no atomics, nothing to clear).
+// --------------------------------------------------------------------------
+template <bool CONTIG>
+__global__ __launch_bounds__(256) void amax_partial_kernel(const uint16_t *__restrict__ x, int64_t R,
+                                                           int64_t C, int64_t ld,
+                                                           uint32_t *__restrict__ partial)
+{
+    __shared__ uint32_t wave_max[4];
+    const int64_t vec_per_row = C >> 3;
+    const int64_t nvec = R * vec_per_row;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    uint32_t acc = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+        int64_t off;
+        if (CONTIG) off = i << 3;
+        else {
+            int64_t r = i / vec_per_row;
+            off = r * ld + ((i - r * vec_per_row) << 3);
+        }
+        uint4v v = *(const uint4v *)(x + off);    // ordinary load: pass 2 re-reads x, let the caches keep it
+        acc = pk_absmax_u16(acc, v.x);
+        acc = pk_absmax_u16(acc, v.y);
+        acc = pk_absmax_u16(acc, v.z);
+        acc = pk_absmax_u16(acc, v.w);
+    }
+    uint32_t m = wave_max_u32(pk_hmax_u16(acc));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        partial[blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+}
+
+// Every workgroup of a pass-2 kernel reduces the partials again (a few KB out
+// of L2) and so knows the tensor scale without a third launch.
+__device__ __forceinline__ float resolve_global_scale(const float *gs_in, const uint32_t *partial,
+                                                      int n_partial, float *gs_out, uint32_t *lds4)
+{
+    float sg;
+    if (gs_in) {
+        sg = *gs_in;
+    } else {
+        uint32_t acc = 0;
+        for (int i = threadIdx.x; i < n_partial; i += blockDim.x) acc = max(acc, partial[i]);
+        uint32_t m = wave_max_u32(acc);
+        if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = m;
+        __syncthreads();
+        m = 0;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) m = max(m, lds4[w]);
+        sg = global_scale_from_amax_bits(m);
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *gs_out = sg;
+    return sg;
+}
+
+// --------------------------------------------------------------------------
+// Pass 2, blocks along the contiguous axis: one lane per 16-element block
+// (two 128-bit loads, one 64-bit code store, one scale byte).
+// --------------------------------------------------------------------------
+template <bool CONTIG>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
+                                                            int64_t C, int64_t ld,
+                                                            const float *__restrict__ gs_in,
+                                                            const uint32_t *__restrict__ partial,
+                                                            int n_partial, uint8_t *__restrict__ codes,
+                                                            uint8_t *__restrict__ scales,
+                                                            float *__restrict__ gs_out)
+{
+    __shared__ uint32_t lds4[4];
+    const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
+    const float inv_6sg = 1.0f / (6.0f * sg);
+    const int64_t nb_row = C >> 4;
+    const int64_t nblk = R * nb_row;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < nblk; g += stride) {
+        int64_t off;
+        if (CONTIG) off = g << 4;
+        else {
+            int64_t r = g / nb_row;
+            off = r * ld + ((g - r * nb_row) << 4);
+        }
+        const uint4v *p = (const uint4v *)(x + off);
+        uint4v v0 = __builtin_nontemporal_load(p), v1 = __builtin_nontemporal_load(p + 1);
+        uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        uint32_t acc = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
+        float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
+        uint32_t sbyte = block_scale_exact(bmax, sg, inv_6sg);
+        uint32_t c0, c1;
+        encode_block16(w, e4m3_to_f32(sbyte), sg, c0, c1);
+        uint2v cc = {c0, c1};
+        __builtin_nontemporal_store(cc, (uint2v *)(codes + (g << 3)));
+        scales[g] = (uint8_t)sbyte;
+    }
+}
+
+// --------------------------------------------------------------------------
+// Pass 2, blocks along the ROW axis (the operand re-quantized along its other
+// axis for dgrad / wgrad).  x [R, C] -> codes [C, R/2], scales [C, R/16].
+// A workgroup takes a tile of 128 rows x 256 columns: thread (rb, cg) loads 16
+// rows x 8 columns (sixteen 128-bit loads, coalesced along C), owns 8 whole
+// blocks (one per column), and the packed results go through LDS so that every
+// output row is written in 64-byte runs.
+// --------------------------------------------------------------------------
+constexpr int kTR = 128, kTC = 256;
+__global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__restrict__ x, int64_t R,
+                                                            int64_t C, int64_t ld,
+                                                            const float *__restrict__ gs_in,
+                                                            const uint32_t *__restrict__ partial,
+                                                            int n_partial, uint8_t *__restrict__ codes,
+                                                            uint8_t *__restrict__ scales,
+                                                            float *__restrict__ gs_out)
+{
+    __shared__ uint32_t lds4[4];
+    __shared__ uint2v lds_codes[kTC][kTR / 16 + 1];     // [column][row block], padded
+    __shared__ uint8_t lds_scales[kTC][kTR / 16];
+    const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
+    const float inv_6sg = 1.0f / (6.0f * sg);
+    const int cg = threadIdx.x & 31, rb = threadIdx.x >> 5;
+    const int64_t r0 = (int64_t)blockIdx.y * kTR, c0 = (int64_t)blockIdx.x * kTC;
+    const int64_t r = r0 + rb * 16, c = c0 + cg * 8;
+    const bool live = (r < R) && (c < C);      // R % 16 == 0 and C % 8 == 0: whole blocks only
+    if (live) {
+        uint4v v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            v[i] = __builtin_nontemporal_load((const uint4v *)(x + (r + i) * ld + c));
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {      // column c + j: element j of every loaded vector
+            uint32_t w[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                uint32_t a = v[2 * i][j >> 1], b = v[2 * i + 1][j >> 1];
+                // pack rows 2i (low half) and 2i+1 (high half) of this column
+                w[i] = (j & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+            }
+            uint32_t acc = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
+            float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
+            uint32_t sbyte = block_scale_exact(bmax, sg, inv_6sg);
+            uint32_t k0, k1;
+            encode_block16(w, e4m3_to_f32(sbyte), sg, k0, k1);
+            uint2v cc = {k0, k1};
+            lds_codes[cg * 8 + j][rb] = cc;
+            lds_scales[cg * 8 + j][rb] = (uint8_t)sbyte;
+        }
+    }
+    __syncthreads();
+    // cooperative store: per column 8 row blocks = 64 B of codes + 8 B of scales
+    const int64_t rows_here = min((int64_t)kTR, R - r0);          // multiple of 16
+    const int nrb = (int)(rows_here >> 4);
+    for (int t = threadIdx.x; t < kTC * (kTR / 16); t += 256) {
+        int col = t >> 3, b = t & 7;
+        if (c0 + col < C && b < nrb) {
+            *(uint2v *)(codes + (c0 + col) * (R >> 1) + (r0 >> 1) + b * 8) = lds_codes[col][b];
+            scales[(c0 + col) * (R >> 4) + (r0 >> 4) + b] = lds_scales[col][b];
+        }
+    }
+}
+
+// --------------------------------------------------------------------------
+// KV-cache reconstruction: x^ = RN_bf16(code * s_b * s_g), the product exact,
+// one rounding.  For a given tensor there are only 127 * 8 distinct magnitudes,
+// so each workgroup builds that table exactly (fp64) in LDS once, split into a
+// low-byte and a high-byte plane per scale, and every element is then two
+// byte-permute lookups.  One lane per 16-element block.
+// --------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__restrict__ codes,
+                                                           const uint8_t *__restrict__ scales,
+                                                           const float *__restrict__ gs, int64_t nblk,
+                                                           uint16_t *__restrict__ out)
+{
+    __shared__ uint4v table[128];        // [scale byte] -> {lo bytes idx0-3, lo idx4-7, hi idx0-3, hi idx4-7}
+    const double sg = (double)*gs;
+    if (threadIdx.x < 128) {
+        const uint32_t s = threadIdx.x;
+        const double sb = (double)e4m3_to_f32(s < 127u ? s : 0u);
+        uint32_t lo0 = 0, lo1 = 0, hi0 = 0, hi1 = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const double mag = i < 4 ? 0.5 * i : (i == 4 ? 2.0 : (i == 5 ? 3.0 : (i == 6 ? 4.0 : 6.0)));
+            uint32_t h = bf16_rne_from_f64(mag * sb * sg);   // mag*sb: 6 bits, times 24 bits: exact
+            if (i < 4) { lo0 |= (h & 0xFFu) << (8 * i); hi0 |= (h >> 8) << (8 * i); }
+            else { lo1 |= (h & 0xFFu) << (8 * (i - 4)); hi1 |= (h >> 8) << (8 * (i - 4)); }
+        }
+        uint4v e = {lo0, lo1, hi0, hi1};
+        table[s] = e;
+    }
+    __syncthreads();
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < nblk; g += stride) {
+        uint2v cc = __builtin_nontemporal_load((const uint2v *)(codes + (g << 3)));
+        uint4v t = table[scales[g] & 0x7Fu];
+        uint32_t o[8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t cw = h ? cc.y : cc.x;
+            // selectors: magnitude index of the even / odd elements, one per byte
+            uint32_t se = cw & 0x07070707u, so = (cw >> 4) & 0x07070707u;
+            uint32_t lo_e = __builtin_amdgcn_perm(t.y, t.x, se), lo_o = __builtin_amdgcn_perm(t.y, t.x, so);
+            uint32_t hi_e = __builtin_amdgcn_perm(t.w, t.z, se), hi_o = __builtin_amdgcn_perm(t.w, t.z, so);
+            hi_e |= (cw << 4) & 0x80808080u;      // sign of even elements: bit 3 of each byte
+            hi_o |= cw & 0x80808080u;             // sign of odd elements: bit 7
+            // element 2b = (hi_e.b, lo_e.b), element 2b+1 = (hi_o.b, lo_o.b); dword b = elems 2b, 2b+1
+            uint32_t e01 = __builtin_amdgcn_perm(hi_e, lo_e, 0x05010400u);  // even elems 0,1 -> b0 b1
+            uint32_t e23 = __builtin_amdgcn_perm(hi_e, lo_e, 0x07030602u);
+            uint32_t o01 = __builtin_amdgcn_perm(hi_o, lo_o, 0x05010400u);
+            uint32_t o23 = __builtin_amdgcn_perm(hi_o, lo_o, 0x07030602u);
+            // e01 = [even(byte0) | even(byte1)<<16] ; o01 likewise for the odd nibbles
+            o[4 * h + 0] = __builtin_amdgcn_perm(o01, e01, 0x05040100u);
+            o[4 * h + 1] = __builtin_amdgcn_perm(o01, e01, 0x07060302u);
+            o[4 * h + 2] = __builtin_amdgcn_perm(o23, e23, 0x05040100u);
+            o[4 * h + 3] = __builtin_amdgcn_perm(o23, e23, 0x07060302u);
+        }
+        uint4v a = {o[0], o[1], o[2], o[3]}, b = {o[4], o[5], o[6], o[7]};
+        uint4v *q = (uint4v *)(out + (g << 4));
+        __builtin_nontemporal_store(a, q);
+        __builtin_nontemporal_store(b, q + 1);
+    }
+}
+
+// --------------------------------------------------------------------------
+// host-side launchers
+// --------------------------------------------------------------------------
+static int grid_for(int64_t work_items, int max_grid)
+{
+    int64_t g = (work_items + 255) / 256;
+    if (g < 1) g = 1;
+    return (int)(g < max_grid ? g : max_grid);
+}
+
+hipError_t launch_amax(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t *partial,
+                       int *n_partial, hipStream_t s)
+{
+    int grid = grid_for(R * (C >> 3), kMaxPartials);
+    *n_partial = grid;
+    if (ld == C) amax_partial_kernel<true><<<grid, 256, 0, s>>>(x, R, C, ld, partial);
+    else amax_partial_kernel<false><<<grid, 256, 0, s>>>(x, R, C, ld, partial);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_rows(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
+                                const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
+                                float *gs_out, hipStream_t s)
+{
+    int grid = grid_for(R * (C >> 4), 2048);
+    if (ld == C)
+        quantize_rows_kernel<true><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes,
+                                                        scales, gs_out);
+    else
+        quantize_rows_kernel<false><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes,
+                                                         scales, gs_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_cols(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
+                                const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
+                                float *gs_out, hipStream_t s)
+{
+    dim3 grid((unsigned)((C + kTC - 1) / kTC), (unsigned)((R + kTR - 1) / kTR));
+    quantize_cols_kernel<<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes, scales, gs_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, const float *gs, int64_t rows,
+                               int64_t K, uint16_t *out, hipStream_t s)
+{
+    int64_t nblk = rows * (K >> 4);
+    int grid = grid_for(nblk, 2048);
+    dequant_bf16_kernel<<<grid, 256, 0, s>>>(codes, scales, gs, nblk, out);
+    return hipGetLastError();
+}
+
+}  // namespace nvfp4

@@ -1,0 +1,104 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_18739_amd as nv
+from paper_2605_18739_amd.binding import _CTensor
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "nvfp4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nvfp4_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = nv.lib()
+    names = _declared_symbols()
+    assert {"nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_act_quant", "nvfp4_kv_quant",
+            "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings():
+    L = nv.lib()
+    assert L.nvfp4_status_string(0) == b"ok"
+    for rc in (-1, -2, -3, -4, -5):
+        assert len(L.nvfp4_status_string(rc)) > 5
+    assert L.nvfp4_status_string(-99) == b"unknown status"
+
+
+def test_workspace_sizes():
+    assert nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE, 128, 256) == 4096
+    assert nv.nvfp4_workspace_bytes(nv.OP_KV_QUANT, 10, 24, 128) == 4096
+    with_h = nv.nvfp4_workspace_bytes(nv.OP_GEMM_ACT_QUANT, 3520, 14336, 0)
+    without_h = nv.nvfp4_workspace_bytes(nv.OP_GEMM_ACT_QUANT, 3520, 14336, 1)
+    assert with_h - without_h == 3520 * 14336 * 2
+    assert nv.nvfp4_workspace_bytes(99, 1, 1, 1) == 0
+
+
+def _t(codes=0x1000, scales=0x2000, gs=0x3000, rows=4, K=32):
+    return _CTensor(codes, scales, gs, rows, K)
+
+
+def test_quantize_rejects_bad_arguments_on_the_host():
+    """Pointers below are fake but never dereferenced: validation fails first."""
+    L = nv.lib()
+    x, ws = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000)
+    ok = _t()
+    q = lambda xp, R, C, ld, ax, t, w, wb: L.nvfp4_quantize(xp, R, C, ld, ax, None, ctypes.byref(t), w, wb, None)
+    assert q(None, 4, 32, 32, 0, ok, ws, 4096) == -1                 # NULL input
+    assert q(x, 4, 32, 32, 0, _t(codes=None), ws, 4096) == -1        # NULL output plane
+    assert q(x, 4, 24, 24, 0, _t(K=24), ws, 4096) == -2              # K % 16
+    assert q(x, 4, 32, 32, 0, _t(rows=5), ws, 4096) == -2            # out shape mismatch
+    assert q(x, 4, 32, 16, 0, ok, ws, 4096) == -2                    # ld < C
+    assert q(x, 4, 32, 32, 2, ok, ws, 4096) == -2                    # bad axis
+    assert q(ctypes.c_void_p(0x10002), 4, 32, 32, 0, ok, ws, 4096) == -3   # misaligned x
+    assert q(x, 4, 32, 36, 0, ok, ws, 4096) == -3                    # ld % 8
+    assert q(x, 4, 32, 32, 0, _t(codes=0x1001), ws, 4096) == -3      # misaligned codes
+    assert q(x, 4, 32, 32, 0, ok, None, 0) == -4                     # workspace missing
+    assert q(x, 4, 32, 32, 0, ok, ws, 100) == -4                     # workspace too small
+    # transposed: rows = C, K = R
+    assert q(x, 32, 8, 8, 1, _t(rows=8, K=32), ws, 100) == -4
+    assert q(x, 24, 8, 8, 1, _t(rows=8, K=24), ws, 4096) == -2
+
+
+def test_gemm_and_kv_reject_bad_arguments_on_the_host():
+    L = nv.lib()
+    y = ctypes.c_void_p(0x40000)
+    a, w = _t(rows=4, K=32), _t(rows=8, K=32)
+    assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), None, 8, 0, None) == -1
+    assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(_t(rows=8, K=64)), y, 8, 0, None) == -2   # K mismatch
+    assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 4, 0, None) == -2                  # ldy < N
+    assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 8, 7, None) == -2                  # bad dtype
+    assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 10, 0, None) == -3                 # ldy % 4
+    out = _t(rows=4, K=16)
+    ws = ctypes.c_void_p(0x50000)
+    assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w), 1, None, ctypes.byref(out), None, ws, 1 << 20, None) == -2
+    out = _t(rows=4, K=8)
+    assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w), 1, None, ctypes.byref(out), None, ws, 1 << 20, None) == -2
+    w16 = _t(rows=16, K=32)
+    out = _t(rows=4, K=16)
+    assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w16), 5, None, ctypes.byref(out), None, ws, 1 << 20, None) == -2
+    assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w16), 1, None, ctypes.byref(out), None, ws, 16, None) == -4
+    kv = ctypes.c_void_p(0x60000)
+    t = _t(rows=6, K=32)
+    assert L.nvfp4_kv_quant(kv, 0, 3, 32, ctypes.byref(t), ws, 4096, None) == -2
+    assert L.nvfp4_kv_quant(kv, 2, 3, 24, ctypes.byref(_t(rows=6, K=24)), ws, 4096, None) == -2
+    assert L.nvfp4_kv_dequant(ctypes.byref(t), None, 2, 3, 32, None) == -1
+    assert L.nvfp4_kv_dequant(ctypes.byref(t), kv, 2, 4, 32, None) == -2
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    from paper_2605_18739_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libnvfp4_hip.so")
+    with pytest.raises(binding.NVFP4Error):
+        binding.lib()

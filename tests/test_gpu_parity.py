@@ -1,0 +1,293 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element, on seeded inputs that span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_18739_amd as nv
+from paper_2605_18739_amd import workloads as wl
+from tests.parity import assert_gemm_close, assert_q_equal, dev_bf16, host_q
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ quantize
+
+def _quant_case(oracle, xb, what, **kw):
+    say(f"[quantize] {what} shape={xb.shape}")
+    oq = oracle.quantize(xb)
+    gq = nv.nvfp4_quantize(dev_bf16(xb))
+    assert_q_equal(gq, oq, what)
+    return oq, gq
+
+
+def test_quantize_config1(oracle):
+    cfg = wl.config1()
+    _quant_case(oracle, cfg["A"], "config1 A")
+    _quant_case(oracle, cfg["W"], "config1 W")
+
+
+@pytest.mark.parametrize("R,C", [(1, 16), (3, 48), (257, 272), (64, 4096), (1000, 1040)])
+def test_quantize_ragged_shapes(oracle, R, C):
+    g = np.random.default_rng(R * 7 + C)
+    x = g.standard_normal((R, C)).astype(np.float32) * np.float32(10.0 ** g.uniform(-3, 3))
+    _quant_case(oracle, wl.to_bf16_bits(x), f"ragged {R}x{C}")
+
+
+def test_quantize_outliers_small_weights_and_gradients(oracle):
+    _quant_case(oracle, wl.activation_with_outliers(300, 3072, 1, 0), "outlier activations")
+    _quant_case(oracle, wl.normal((256, 3072), 0.02, 1, 1), "weights sigma 0.02")
+    _quant_case(oracle, wl.normal((128, 14336), 1e-3, 4, 2), "gradients sigma 1e-3")
+
+
+def test_quantize_degenerate(oracle):
+    z = np.zeros((8, 64), np.float32)
+    _quant_case(oracle, wl.to_bf16_bits(z), "all zero")
+    z[3, 17] = -0.0
+    z[5, 40] = 3.0            # one non-zero element: every other block is all zero
+    _quant_case(oracle, wl.to_bf16_bits(z), "single element")
+    z[:] = 1.0
+    _quant_case(oracle, wl.to_bf16_bits(z), "constant")
+    big = np.full((4, 32), 3.0e38, np.float32)
+    big[0, :16] = 1e-30       # block scale underflows to 0
+    _quant_case(oracle, wl.to_bf16_bits(big), "huge and tiny")
+
+
+def test_quantize_tie_heavy(oracle):
+    """amax = 5.25 gives s_g = 2^-9 exactly; small-integer multiples of 2^-k then land
+    on rounding midpoints all the time, which exercises the exact slow path."""
+    g = np.random.default_rng(17)
+    x = g.integers(-40, 41, size=(128, 256)).astype(np.float32) * np.float32(0.125)
+    x[x > 5.25] = 5.25
+    x[x < -5.25] = -5.25
+    x[7, 100] = 5.25
+    _quant_case(oracle, wl.to_bf16_bits(x), "tie heavy s_g=2^-9")
+    x2 = g.integers(-21, 22, size=(64, 128)).astype(np.float32)
+    x2[0, 0] = 21.0           # s_g = 21/2688 = 2^-7
+    _quant_case(oracle, wl.to_bf16_bits(x2), "integers s_g=2^-7")
+
+
+def test_quantize_given_scale_and_stride(oracle):
+    g = np.random.default_rng(23)
+    xb = wl.to_bf16_bits(g.standard_normal((100, 200)).astype(np.float32))   # padded rows: ld = 200, C = 176
+    x = dev_bf16(xb)
+    view = x[:, :176]
+    oq = oracle.quantize(np.ascontiguousarray(xb[:, :176]))
+    assert_q_equal(nv.nvfp4_quantize(view), oq, "strided")
+    for gs in (2.0 ** -9, 0.0011, 0.02):
+        gsd = torch.tensor([gs], dtype=torch.float32, device="cuda")
+        oq = oracle.quantize(np.ascontiguousarray(xb[:, :176]), global_scale_in=gs)
+        assert_q_equal(nv.nvfp4_quantize(view, global_scale_in=gsd), oq, f"given scale {gs}")
+
+
+@pytest.mark.parametrize("R,C", [(16, 8), (48, 24), (128, 256), (400, 520), (1024, 3072)])
+def test_quantize_transposed(oracle, R, C):
+    g = np.random.default_rng(R + C)
+    xb = wl.to_bf16_bits(g.standard_normal((R, C)).astype(np.float32) * np.float32(0.3))
+    say(f"[quantize^T] {R}x{C}")
+    oq = oracle.quantize(xb, block_axis=1)
+    gq = nv.nvfp4_quantize(dev_bf16(xb), block_axis=1)
+    assert gq.rows == C and gq.K == R
+    assert_q_equal(gq, oq, f"transposed {R}x{C}")
+
+
+def test_quantize_is_deterministic():
+    xb = wl.activation_with_outliers(512, 3072, 1, 0)
+    x = dev_bf16(xb)
+    a, b = host_q(nv.nvfp4_quantize(x)), host_q(nv.nvfp4_quantize(x))
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all() and a[2] == b[2]
+
+
+# ------------------------------------------------------------------------ KV
+
+@pytest.mark.parametrize("T,H,d", [(1, 1, 16), (33, 24, 128), (257, 3, 64)])
+def test_kv_round_trip(oracle, T, H, d):
+    say(f"[kv] T={T} H={H} d={d}")
+    kb = wl.kv_tensor(T, H, d, 3, 0)
+    oq = oracle.quantize(kb.reshape(T * H, d))
+    kv = dev_bf16(kb)
+    gq = nv.nvfp4_kv_quant(kv)
+    assert_q_equal(gq, oq, "kv quant")
+    back = nv.nvfp4_kv_dequant(gq, T, H, d)
+    want = oracle.dequant_bf16(oq).reshape(T, H, d)
+    got = nv.bits_from_bf16(back)
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"kv dequant: {len(bad)} differ, first {bad[0]} gpu {got[tuple(bad[0])]:#x} oracle {want[tuple(bad[0])]:#x}"
+
+
+def test_kv_dequant_awkward_scales(oracle):
+    """Global scales with full 24-bit mantissas and subnormal block scales: the single
+    rounding to bf16 must match the oracle's."""
+    g = np.random.default_rng(5)
+    rows, d = 64, 128
+    codes = g.integers(0, 256, size=(rows, d // 2)).astype(np.uint8)
+    scales = g.integers(0, 127, size=(rows, d // 16)).astype(np.uint8)
+    for gs in (np.float32(1.0 / 2688), np.float32(0.0123456789), np.float32(3.3e-5), np.float32(1.0)):
+        oq = oracle.Q(codes, scales, gs)
+        want = oracle.dequant_bf16(oq)
+        t = nv.NVFP4Tensor.from_host(codes, scales, gs)
+        got = nv.bits_from_bf16(nv.nvfp4_kv_dequant(t, rows, 1, d)).reshape(rows, d)
+        assert (got == want).all(), f"gs={gs}"
+
+
+# ---------------------------------------------------------------------- GEMM
+
+def _gemm_case(oracle, ab, wb, what, rows=None, check_bf16=True):
+    say(f"[gemm] {what} A{ab.shape} W{wb.shape}")
+    oa, ow = oracle.quantize(ab), oracle.quantize(wb)
+    ga, gw = nv.nvfp4_quantize(dev_bf16(ab)), nv.nvfp4_quantize(dev_bf16(wb))
+    assert_q_equal(ga, oa, what + " A")
+    assert_q_equal(gw, ow, what + " W")
+    Y, S = oracle.gemm(oa, ow, rows=rows)
+    y32 = nv.nvfp4_gemm(ga, gw, nv.OUT_F32)
+    torch.cuda.synchronize()
+    y = y32.cpu().numpy()
+    ysel = y if rows is None else y[rows]
+    fro, worst = assert_gemm_close(ysel, Y, S, what)
+    say(f"        rel fro {fro:.2e}  worst err/S {worst:.2e}")
+    if check_bf16:
+        y16 = nv.nvfp4_gemm(ga, gw, nv.OUT_BF16)
+        # bf16 output is the fp32 result rounded once, bit for bit
+        assert (nv.bits_from_bf16(y16) == nv.bits_from_bf16(y32.to(torch.bfloat16))).all()
+    return y32
+
+
+def test_gemm_config1(oracle):
+    cfg = wl.config1()
+    _gemm_case(oracle, cfg["A"], cfg["W"], "config1")
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 4, 64), (100, 136, 192), (130, 260, 128), (300, 520, 64),
+                                   (513, 1028, 320)])
+def test_gemm_ragged_tiles(oracle, M, N, K):
+    g = np.random.default_rng(M + N + K)
+    ab = wl.to_bf16_bits(g.standard_normal((M, K)).astype(np.float32))
+    wb = wl.to_bf16_bits((g.standard_normal((N, K)) * 0.02).astype(np.float32))
+    _gemm_case(oracle, ab, wb, f"ragged {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("M,N,K", [(5, 8, 16), (7, 12, 48), (9, 4, 80)])
+def test_gemm_small_k_untiled(oracle, M, N, K):
+    g = np.random.default_rng(M * N * K)
+    ab = wl.to_bf16_bits(g.standard_normal((M, K)).astype(np.float32))
+    wb = wl.to_bf16_bits(g.standard_normal((N, K)).astype(np.float32))
+    _gemm_case(oracle, ab, wb, f"untiled {M}x{N}x{K}", check_bf16=(N % 4 == 0))
+
+
+def test_gemm_unit_scales_is_bit_exact(oracle):
+    """Block scales 1, tensor scales 1: every partial sum is a small multiple of 1/4, so
+    FP32 accumulation in any order is exact and the GPU must match the oracle bit for bit."""
+    g = np.random.default_rng(4)
+    mags = np.array([0, .5, 1, 1.5, 2, 3, 4, 6])
+
+    def unit(rows, K):
+        v = mags[g.integers(0, 8, size=(rows, K))] * g.choice([-1.0, 1.0], size=(rows, K))
+        v[:, 0::16] = 6.0
+        v[0, 1] = 2688.0
+        return wl.to_bf16_bits(v.astype(np.float32))
+
+    ab, wb = unit(192, 256), unit(160, 256)
+    oa, ow = oracle.quantize(ab), oracle.quantize(wb)
+    assert oa.global_scale == 1 and ow.global_scale == 1
+    Y, _ = oracle.gemm(oa, ow)
+    ga, gw = nv.nvfp4_quantize(dev_bf16(ab)), nv.nvfp4_quantize(dev_bf16(wb))
+    y = nv.nvfp4_gemm(ga, gw, nv.OUT_F32).cpu().numpy().astype(np.float64)
+    # [0, 0] holds 2688 * 2688 plus quarters: more than 24 bits, the only inexact element
+    y[0, 0] = Y[0, 0] = 0.0
+    assert (y == Y).all()
+
+
+def test_gemm_scale_linearity_and_determinism(oracle):
+    cfg = wl.config1()
+    ga, gw = nv.nvfp4_quantize(dev_bf16(cfg["A"])), nv.nvfp4_quantize(dev_bf16(cfg["W"]))
+    y1 = nv.nvfp4_gemm(ga, gw).clone()
+    y2 = nv.nvfp4_gemm(ga, gw)
+    assert torch.equal(y1, y2)
+    ga.global_scale.mul_(0.5)
+    y3 = nv.nvfp4_gemm(ga, gw)
+    assert torch.equal(y3, y1 * 0.5)
+
+
+def test_gemm_backward_operands(oracle):
+    """dgrad dX = dY W and wgrad dW = dY^T X with every operand re-quantized along its own K."""
+    M, N, K = 272, 320, 192          # X [M,K], W [N,K], dY [M,N]
+    g = np.random.default_rng(31)
+    xb = wl.activation_with_outliers(M, K, 4, 0)
+    wb = wl.normal((N, K), 0.02, 4, 1)
+    dyb = wl.normal((M, N), 1e-3, 4, 2)
+    x, w, dy = dev_bf16(xb), dev_bf16(wb), dev_bf16(dyb)
+    # dgrad: A = dY [M, K'=N] (blocks along N), W' = W^T [K, K'=N] (blocks along W's row axis)
+    o_dy, o_wt = oracle.quantize(dyb), oracle.quantize(np.ascontiguousarray(wb.T))
+    g_dy, g_wt = nv.nvfp4_quantize(dy), nv.nvfp4_quantize(w, block_axis=1)
+    assert_q_equal(g_wt, o_wt, "W^T")
+    Y, S = oracle.gemm(o_dy, o_wt)
+    assert_gemm_close(nv.nvfp4_gemm(g_dy, g_wt).cpu().numpy(), Y, S, "dgrad")
+    # wgrad: A = dY^T [N, K'=M], W' = X^T [K, K'=M]
+    o_dyt, o_xt = oracle.quantize(np.ascontiguousarray(dyb.T)), oracle.quantize(np.ascontiguousarray(xb.T))
+    g_dyt, g_xt = nv.nvfp4_quantize(dy, block_axis=1), nv.nvfp4_quantize(x, block_axis=1)
+    assert_q_equal(g_dyt, o_dyt, "dY^T")
+    assert_q_equal(g_xt, o_xt, "X^T")
+    Y, S = oracle.gemm(o_dyt, o_xt)
+    assert_gemm_close(nv.nvfp4_gemm(g_dyt, g_xt).cpu().numpy(), Y, S, "wgrad")
+
+
+# --------------------------------------------------- fused activation + quantize
+
+def _act_quant_case(oracle, M, N, K, given_scale, what):
+    say(f"[act-quant] {what} {M}x{N}x{K} given_scale={given_scale}")
+    g = np.random.default_rng(M + N)
+    ab = wl.activation_with_outliers(M, K, 2, 0)
+    wb = wl.normal((N, K), 0.02, 2, 1)
+    ga, gw = nv.nvfp4_quantize(dev_bf16(ab)), nv.nvfp4_quantize(dev_bf16(wb))
+    oa, ow = oracle.quantize(ab), oracle.quantize(wb)
+    h = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    gs = torch.tensor([0.004], dtype=torch.float32, device="cuda") if given_scale else None
+    out = nv.nvfp4_gemm_act_quant(ga, gw, nv.ACT_GELU_TANH, global_scale_in=gs, h_bf16=h)
+    torch.cuda.synchronize()
+    hb = nv.bits_from_bf16(h)
+    # (1) the packed output is exactly the quantizer applied to the H this GEMM produced
+    oq = oracle.quantize(hb, global_scale_in=0.004 if given_scale else None)
+    assert_q_equal(out, oq, what + " fused vs quantize(H)")
+    # (2) H itself is the activation of the GEMM, within bf16 rounding of the fp64 chain
+    Y, S = oracle.gemm(oa, ow)
+    want = wl.bf16_bits_to_f32(oracle.gelu_tanh_bf16(Y)).astype(np.float64)
+    got = wl.bf16_bits_to_f32(hb).astype(np.float64)
+    tol = 2.0 ** -7 * np.abs(want) + 2.0 ** -15 * S + 1e-30      # one bf16 ulp + GEMM bound
+    assert (np.abs(got - want) <= tol).all()
+    assert (got != want).mean() < 0.02                            # and it is the same bf16 almost everywhere
+    # (3) without the optional H buffer the bytes are the same
+    out2 = nv.nvfp4_gemm_act_quant(ga, gw, nv.ACT_GELU_TANH, global_scale_in=gs)
+    a, b = host_q(out), host_q(out2)
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all() and a[2] == b[2]
+
+
+@pytest.mark.parametrize("given_scale", [False, True])
+def test_gemm_act_quant(oracle, given_scale):
+    _act_quant_case(oracle, 200, 272, 256, given_scale, "small")
+    _act_quant_case(oracle, 520, 1040, 128, given_scale, "multi-tile")
+
+
+# -------------------------------------------------------- full benchmark sizes
+
+def test_full_size_projection_config2(oracle):
+    """A[3520,3072], W[3072,3072]: codes and scales in full, GEMM on sampled rows
+    (first/last row of tiles plus seeded rows), in the launch configuration bench.py times."""
+    cfg = wl.config2()
+    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, 3455, 3456, 3519],
+                                     np.random.default_rng(0).integers(0, 3520, 24)])).astype(np.int64)
+    y = _gemm_case(oracle, cfg["A"], cfg["W"], "config2", rows=rows)
+    assert torch.isfinite(y).all()
+
+
+def test_gemm_large_tile_path(oracle):
+    """A shape large enough for the 256x256 workgroup tile, with ragged M and N tails."""
+    M, N, K = 4100, 8196, 128
+    g = np.random.default_rng(77)
+    ab = wl.activation_with_outliers(M, K, 7, 0)
+    wb = wl.normal((N, K), 0.02, 7, 1)
+    rows = np.unique(np.concatenate([[0, 255, 256, 4095, 4096, 4099], g.integers(0, M, 20)])).astype(np.int64)
+    _gemm_case(oracle, ab, wb, "large tile", rows=rows)
