@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the NVFP4 hot path on one MI355X.
+
+A step is one forward pass of the DiT FFN pair (A[3520,3072] -> up 14336 -> GELU-tanh ->
+re-quantize -> down 3072, bf16 out): quantize A (amax + encode), up GEMM with activation and
+re-quantization, down GEMM.  Weights are quantized once, outside the timed region.  The value
+is the two GEMMs' 2*M*N*K flops over the whole step time.  The other rows of the path (KV
+quantize / dequantize, transposed quantize, dgrad / wgrad GEMMs at the training shape) are
+measured once each after the timed region and reported under "rows".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16_TFLOPS = 2500.0     # MI355X dense f16/bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+B_PER_ELEM = 2.5625               # quantize: 2 B read + 0.5625 B written; KV dequant the reverse
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-rows", action="store_true", help="skip the per-row extras (KV, training triplet)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2605_18739_amd as nv
+    from paper_2605_18739_amd import workloads as wl
+
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    M, D, F = wl.TOKENS_INFER, wl.D_MODEL, wl.D_FFN
+    cfg = wl.config3()
+    A = nv.bf16_from_bits(cfg["A"], dev)
+    W1 = nv.nvfp4_quantize(nv.bf16_from_bits(cfg["W1"], dev))
+    W2 = nv.nvfp4_quantize(nv.bf16_from_bits(cfg["W2"], dev))
+    # everything a step touches is allocated up front
+    qA = nv.NVFP4Tensor(M, D, dev)
+    qH = nv.NVFP4Tensor(M, F, dev)
+    Y = torch.empty((M, D), dtype=torch.bfloat16, device=dev)
+    ws_q = torch.empty(nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE, M, D), dtype=torch.uint8, device=dev)
+    ws_g = torch.empty(nv.nvfp4_workspace_bytes(nv.OP_GEMM_ACT_QUANT, M, F, 0), dtype=torch.uint8, device=dev)
+
+    def step():
+        nv.nvfp4_quantize(A, out=qA, workspace=ws_q)
+        nv.nvfp4_gemm_act_quant(qA, W1, nv.ACT_GELU_TANH, out=qH, workspace=ws_g)
+        nv.nvfp4_gemm(qH, W2, nv.OUT_BF16, Y=Y)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    nv.nvfp4_set_timing(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    n_gemm, ms_gemm = nv.nvfp4_timing_read(nv.OP_GEMM)
+    n_fused, ms_fused = nv.nvfp4_timing_read(nv.OP_GEMM_ACT_QUANT)
+    n_q, ms_q = nv.nvfp4_timing_read(nv.OP_QUANTIZE)
+    nv.nvfp4_set_timing(False)
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    flops_gemm = 2.0 * M * F * D
+    value = 2 * flops_gemm / (ms_step * 1e-3) / 1e12
+    # dominant kernel: the down-projection GEMM launch (one kernel per nvfp4_gemm call)
+    gemm_ms = ms_gemm / max(n_gemm, 1)
+    achieved = flops_gemm / (gemm_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_f16mfma_kernel (down projection 3520x3072x14336)",
+                "achieved": round(achieved, 1), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": round(gemm_ms, 4), "launches": n_gemm}
+    fused_ms = ms_fused / max(n_fused, 1)
+    q_ms = ms_q / max(n_q, 1)
+    kernels = {
+        "up_gemm_gelu_requant": {"ms": round(fused_ms, 4), "tflops": round(flops_gemm / (fused_ms * 1e-3) / 1e12, 1)},
+        "quantize_A_3520x3072": {"ms": round(q_ms, 4),
+                                 "GBs": round(B_PER_ELEM * M * D / (q_ms * 1e-3) / 1e9, 1)},
+    }
+
+    rows = None if args.no_rows else measure_rows(nv, wl, torch, np)
+    cpu = None if args.no_cpu else cpu_baseline(cfg, wl, np)
+
+    out = {
+        "metric": "nvfp4_gemm_tflops_dit_ffn", "value": round(value, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "dit_ffn_pair: A[3520,3072] -> W1[14336,3072] -> gelu_tanh -> requantize -> "
+                               "W2[3072,14336], W4A4 NVFP4, bf16 out (BASELINE configs[2])",
+                   "global_batch": M, "parallelism": "single-gpu"},
+        "roofline": roofline, "kernels": kernels, "rows": rows, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+def _time_op(nv, torch, op_id, fn, iters, warm=2):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    nv.nvfp4_set_timing(True)
+    for _ in range(iters):
+        fn()
+    torch.cuda.synchronize()
+    n, ms = nv.nvfp4_timing_read(op_id)
+    nv.nvfp4_set_timing(False)
+    return ms / max(n, 1)
+
+
+def measure_rows(nv, wl, torch, np):
+    """One measurement per remaining row of the path, at the sizes of the KV and training configs."""
+    dev = "cuda"
+    res = {}
+    # --- KV cache: K [18480, 24, 128] -------------------------------------------------------
+    T, H, d = wl.KV_TOKENS, wl.KV_HEADS, wl.KV_DIM
+    kv = nv.bf16_from_bits(wl.kv_tensor(T, H, d, 3, 0), dev)
+    q = nv.NVFP4Tensor(T * H, d, dev)
+    ws = torch.empty(4096, dtype=torch.uint8, device=dev)
+    back = torch.empty_like(kv)
+    n = T * H * d
+    ms = _time_op(nv, torch, nv.OP_KV_QUANT, lambda: nv.nvfp4_kv_quant(kv, out=q, workspace=ws), 20)
+    res["kv_quant_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
+                                    "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    ms = _time_op(nv, torch, nv.OP_KV_DEQUANT, lambda: nv.nvfp4_kv_dequant(q, T, H, d, out=back), 20)
+    res["kv_dequant_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
+                                      "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    del kv, back, q
+    # --- training triplet: X[17600,3072], W[14336,3072], dY[17600,14336] ---------------------
+    c5 = wl.config5()
+    Mt, D, F = wl.TOKENS_TRAIN, wl.D_MODEL, wl.D_FFN
+    X, W, dY = (nv.bf16_from_bits(c5[k], dev) for k in ("X", "W", "dY"))
+    del c5
+
+    def qtime(x, axis, name):
+        R, C = x.shape
+        rows, K = (R, C) if axis == 0 else (C, R)
+        out = nv.NVFP4Tensor(rows, K, dev)
+        ms = _time_op(nv, torch, nv.OP_QUANTIZE, lambda: nv.nvfp4_quantize(x, block_axis=axis, out=out, workspace=ws), 10)
+        res[name] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * R * C / ms / 1e6, 1),
+                     "frac_hbm": round(B_PER_ELEM * R * C / ms / 1e6 / PEAK_HBM_GBS, 4)}
+        return out
+
+    qX = qtime(X, 0, "quantize_X_17600x3072")
+    qdY = qtime(dY, 0, "quantize_dY_17600x14336")
+    qW = qtime(W, 0, "quantize_W_14336x3072")
+    qWt = qtime(W, 1, "quantize_T_W_14336x3072")
+    qdYt = qtime(dY, 1, "quantize_T_dY_17600x14336")
+    qXt = qtime(X, 1, "quantize_T_X_17600x3072")
+    gs = torch.tensor([float(qdY.global_scale.item())], dtype=torch.float32, device=dev)
+    out = nv.NVFP4Tensor(Mt, F, dev)
+    ms = _time_op(nv, torch, nv.OP_QUANTIZE, lambda: nv.nvfp4_quantize(dY, global_scale_in=gs, out=out, workspace=ws), 10)
+    res["quantize_dY_given_scale"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * Mt * F / ms / 1e6, 1),
+                                      "frac_hbm": round(B_PER_ELEM * Mt * F / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    del out, X, dY, W
+
+    def gtime(a, w, name):
+        y = torch.empty((a.rows, w.rows), dtype=torch.float32, device=dev)
+        ms = _time_op(nv, torch, nv.OP_GEMM, lambda: nv.nvfp4_gemm(a, w, nv.OUT_F32, Y=y), 5, warm=1)
+        fl = 2.0 * a.rows * w.rows * a.K
+        res[name] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 1),
+                     "frac_mfma": round(fl / ms / 1e9 / PEAK_MFMA_F16_TFLOPS, 4)}
+
+    gtime(qX, qW, "fprop_17600x14336x3072")
+    gtime(qdY, qWt, "dgrad_17600x3072x14336")
+    gtime(qdYt, qXt, "wgrad_14336x3072x17600")
+    return res
+
+
+def cpu_baseline(cfg, wl, np):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import nvfp4_oracle as oracle
+    M, D, F = cfg["A"].shape[0], wl.D_MODEL, wl.D_FFN
+    n_rows = M           # the whole up projection: about 6 s on 16 cores
+    t0 = time.perf_counter()
+    oa = oracle.quantize(cfg["A"])
+    t1 = time.perf_counter()
+    ow = oracle.quantize(cfg["W1"])
+    rows = np.arange(n_rows, dtype=np.int64)
+    t2 = time.perf_counter()
+    oracle.gemm(oa, ow, rows=rows, want_abs=True)
+    t3 = time.perf_counter()
+    flops = 2.0 * n_rows * F * D
+    return {"value": round(flops / (t3 - t2) / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"oracle GEMM (fp64 loops incl. dequantizing W1) on rows 0..{n_rows - 1} of the up projection "
+                      f"({n_rows}x{F}x{D}), {t3 - t2:.2f} s; oracle quantize of A[{M},{D}] {t1 - t0:.2f} s = "
+                      f"{B_PER_ELEM * M * D / (t1 - t0) / 1e9:.3f} GB/s"}
+
+
+if __name__ == "__main__":
+    main()

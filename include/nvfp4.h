@@ -63,7 +63,8 @@ typedef struct nvfp4_tensor {
 
 enum { NVFP4_OUT_F32 = 0, NVFP4_OUT_BF16 = 1 };
 enum { NVFP4_ACT_NONE = 0, NVFP4_ACT_GELU_TANH = 1 };
-enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2 };
+enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2, NVFP4_OP_GEMM = 3,
+       NVFP4_OP_KV_DEQUANT = 4 };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
@@ -133,12 +134,14 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c);
 /* Static, human-readable text for a status code. */
 const char *nvfp4_status_string(int status);
 
-/* Launch durations: when enabled, every entry point brackets its kernels with
- * HIP events on the caller's stream and nvfp4_last_kernel_ms() returns the
- * duration of the most recent call's kernels (it synchronises on that call's
- * end event).  Off by default; meant for benchmarks. */
-void  nvfp4_set_timing(int enabled);
-float nvfp4_last_kernel_ms(void);
+/* Launch durations, for benchmarks.  While timing is enabled every entry point
+ * records a pair of HIP events around its kernels on the caller's stream
+ * (enabling also discards earlier records; at most 8192 calls are recorded).
+ * nvfp4_timing_read() waits for the recorded events of entry point `op`
+ * (NVFP4_OP_*) and returns how many calls were recorded and the sum of their
+ * durations in milliseconds.  Host pointers. */
+void nvfp4_set_timing(int enabled);
+int  nvfp4_timing_read(int op, int *calls, float *total_ms);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ _lib = None
 
 OUT_F32, OUT_BF16 = 0, 1
 ACT_NONE, ACT_GELU_TANH = 0, 1
-OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT = 0, 1, 2
+OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT = 0, 1, 2, 3, 4
 
 
 class _CTensor(ctypes.Structure):
@@ -55,8 +55,8 @@ def lib():
         L.nvfp4_status_string.argtypes = [c.c_int]
         L.nvfp4_set_timing.restype = None
         L.nvfp4_set_timing.argtypes = [c.c_int]
-        L.nvfp4_last_kernel_ms.restype = c.c_float
-        L.nvfp4_last_kernel_ms.argtypes = []
+        L.nvfp4_timing_read.restype = c.c_int
+        L.nvfp4_timing_read.argtypes = [c.c_int, c.POINTER(c.c_int), c.POINTER(c.c_float)]
         _lib = L
     return _lib
 
@@ -173,8 +173,11 @@ def nvfp4_set_timing(enabled):
     lib().nvfp4_set_timing(1 if enabled else 0)
 
 
-def nvfp4_last_kernel_ms():
-    return float(lib().nvfp4_last_kernel_ms())
+def nvfp4_timing_read(op):
+    """-> (calls, total_ms) recorded for entry point `op` since timing was enabled."""
+    n, ms = ctypes.c_int(0), ctypes.c_float(0)
+    _check(lib().nvfp4_timing_read(op, ctypes.byref(n), ctypes.byref(ms)))
+    return n.value, ms.value
 
 
 def bf16_from_bits(bits_np, device="cuda"):

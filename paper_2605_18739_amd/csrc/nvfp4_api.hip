@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <mutex>
+#include <vector>
 
 using namespace nvfp4;
 
@@ -22,30 +23,34 @@ int check_tensor(const nvfp4_tensor *t)
 }
 
 // ---- optional launch timing (benchmarks) -----------------------------------
+// When enabled, every entry point records a pair of HIP events around its
+// kernels on the caller's stream, tagged with its NVFP4_OP_* id.  Nothing is
+// synchronised until nvfp4_timing_read() is called.
 std::mutex g_mu;
 bool g_timing = false;
-hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
-bool g_have_interval = false;
+constexpr int kMaxRecords = 8192;
+struct Record { hipEvent_t e0, e1; int op; };
+std::vector<Record> g_pool;     // events are created once and reused
+int g_used = 0;
 
 struct Timed {
     hipStream_t s;
-    bool on;
-    explicit Timed(hipStream_t st) : s(st), on(g_timing)
+    int slot;
+    Timed(hipStream_t st, int op) : s(st), slot(-1)
     {
-        if (!on) return;
-        if (!g_ev0) {
-            if (hipEventCreate(&g_ev0) != hipSuccess || hipEventCreate(&g_ev1) != hipSuccess) {
-                on = false;
-                return;
-            }
+        if (!g_timing || g_used >= kMaxRecords) return;
+        if (g_used == (int)g_pool.size()) {
+            Record r{nullptr, nullptr, op};
+            if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
+            g_pool.push_back(r);
         }
-        (void)hipEventRecord(g_ev0, s);
+        slot = g_used++;
+        g_pool[slot].op = op;
+        (void)hipEventRecord(g_pool[slot].e0, s);
     }
     ~Timed()
     {
-        if (!on) return;
-        (void)hipEventRecord(g_ev1, s);
-        g_have_interval = true;
+        if (slot >= 0) (void)hipEventRecord(g_pool[slot].e1, s);
     }
 };
 
@@ -97,7 +102,7 @@ int nvfp4_quantize(const void *x_bf16, int64_t R, int64_t C, int64_t ld, int blo
                    size_t workspace_bytes, void *stream)
 {
     std::lock_guard<std::mutex> lk(g_mu);
-    Timed t(static_cast<hipStream_t>(stream));
+    Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_QUANTIZE);
     int rc = quantize_impl(x_bf16, R, C, ld, block_axis, global_scale_in, out, workspace, workspace_bytes,
                            static_cast<hipStream_t>(stream));
     return rc;
@@ -108,7 +113,7 @@ int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_t
 {
     if (T <= 0 || H <= 0 || d <= 0) return NVFP4_ERR_SHAPE;
     std::lock_guard<std::mutex> lk(g_mu);
-    Timed t(static_cast<hipStream_t>(stream));
+    Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_KV_QUANT);
     return quantize_impl(kv_bf16, T * H, d, d, 0, nullptr, out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(stream));
 }
@@ -121,7 +126,7 @@ int nvfp4_kv_dequant(const nvfp4_tensor *in, void *kv_bf16_out, int64_t T, int64
     if (T <= 0 || H <= 0 || d <= 0 || in->rows != T * H || in->K != d) return NVFP4_ERR_SHAPE;
     if (!aligned16(kv_bf16_out)) return NVFP4_ERR_ALIGN;
     std::lock_guard<std::mutex> lk(g_mu);
-    Timed t(static_cast<hipStream_t>(stream));
+    Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_KV_DEQUANT);
     hipError_t e = launch_dequant_bf16(in->codes, in->scales, in->global_scale, in->rows, in->K,
                                        static_cast<uint16_t *>(kv_bf16_out), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
@@ -136,7 +141,7 @@ int nvfp4_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y, int64_t ld
     if (ldy < W->rows) return NVFP4_ERR_SHAPE;
     if (!aligned16(Y) || (ldy & 3) != 0) return NVFP4_ERR_ALIGN;
     std::lock_guard<std::mutex> lk(g_mu);
-    Timed t(static_cast<hipStream_t>(stream));
+    Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_GEMM);
     GemmEpilogue ep{};
     ep.out_dtype = out_dtype;
     ep.act = NVFP4_ACT_NONE;
@@ -163,7 +168,7 @@ int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
 
     std::lock_guard<std::mutex> lk(g_mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    Timed t(s);
+    Timed t(s, NVFP4_OP_GEMM_ACT_QUANT);
     // workspace: [partials][H if not supplied]
     uint32_t *partial = static_cast<uint32_t *>(workspace);
     const size_t part_bytes = align_up((size_t)std::max(kMaxPartials, gemm_workgroups(M, N)) * 4, 256);
@@ -221,17 +226,25 @@ void nvfp4_set_timing(int enabled)
 {
     std::lock_guard<std::mutex> lk(g_mu);
     g_timing = enabled != 0;
-    g_have_interval = false;
+    g_used = 0;
 }
 
-float nvfp4_last_kernel_ms(void)
+int nvfp4_timing_read(int op, int *calls, float *total_ms)
 {
     std::lock_guard<std::mutex> lk(g_mu);
-    if (!g_have_interval) return -1.0f;
-    float ms = -1.0f;
-    if (hipEventSynchronize(g_ev1) != hipSuccess) return -1.0f;
-    if (hipEventElapsedTime(&ms, g_ev0, g_ev1) != hipSuccess) return -1.0f;
-    return ms;
+    int n = 0;
+    float sum = 0.0f;
+    for (int i = 0; i < g_used; ++i) {
+        if (g_pool[i].op != op) continue;
+        float ms = 0.0f;
+        if (hipEventSynchronize(g_pool[i].e1) != hipSuccess) return NVFP4_ERR_LAUNCH;
+        if (hipEventElapsedTime(&ms, g_pool[i].e0, g_pool[i].e1) != hipSuccess) return NVFP4_ERR_LAUNCH;
+        sum += ms;
+        ++n;
+    }
+    if (calls) *calls = n;
+    if (total_ms) *total_ms = sum;
+    return NVFP4_OK;
 }
 
 }  // extern "C"
