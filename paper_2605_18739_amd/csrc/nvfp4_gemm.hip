@@ -4,18 +4,40 @@
 // Route: every code*block_scale product (<= 6 significant bits, magnitude in
 // [2^-10, 2688]) is an exact f16 number, and f16*f16 products are exact in the
 // FP32 accumulator of v_mfma_f32_32x32x16_f16, so the only rounding left is the
-// FP32 accumulation.  Packed codes travel HBM -> registers (128-bit loads),
-// are expanded once per workgroup with v_cvt_scalef32_pk_f16_fp4 (two codes per
-// instruction) and one packed f16 multiply by the block scale, and are staged
-// in LDS as f16 in an XOR-swizzled layout that both the 128-bit writes and the
-// 128-bit MFMA fragment reads hit without bank conflicts.
+// FP32 accumulation.  Packed codes travel HBM -> registers (128-bit buffer
+// loads, out-of-range rows read as zero), are expanded once per workgroup with
+// v_cvt_scalef32_pk_f16_fp4 (two codes per instruction) and one packed f16
+// multiply by the block scale (v_cvt_scalef32_pk_f16_fp8 turns the E4M3 byte
+// into f16), and are staged in LDS as f16 in an XOR-swizzled layout that both
+// the 128-bit writes and the 128-bit MFMA fragment reads hit without bank
+// conflicts.
 //
 // Orientation: the MFMA's row operand is the W fragment and its column operand
 // the A fragment, so a lane ends up with ONE output row m and runs of four
-// consecutive n -- 16-byte stores, and the fused quantizer of the epilogue finds
-// half of every 16-element block inside a lane.
+// consecutive n.  The epilogue transposes 32-row slabs through LDS so that
+// global stores are 16 bytes per lane and whole rows of the tile are contiguous.
 #include "nvfp4_device.h"
 #include "nvfp4_kernels.h"
+
+#include <type_traits>
+
+#ifndef NVFP4_SCHED
+#define NVFP4_SCHED 2     // VALU instructions requested after every MFMA of the main loop
+#endif
+#ifndef NVFP4_EXPERIMENT
+#define NVFP4_EXPERIMENT 0   // timing experiments only: bit 0 no refetch, 1 no staging, 2 no fragment reads, 3 no barrier
+#endif
+
+// Empty inline-asm statements that tie values (or memory) to a point of the
+// instruction stream; register constraints only exist in the device pass.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define NVFP4_PIN1(a) asm volatile("" : "+v"(a))
+#define NVFP4_PIN2(a, b) asm volatile("" : "+v"(a), "+v"(b))
+#else
+#define NVFP4_PIN1(a) ((void)(a))
+#define NVFP4_PIN2(a, b) ((void)(a), (void)(b))
+#endif
+#define NVFP4_COMPILER_FENCE() asm volatile("" ::: "memory")
 
 namespace nvfp4 {
 
@@ -47,92 +69,456 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-// One 16-byte chunk of codes (32 elements = 2 blocks) -> four 16-byte f16 chunks.
-__device__ __forceinline__ void expand_chunk(const uint4v &c, uint32_t scale2, half8v (&out)[4])
+// Eight codes (one dword, all inside one 16-element block) times the block
+// scale -> eight f16: four conversions (two codes each) and four packed multiplies.
+__device__ __forceinline__ half8v expand_dword(uint32_t w, half2v p)
 {
-    _Float16 s0 = e4m3_to_f16(scale2 & 0x7Fu), s1 = e4m3_to_f16((scale2 >> 8) & 0x7Fu);
-    half2v p0 = {s0, s0}, p1 = {s1, s1};
-#define NVFP4_EXPAND(I, W, P)                                                        \
-    {                                                                                \
-        half2v a = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(W, 1.0f, 0) * P;         \
-        half2v b = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(W, 1.0f, 1) * P;         \
-        half2v cc = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(W, 1.0f, 2) * P;        \
-        half2v d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(W, 1.0f, 3) * P;         \
-        out[I] = half8v{a.x, a.y, b.x, b.y, cc.x, cc.y, d.x, d.y};                   \
-    }
-    NVFP4_EXPAND(0, c.x, p0) NVFP4_EXPAND(1, c.y, p0) NVFP4_EXPAND(2, c.z, p1) NVFP4_EXPAND(3, c.w, p1)
-#undef NVFP4_EXPAND
+    half2v a = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 0) * p;
+    half2v b = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 1) * p;
+    half2v c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2) * p;
+    half2v d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 3) * p;
+    return half8v{a.x, a.y, b.x, b.y, c.x, c.y, d.x, d.y};
 }
 
-// byte offset of 16-byte chunk `c` (0..7) of staged row `row`
-__device__ __forceinline__ int lds_chunk_off(int row, int c) { return row * ROW_BYTES + ((c ^ (row & 7)) << 4); }
+// 3-bit swizzle key of a row: distinct over every 8 consecutive rows and,
+// combined with the row parity, over every 16.  LDS reads are served 16 lanes at
+// a time out of 64 banks (256 B), writes 8 lanes at a time out of 128 B; with
+// rows of 128 B (or a multiple) XOR-ing the 16-byte chunk index with this key
+// makes "many rows, same chunk" accesses conflict free in both directions.
+__device__ __forceinline__ int swz_key(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void gemm_f16mfma_kernel(GemmArgs g)
+// byte offset of 16-byte chunk `c` (0..7) of staged row `row`
+__device__ __forceinline__ int lds_chunk_off(int row, int c) { return row * ROW_BYTES + ((c ^ swz_key(row)) << 4); }
+
+// Epilogue shared by the tiled kernels.  Each wave transposes its accumulators
+// through a private 16 KB slab of LDS, 32 output rows at a time: a lane owns (row
+// m, four consecutive n) after the MFMA, and (row m, 16 consecutive bytes) when
+// it stores, so whole rows of the wave tile leave as contiguous runs.
+template <int TM, int TN, bool OUT_BF16>
+__device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const GemmArgs &g, uint8_t *lds,
+                                              int64_t wave_m0, int64_t wave_n0)
+{
+    constexpr int WN = TN * 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    __syncthreads();                              // all fragment reads of the main loop are done
+    const float alpha = (*g.gsA) * (*g.gsW);
+    const GemmEpilogue &ep = g.ep;
+    uint8_t *slab = lds + wave * 16384;
+    uint32_t hmax = 0;                            // largest |bf16(H)| pattern seen by this lane
+    const int key = swz_key(lrow);
+    auto epilogue_slab = [&](auto j_c) {
+        constexpr int j = decltype(j_c)::value;
+        if constexpr (!OUT_BF16) {
+            // fp32: slab row = WN * 4 bytes, granule = 4 floats
+            constexpr int ROWB = WN * 4, GPR = WN / 4;       // granules per row
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    float4v o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float y = acc[i][j][rg * 4 + e] * alpha;
+                        if (ep.act == 1) y = gelu_tanh_f32(y);
+                        o[e] = y;
+                    }
+                    const int gi = 8 * i + 2 * rg + lhalf;
+                    *(float4v *)(slab + lrow * ROWB + ((gi ^ key) << 4)) = o;
+                }
+            // read back: lanes sweep granules of a row, then the next row
+#pragma unroll
+            for (int p = 0; p < 32 * GPR / 64; ++p) {
+                const int idx = p * 64 + lane, r = idx / GPR, gi = idx % GPR;
+                float4v o = *(const float4v *)(slab + r * ROWB + ((gi ^ swz_key(r)) << 4));
+                const int64_t m = wave_m0 + j * 32 + r, n = wave_n0 + gi * 4;
+                if (m < g.M && n < g.N) *(float4v *)((float *)ep.Y + m * ep.ldy + n) = o;
+            }
+        } else {
+            // bf16: slab row = WN * 2 bytes, granule = 8 bf16; lane halves trade their
+            // four-element runs so that every lane holds eight consecutive n
+            constexpr int ROWB = WN * 2, GPR = WN / 8;
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int rp = 0; rp < 2; ++rp) {
+                    uint32_t pk[2][2];
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        float y[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            y[e] = acc[i][j][(2 * rp + s) * 4 + e] * alpha;
+                            if (ep.act == 1) y[e] = gelu_tanh_f32(y[e]);
+                        }
+                        pk[s][0] = f32_to_bf16_rne(y[0]) | (f32_to_bf16_rne(y[1]) << 16);
+                        pk[s][1] = f32_to_bf16_rne(y[2]) | (f32_to_bf16_rne(y[3]) << 16);
+                    }
+                    // lower half keeps run s=0 and receives the upper half's s=0; upper half
+                    // keeps s=1 and receives the lower half's s=1
+                    auto x0 = __builtin_amdgcn_permlane32_swap(pk[0][0], pk[1][0], false, false);
+                    auto x1 = __builtin_amdgcn_permlane32_swap(pk[0][1], pk[1][1], false, false);
+                    uint4v o = {x0[0], x1[0], x0[1], x1[1]};
+                    const int gi = 4 * i + 2 * rp + lhalf;
+                    *(uint4v *)(slab + lrow * ROWB + ((gi ^ key) << 4)) = o;
+                }
+#pragma unroll
+            for (int p = 0; p < 32 * GPR / 64; ++p) {
+                const int idx = p * 64 + lane, r = idx / GPR, gi = idx % GPR;
+                uint4v o = *(const uint4v *)(slab + r * ROWB + ((gi ^ swz_key(r)) << 4));
+                const int64_t m = wave_m0 + j * 32 + r, n = wave_n0 + gi * 8;
+                if (m < g.M && n < g.N) {
+                    if (ep.amax_partial) {
+                        hmax = pk_absmax_u16(hmax, o.x);
+                        hmax = pk_absmax_u16(hmax, o.y);
+                        hmax = pk_absmax_u16(hmax, o.z);
+                        hmax = pk_absmax_u16(hmax, o.w);
+                    }
+                    *(uint4v *)((uint16_t *)ep.Y + m * ep.ldy + n) = o;
+                }
+            }
+        }
+    };
+    epilogue_slab(std::integral_constant<int, 0>{});
+    if constexpr (TM > 1) epilogue_slab(std::integral_constant<int, 1>{});
+    if constexpr (TM > 2) epilogue_slab(std::integral_constant<int, 2>{});
+    if constexpr (TM > 3) epilogue_slab(std::integral_constant<int, 3>{});
+    if (ep.amax_partial) {
+        uint32_t mx = wave_max_u32(pk_hmax_u16(hmax));
+        __syncthreads();                          // slabs are no longer needed
+        uint32_t *wmax = (uint32_t *)lds;
+        if (lane == 0) wmax[wave] = mx;
+        __syncthreads();
+        if (tid == 0)
+            ep.amax_partial[blockIdx.y * gridDim.x + blockIdx.x] = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+    }
+}
+
+// staging half-units (x = 0 .. NH-1) handled in MFMA phase kk: phases 0, 1, 2 share them
+__host__ __device__ constexpr int phase_of_half_unit(int x, int NH) { return x * 3 / NH; }
+__host__ __device__ constexpr int half_units_in_phase(int NH, int kk)
+{
+    int n = 0;
+    for (int x = 0; x < NH; ++x) n += phase_of_half_unit(x, NH) == kk;
+    return n;
+}
+
+// Scheduling request for one phase: NM MFMAs, each followed by its share of NV VALU
+// and ND LDS instructions.
+template <int NV, int ND, int NM, int T = 0>
+__device__ __forceinline__ void sched_phase()
+{
+    if constexpr (T < NM) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        constexpr int v = NV * (T + 1) / NM - NV * T / NM, d = ND * (T + 1) / NM - ND * T / NM;
+        if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x002, v, 0);
+        if constexpr (d > 0) __builtin_amdgcn_sched_group_barrier(0x080, d, 0);
+        sched_phase<NV, ND, NM, T + 1>();
+    }
+}
+
+template <int BM, int BN, bool OUT_BF16>
+__global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
 {
     constexpr int WM = BM / 2, WN = BN / 2;        // per-wave tile (2 x 2 waves)
     constexpr int TM = WM / 32, TN = WN / 32;      // 32x32 MFMA tiles per wave
-    constexpr int CA = BM * 2 / 256, CW = BN * 2 / 256;   // 16-byte code chunks per thread and step
-    constexpr int STAGE = (BM + BN) * ROW_BYTES;
+    constexpr int CA = BM / 128, CW = BN / 128;    // staging units (16 B of codes) per thread and step
+    constexpr int NU = CA + CW;
+    constexpr int A_BYTES = BM * ROW_BYTES, W_BYTES = BN * ROW_BYTES;
+    constexpr int W_BASE = 2 * A_BYTES;            // LDS: [A buf0][A buf1][W buf0][W buf1]
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
     const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
-    const int64_t kbytes = g.K >> 1, kblocks = g.K >> 4;
+    const int kbytes = (int)(g.K >> 1), kblocks = (int)(g.K >> 4);
     const int KT = (int)(g.K / BK);
 
-    // staging assignment: chunk q of this thread covers row (tid + 256 q) / 2, half (tid & 1)
-    const uint8_t *pa[CA], *psa[CA], *pw[CW], *psw[CW];
-    int la[CA], lw[CW];
-#pragma unroll
-    for (int q = 0; q < CA; ++q) {
-        int row = (tid + 256 * q) >> 1, h = tid & 1;
-        int64_t gr = min(m0 + row, g.M - 1);
-        pa[q] = g.codesA + gr * kbytes + h * 16;
-        psa[q] = g.scalesA + gr * kblocks + h * 2;
-        la[q] = row;
-    }
-#pragma unroll
-    for (int q = 0; q < CW; ++q) {
-        int row = (tid + 256 * q) >> 1, h = tid & 1;
-        int64_t gr = min(n0 + row, g.N - 1);
-        pw[q] = g.codesW + gr * kbytes + h * 16;
-        psw[q] = g.scalesW + gr * kblocks + h * 2;
-        lw[q] = row;
-    }
-    const int hsel = tid & 1;
+    // buffer resources: rows past the end of an operand read as zero codes
+    const __amdgpu_buffer_rsrc_t rcA = __builtin_amdgcn_make_buffer_rsrc((void *)g.codesA, 0, (int)(g.M * kbytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesA, 0, (int)(g.M * kblocks), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rcW = __builtin_amdgcn_make_buffer_rsrc((void *)g.codesW, 0, (int)(g.N * kbytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesW, 0, (int)(g.N * kblocks), 0x00020000);
 
-    uint4v ra[CA], rw[CW];
-    uint32_t sa[CA], sw[CW];
-    auto load_step = [&](int kt) {
+    // staging: unit u of this thread covers row (tid >> 1) + 128 u', half-row (tid & 1);
+    // units 0..CA-1 belong to A, CA..NU-1 to W
+    const int srow = tid >> 1, hsel = tid & 1;
+    int vc[NU], vs[NU];
 #pragma unroll
-        for (int q = 0; q < CA; ++q) {
-            ra[q] = *(const uint4v *)(pa[q] + (int64_t)kt * 32);
-            sa[q] = *(const uint16_t *)(psa[q] + (int64_t)kt * 4);
-        }
+    for (int u = 0; u < NU; ++u) {
+        const int64_t gr = (u < CA ? m0 : n0) + srow + 128 * (u < CA ? u : u - CA);
+        const int64_t lim = u < CA ? g.M : g.N;
+        // an out-of-range row gets an offset past the end of the buffer (reads zero)
+        vc[u] = gr < lim ? (int)(gr * kbytes) + hsel * 16 : 0x7FFFFFF0;
+        vs[u] = gr < lim ? (int)(gr * kblocks) + hsel * 2 : 0x7FFFFFF0;
+    }
+    int st_a[4], st_w[4];          // LDS byte offsets of this thread's four chunks of a staged row
 #pragma unroll
-        for (int q = 0; q < CW; ++q) {
-            rw[q] = *(const uint4v *)(pw[q] + (int64_t)kt * 32);
-            sw[q] = *(const uint16_t *)(psw[q] + (int64_t)kt * 4);
+    for (int i = 0; i < 4; ++i) {
+        st_a[i] = lds_chunk_off(srow, 4 * hsel + i);
+        st_w[i] = st_a[i] + W_BASE;
+    }
+    int fr_a[4], fr_w[4];          // LDS byte offsets of this lane's fragment in phase kk
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        fr_a[kk] = lds_chunk_off(lrow, 2 * kk + lhalf) + wm * WM * ROW_BYTES;
+        fr_w[kk] = lds_chunk_off(lrow, 2 * kk + lhalf) + W_BASE + wn * WN * ROW_BYTES;
+    }
+
+    uint4v rc[NU];
+    uint32_t rs[NU];
+    auto load_unit = [&](int u, int kt) {
+        kt = min(kt, KT - 1);                      // never read past the last K step of a row
+        rc[u] = __builtin_amdgcn_raw_buffer_load_b128(u < CA ? rcA : rcW, vc[u], kt * 32, 0);
+        rs[u] = __builtin_amdgcn_raw_buffer_load_b16(u < CA ? rsA : rsW, vs[u], kt * 4, 0);
+    };
+    // half h of unit u: 16 codes = one block -> two 16-byte f16 chunks
+    auto stage_half = [&](int u, int h, int buf) {
+        const int imm = u < CA ? buf * A_BYTES + u * 128 * ROW_BYTES : buf * W_BYTES + (u - CA) * 128 * ROW_BYTES;
+        const int *st = u < CA ? st_a : st_w;
+        half2v sc = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rs[u], 1.0f, false);   // both E4M3 scales -> f16
+        half2v p = h ? half2v{sc.y, sc.y} : half2v{sc.x, sc.x};
+        *(half8v *)(lds + st[2 * h] + imm) = expand_dword(rc[u][2 * h], p);
+        *(half8v *)(lds + st[2 * h + 1] + imm) = expand_dword(rc[u][2 * h + 1], p);
+    };
+
+    float16v acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    half8v fa[2][TM], fw[2][TN];
+    auto read_frags = [&](int buf, int kk, int slot) {
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+            fa[slot][j] = *(const half8v *)(lds + fr_a[kk] + buf * A_BYTES + j * 32 * ROW_BYTES);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+            fw[slot][i] = *(const half8v *)(lds + fr_w[kk] + buf * W_BYTES + i * 32 * ROW_BYTES);
+    };
+    auto mfma_range = [&](int kk, int lo, int hi) {
+#pragma unroll
+        for (int t = lo; t < hi; ++t) {
+            const int i = t / TM, j = t % TM;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[kk & 1][i], fa[kk & 1][j], acc[i][j], 0, 0, 0);
         }
     };
-    auto stage_step = [&](int buf) {
-        uint8_t *base = lds + buf * STAGE;
+
+    // prologue: step 0 staged, step 1 in registers, fragments of (step 0, phase 0) in flight
 #pragma unroll
-        for (int q = 0; q < CA; ++q) {
-            half8v e[4];
-            expand_chunk(ra[q], sa[q], e);
+    for (int u = 0; u < NU; ++u) load_unit(u, 0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) *(half8v *)(base + lds_chunk_off(la[q], 4 * hsel + i)) = e[i];
+    for (int u = 0; u < NU; ++u) {
+        stage_half(u, 0, 0);
+        stage_half(u, 1, 0);
+    }
+    if (KT > 1) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) load_unit(u, 1);
+    }
+    __syncthreads();
+    read_frags(0, 0, 0);
+
+    // Iteration kt multiplies out of LDS buffer kt&1 in four 16-wide MFMA phases.
+    // Meanwhile the codes of step kt+1 (already in registers) are expanded into the
+    // other buffer during phases 0..2 and the codes of step kt+2 are fetched.  Every
+    // fragment of the current buffer has been read by the end of phase 2, so the
+    // single barrier sits in the middle of phase 3: after it the other buffer is
+    // complete, its first fragments are requested, and the remaining MFMAs of
+    // phase 3 cover that LDS latency.
+    auto iteration = [&](int kt, auto buf_c, auto stage_next, auto load_next2) {
+        constexpr int buf = decltype(buf_c)::value;
+        constexpr bool kStage = decltype(stage_next)::value, kLoad = decltype(load_next2)::value;
+        constexpr int NH = 2 * NU;                  // half-units to stage
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+#if !(NVFP4_EXPERIMENT & 4)
+            if (kk < 3) read_frags(buf, kk + 1, (kk + 1) & 1);
+#endif
+            if (kStage) {
+#pragma unroll
+                for (int x = 0; x < NH; ++x) {
+                    if (phase_of_half_unit(x, NH) == kk) {
+#if !(NVFP4_EXPERIMENT & 2)
+                        stage_half(x >> 1, x & 1, buf ^ 1);
+#endif
+#if !(NVFP4_EXPERIMENT & 1)
+                        if (kLoad && (x & 1)) load_unit(x >> 1, kt + 2);
+#endif
+                    }
+                }
+            }
+            if (kk < 3) {
+                mfma_range(kk, 0, TN * TM);
+            } else {
+                mfma_range(kk, 0, TN * TM / 2);
+#if !(NVFP4_EXPERIMENT & 8)
+                __syncthreads();
+#endif
+#if !(NVFP4_EXPERIMENT & 4)
+                if (kStage) read_frags(buf ^ 1, 0, 0);
+#endif
+                mfma_range(kk, TN * TM / 2, TN * TM);
+            }
         }
+#if NVFP4_SCHED
+        // Ask the scheduler for a steady interleave.  Phase kk holds 16 MFMAs, the
+        // eight fragment reads of the next phase, and hu half-units of staging (about
+        // 18 VALU and two LDS writes each, plus a pair of buffer loads per unit); they
+        // are dealt out evenly behind the MFMAs.
+        if constexpr (kStage) {
+            sched_phase<half_units_in_phase(NH, 0) * 18, 8 + 2 * half_units_in_phase(NH, 0), TN * TM>();
+            sched_phase<half_units_in_phase(NH, 1) * 18, 8 + 2 * half_units_in_phase(NH, 1), TN * TM>();
+            sched_phase<half_units_in_phase(NH, 2) * 18, 8 + 2 * half_units_in_phase(NH, 2), TN * TM>();
+        }
+#endif
+    };
+    {
+        // Every iteration stages "the next step" and fetches "the one after"; past the
+        // end of K the fetch is clamped to the last step, and what gets staged from it
+        // is never multiplied.
+        using T = std::true_type;
+        using B0 = std::integral_constant<int, 0>;
+        using B1 = std::integral_constant<int, 1>;
+        int kt = 0;
+        for (; kt + 1 < KT; kt += 2) {          // two steps per trip so the buffer index is a constant
+            iteration(kt, B0{}, T{}, T{});
+            iteration(kt + 1, B1{}, T{}, T{});
+        }
+        if (kt < KT) iteration(kt, B0{}, T{}, T{});
+    }
+
+    gemm_epilogue<TM, TN, OUT_BF16>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
+}
+
+// ============================================================================
+// Register-dequantizing kernel (the fast path for large tiles).
+//
+// The operands stay 4-bit all the way into LDS: every K step of 64 the packed
+// codes of the tile (32 B per row) are copied HBM -> LDS by buffer loads that
+// write LDS directly (no registers, no VALU, no LDS-write instructions), and
+// the E4M3 scales follow every fourth step (16 B per row cover 256 k).  A wave
+// reads its own rows' codes back with one 128-bit LDS read per 32-row tile and
+// step, and expands them in registers right before the MFMAs that consume them:
+// one v_cvt_scalef32_pk_f16_fp4 and one v_pk_mul_f16 per pair of elements.  On
+// this machine VALU instructions issue in the shadow of a running MFMA while
+// LDS instructions largely do not, so trading LDS traffic (4x fewer bytes, 4x
+// fewer instructions than staging f16) for VALU work (each operand element is
+// expanded by the two waves that use it) is what keeps the matrix pipe busy.
+//
+// K order inside a step: lane half h (lanes 32h..32h+31) of an MFMA operand owns
+// codes k = 32h .. 32h+31 of the step, and MFMA sub-step j (0..3) multiplies
+// codes 32h + 8j .. 32h + 8j + 7 -- a permutation of k applied to both operands
+// alike.  Those eight codes sit in dword j of the lane's 16-byte chunk and share
+// block scale 2h + j/2.
+// ============================================================================
+constexpr int kStages = 3;             // LDS ring of code stages (all copy targets stay below 64 KB)
+constexpr int kScaleGroup = 4;         // K steps covered by one 16-byte run of scales
+
+// s_waitcnt vmcnt(N) alone: vmcnt sits in bits 3:0 and 15:14, expcnt (6:4) and
+// lgkmcnt (11:8) are left at "do not wait".
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_le()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
+}
+
+template <int BM, int BN, bool OUT_BF16>
+__global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
+{
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
+    constexpr int WM = BM / 2, WN = BN / 2;        // per-wave tile (2 x 2 waves)
+    constexpr int TM = WM / 32, TN = WN / 32;      // 32x32 MFMA tiles per wave
+    constexpr int NF = TM + TN;                    // operand fragments per MFMA sub-step
+    constexpr int NMF = TM * TN;                   // MFMAs per sub-step
+    constexpr int ROWS = BM + BN;                  // staged rows: A rows first, then W rows
+    constexpr int CODE_STAGE = ROWS * 32;          // [2 chunks][ROWS][16 B]
+    constexpr int SCALE_STAGE = ROWS * 16;         // [ROWS][16 B]
+    constexpr int SCALE_BASE = kStages * CODE_STAGE;
+    constexpr int UNITS = ROWS * 2 / 64;           // 1 KB copy instructions per code stage
+    constexpr int UPW = UNITS / 4;                 // ... per wave
+    constexpr int SUNITS = ROWS / 64, SUPW = SUNITS / 4;
+    static_assert(UNITS % 4 == 0 && SUNITS % 4 == 0 && BM % 64 == 0 && BN % 64 == 0, "tile shape");
+    static_assert(2 * NF == NMF || true, "");
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: it selects LDS targets of the copies
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    const int kbytes = (int)(g.K >> 1), kblocks = (int)(g.K >> 4);
+    const int KT = (int)(g.K / BK);
+
+    const __amdgpu_buffer_rsrc_t rcA = __builtin_amdgcn_make_buffer_rsrc((void *)g.codesA, 0, (int)(g.M * kbytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesA, 0, (int)(g.M * kblocks), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rcW = __builtin_amdgcn_make_buffer_rsrc((void *)g.codesW, 0, (int)(g.N * kbytes), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesW, 0, (int)(g.N * kblocks), 0x00020000);
+
+    // ---- copy units.  Code unit q (0 .. UNITS-1) is 64 consecutive staged rows of
+    // one 16-byte chunk: q = chunk * (ROWS/64) + row group; lane l copies row
+    // 64*group + l.  Wave w issues units w*UPW .. w*UPW+UPW-1.  A row past the end of
+    // its operand gets an offset beyond the buffer and is filled with zeros.
+    int cvoff[UPW], svoff[SUPW];
 #pragma unroll
-        for (int q = 0; q < CW; ++q) {
-            half8v e[4];
-            expand_chunk(rw[q], sw[q], e);
+    for (int x = 0; x < UPW; ++x) {
+        const int q = wave * UPW + x, chunk = q / (ROWS / 64), srow = (q % (ROWS / 64)) * 64 + lane;
+        const bool isA = srow < BM;
+        const int64_t gr = isA ? m0 + srow : n0 + (srow - BM);
+        cvoff[x] = gr < (isA ? g.M : g.N) ? (int)(gr * kbytes) + chunk * 16 : 0x7FFFFFF0;
+    }
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                *(half8v *)(base + BM * ROW_BYTES + lds_chunk_off(lw[q], 4 * hsel + i)) = e[i];
+    for (int x = 0; x < SUPW; ++x) {
+        const int srow = (wave * SUPW + x) * 64 + lane;
+        const bool isA = srow < BM;
+        const int64_t gr = isA ? m0 + srow : n0 + (srow - BM);
+        svoff[x] = gr < (isA ? g.M : g.N) ? (int)(gr * kblocks) : 0x7FFFFFF0;
+    }
+    auto copy_codes = [&](int kt, int stage) {      // K step kt -> ring stage `stage` (= kt % kStages)
+#pragma unroll
+        for (int x = 0; x < UPW; ++x) {
+            const int q = wave * UPW + x;
+            const bool isA = (q % (ROWS / 64)) * 64 < BM;
+            uint8_t *dst = lds + stage * CODE_STAGE + q * 1024;
+            if (isA) __builtin_amdgcn_raw_ptr_buffer_load_lds(rcA, (lds_ptr_t)dst, 16, cvoff[x], kt * 32, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rcW, (lds_ptr_t)dst, 16, cvoff[x], kt * 32, 0, 0);
+        }
+    };
+    auto copy_scales = [&](int grp) {               // scale group grp (steps 4 grp .. 4 grp + 3) -> stage grp & 1
+#pragma unroll
+        for (int x = 0; x < SUPW; ++x) {
+            const int u = wave * SUPW + x;
+            const bool isA = u * 64 < BM;
+            uint8_t *dst = lds + SCALE_BASE + (grp & 1) * SCALE_STAGE + u * 1024;
+            if (isA) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)dst, 16, svoff[x], grp * 16, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsW, (lds_ptr_t)dst, 16, svoff[x], grp * 16, 0, 0);
+        }
+    };
+
+    // ---- what this lane reads back: fragment f (0..TM-1: A tiles, TM..NF-1: W tiles)
+    // is staged row frow[f]; its codes are chunk lhalf of that row.
+    int code_off[NF], scale_off[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        const int srow = f < TM ? wm * WM + f * 32 + lrow : BM + wn * WN + (f - TM) * 32 + lrow;
+        code_off[f] = (lhalf * ROWS + srow) * 16;
+        scale_off[f] = SCALE_BASE + srow * 16 + 2 * lhalf;
+    }
+    uint4v codes[2][NF];          // packed codes of the step being multiplied / the next one
+    uint32_t scl[2][NF];          // their two block scales (E4M3 bytes) ...
+    uint32_t scf[2][NF];          // ... and the same as a pair of f16
+    auto read_step = [&](int kt, int stage, int set) {
+        const int sbase = ((kt / kScaleGroup) & 1) * SCALE_STAGE + (kt & (kScaleGroup - 1)) * 4;
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            codes[set][f] = *(const uint4v *)(lds + stage * CODE_STAGE + code_off[f]);
+            scl[set][f] = *(const uint16_t *)(lds + sbase + scale_off[f]);
         }
     };
 
@@ -144,82 +530,113 @@ __global__ __launch_bounds__(256) void gemm_f16mfma_kernel(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    load_step(0);
-    stage_step(0);
-    __syncthreads();
+    // fragments of MFMA sub-step j live in frag[j & 1]; order: A tiles then W tiles
+    uint4v frag[2][NF];
+    // piece pc (0 .. 2 NF - 1) of sub-step j of register set `set`: half a fragment
+    auto expand_piece = [&](int set, int j, int pc) {
+        const int f = pc >> 1, hp = pc & 1;
+        const half2v sc = __builtin_bit_cast(half2v, scf[set][f]);
+        half2v p = (j >> 1) ? half2v{sc.y, sc.y} : half2v{sc.x, sc.x};
+        const uint32_t w = codes[set][f][j];
+        const int d0 = 2 * hp, d1 = 2 * hp + 1;
+        half2v e0 = hp ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2) : __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 0);
+        half2v e1 = hp ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 3) : __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 1);
+        uint32_t x0 = __builtin_bit_cast(uint32_t, e0 * p), x1 = __builtin_bit_cast(uint32_t, e1 * p);
+        // keep the expansion where it is written: without this the optimizer sinks it
+        // towards its use, out of the shadow of the MFMAs it is meant to hide behind
+        NVFP4_PIN2(x0, x1);
+        frag[j & 1][f][d0] = x0;
+        frag[j & 1][f][d1] = x1;
+    };
 
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) load_step(kt + 1);
-        const uint8_t *a_base = lds + buf * STAGE;
-        const uint8_t *w_base = a_base + BM * ROW_BYTES;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int c = 2 * kk + lhalf;
-            half8v fa[TM], fw[TN];
-#pragma unroll
-            for (int j = 0; j < TM; ++j) fa[j] = *(const half8v *)(a_base + lds_chunk_off(wm * WM + j * 32 + lrow, c));
-#pragma unroll
-            for (int i = 0; i < TN; ++i) fw[i] = *(const half8v *)(w_base + lds_chunk_off(wn * WN + i * 32 + lrow, c));
-#pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[i], fa[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < KT) stage_step(buf ^ 1);
-        __syncthreads();
-    }
+    auto convert_scales = [&](int set, int f) {     // E4M3 pair -> f16 pair, pinned where it is written
+        uint32_t raw = scl[set][f];
+        NVFP4_PIN1(raw);               // do not start before this point (the LDS read may still be in flight)
+        uint32_t x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(raw, 1.0f, false));
+        NVFP4_PIN1(x);
+        scf[set][f] = x;
+    };
 
-    // ---------------------------------------------------------------- epilogue
-    const float alpha = (*g.gsA) * (*g.gsW);
-    const GemmEpilogue &ep = g.ep;
-    uint32_t hmax = 0;      // largest |bf16(H)| pattern seen by this lane
+    // ---- prologue: steps 0 .. kStages-1 in flight, step 0 in registers and expanded.
+    // Copies never reach past the last K step: a step index is clamped to KT-1 (the
+    // clamped copy lands in a stage nobody multiplies from).
+    const int last_kt = KT - 1, last_grp = last_kt / kScaleGroup;
+    copy_scales(0);
 #pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        const int64_t m = m0 + wm * WM + j * 32 + lrow;
+    for (int s = 0; s < kStages; ++s) copy_codes(min(s, last_kt), s);
+    wait_vmcnt_le<(kStages - 1) * UPW>();          // step 0 (and the scales before it) has landed
+    NVFP4_COMPILER_FENCE();
+    __builtin_amdgcn_s_barrier();
+    NVFP4_COMPILER_FENCE();
+    read_step(0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < TN; ++i) {
+    for (int f = 0; f < NF; ++f) convert_scales(0, f);
 #pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                const int64_t n = n0 + wn * WN + i * 32 + rg * 8 + lhalf * 4;
-                float y[4];
+    for (int pc = 0; pc < 2 * NF; ++pc) expand_piece(0, 0, pc);
+
+    // ---- main loop.  Iteration kt: wait for the copies of step kt+1 (issued two
+    // iterations ago; only the newest batch may still be in flight), barrier, read
+    // step kt+1 into the other register set, start the copies of step kt+kStages into
+    // the stage step kt occupied (every wave finished reading it before the barrier),
+    // then four sub-steps of NMF MFMAs, each interleaved with the expansion of the
+    // next sub-step's fragments.
+    int stage_next = 1 % kStages;                  // ring stage of step kt+1
+    auto iteration = [&](int kt, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        wait_vmcnt_le<UPW>();
+        NVFP4_COMPILER_FENCE();
+        __builtin_amdgcn_s_barrier();
+        NVFP4_COMPILER_FENCE();
+        read_step(kt + 1, stage_next, set ^ 1);
+        const int stage_free = stage_next == 0 ? kStages - 1 : stage_next - 1;   // stage of step kt
+        const int nk = kt + kStages;
+        if ((nk & (kScaleGroup - 1)) == 0) copy_scales(min(nk / kScaleGroup, last_grp));
+        copy_codes(min(nk, last_kt), stage_free);
+        stage_next = stage_next == kStages - 1 ? 0 : stage_next + 1;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    y[e] = acc[i][j][rg * 4 + e] * alpha;
-                    if (ep.act == 1) y[e] = gelu_tanh_f32(y[e]);
-                }
-                if (m < g.M && n < g.N) {      // N % 4 == 0: a run of four is all in or all out
-                    if (ep.out_dtype == 0) {
-                        float4v o = {y[0], y[1], y[2], y[3]};
-                        *(float4v *)((float *)ep.Y + m * ep.ldy + n) = o;
-                    } else {
-                        uint32_t b0 = f32_to_bf16_rne(y[0]), b1 = f32_to_bf16_rne(y[1]);
-                        uint32_t b2 = f32_to_bf16_rne(y[2]), b3 = f32_to_bf16_rne(y[3]);
-                        uint2v o = {b0 | (b1 << 16), b2 | (b3 << 16)};
-                        if (ep.amax_partial) {
-                            hmax = pk_absmax_u16(hmax, o.x);
-                            hmax = pk_absmax_u16(hmax, o.y);
-                        }
-                        *(uint2v *)((uint16_t *)ep.Y + m * ep.ldy + n) = o;
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int t = 0; t < NMF; ++t) {
+                const int i = t / TM, jj = t % TM;
+                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, frag[j & 1][TM + i]),
+                                                                     __builtin_bit_cast(half8v, frag[j & 1][jj]),
+                                                                     acc[i][jj], 0, 0, 0);
+                // next sub-step's fragments: 2 NF pieces dealt over the NMF MFMAs
+#pragma unroll
+                for (int pc = 0; pc < 2 * NF; ++pc)
+                    if (pc * NMF / (2 * NF) == t) {
+                        if (j < 3) expand_piece(set, j + 1, pc);
+                        else expand_piece(set ^ 1, 0, pc);
                     }
-                }
+                // the next step's scales (read at the top of this iteration) become f16 during sub-step 2
+                if (j == 2 && t < NF) convert_scales(set ^ 1, t);
+#if NVFP4_SCHED
+                __builtin_amdgcn_sched_barrier(0);
+#endif
             }
         }
+    };
+    {
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, 1>;
+        int kt = 0;
+        for (; kt + 1 < KT; kt += 2) {
+            iteration(kt, S0{});
+            iteration(kt + 1, S1{});
+        }
+        if (kt < KT) iteration(kt, S0{});
     }
-    if (ep.amax_partial) {
-        __shared__ uint32_t wmax[4];
-        uint32_t mx = wave_max_u32(pk_hmax_u16(hmax));
-        if (lane == 0) wmax[wave] = mx;
-        __syncthreads();
-        if (tid == 0)
-            ep.amax_partial[blockIdx.y * gridDim.x + blockIdx.x] = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
-    }
+    wait_vmcnt_le<0>();                            // no copy may still be writing LDS when the epilogue reuses it
+    __syncthreads();
+    gemm_epilogue<TM, TN, OUT_BF16>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
+#else
+    (void)g;
+#endif
 }
 
-// Any K % 16 == 0 (K not a multiple of 64), any M, N: one output per thread, plain loop.
-// Only used for shapes the tiled kernel does not take; not a performance path.
+// Any K % 16 == 0, any M, N: one output per thread, plain loop.  Only used for
+// shapes the tiled kernel does not take (K not a multiple of 64, N not a
+// multiple of 8); not a performance path.
 __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g)
 {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -244,19 +661,37 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g)
     else ((uint16_t *)g.ep.Y)[m * g.ep.ldy + n] = (uint16_t)f32_to_bf16_rne(y);
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool OUT_BF16>
 static hipError_t launch_tiled(const GemmArgs &g, hipStream_t s)
 {
-    constexpr int smem = 2 * (BM + BN) * ROW_BYTES;
+    constexpr int smem_main = 2 * (BM + BN) * ROW_BYTES, smem_epi = 4 * 16384;
+    constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_f16mfma_kernel<BM, BN>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_ldsf16_kernel<BM, BN, OUT_BF16>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM));
-    gemm_f16mfma_kernel<BM, BN><<<grid, 256, smem, s>>>(g);
+    gemm_ldsf16_kernel<BM, BN, OUT_BF16><<<grid, 256, smem, s>>>(g);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, bool OUT_BF16>
+static hipError_t launch_regdq(const GemmArgs &g, hipStream_t s)
+{
+    constexpr int smem_main = kStages * (BM + BN) * 32 + 2 * (BM + BN) * 16, smem_epi = 4 * 16384;
+    constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_regdq_kernel<BM, BN, OUT_BF16>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM));
+    gemm_regdq_kernel<BM, BN, OUT_BF16><<<grid, 256, smem, s>>>(g);
     return hipGetLastError();
 }
 
@@ -265,6 +700,12 @@ static bool use_big_tile(int64_t M, int64_t N)
     // 256x256 tiles once they fill the 256 CUs at least ~2 times over; else 128x128
     int64_t big = ((M + 255) / 256) * ((N + 255) / 256);
     return big >= 512;
+}
+
+static bool tiled_ok(int64_t M, int64_t N, int64_t K)
+{
+    // 32-bit buffer offsets and zero-fill of out-of-range rows need operands below 2 GiB
+    return K % BK == 0 && N % 8 == 0 && M * (K >> 1) < 0x7FFFFFF0LL && N * (K >> 1) < 0x7FFFFFF0LL;
 }
 
 int gemm_workgroups(int64_t M, int64_t N)
@@ -278,15 +719,16 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
                        int64_t N, int64_t K, const GemmEpilogue &ep, int *n_wg, hipStream_t s)
 {
     GemmArgs g{codesA, scalesA, codesW, scalesW, gsA, gsW, M, N, K, ep};
-    if (K % BK != 0 || N % 4 != 0) {
+    if (!tiled_ok(M, N, K)) {
         if (n_wg) *n_wg = 0;
         int64_t total = M * N;
         gemm_generic_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(g);
         return hipGetLastError();
     }
     if (n_wg) *n_wg = gemm_workgroups(M, N);
-    if (use_big_tile(M, N)) return launch_tiled<256, 256>(g, s);
-    return launch_tiled<128, 128>(g, s);
+    const bool bf16 = ep.out_dtype != 0;
+    if (use_big_tile(M, N)) return bf16 ? launch_regdq<256, 256, true>(g, s) : launch_regdq<256, 256, false>(g, s);
+    return bf16 ? launch_tiled<128, 128, true>(g, s) : launch_tiled<128, 128, false>(g, s);
 }
 
 }  // namespace nvfp4
