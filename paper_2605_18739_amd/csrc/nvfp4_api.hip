@@ -171,7 +171,7 @@ int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
     Timed t(s, NVFP4_OP_GEMM_ACT_QUANT);
     // workspace: [partials][H if not supplied]
     uint32_t *partial = static_cast<uint32_t *>(workspace);
-    const size_t part_bytes = align_up((size_t)std::max(kMaxPartials, gemm_workgroups(M, N)) * 4, 256);
+    const size_t part_bytes = align_up((size_t)std::max<int64_t>(kMaxPartials, ((M + 127) / 128) * ((N + 127) / 128)) * 4, 256);
     uint16_t *H = h_bf16_opt ? static_cast<uint16_t *>(h_bf16_opt)
                              : reinterpret_cast<uint16_t *>(static_cast<uint8_t *>(workspace) + part_bytes);
     GemmEpilogue ep{};
@@ -201,7 +201,9 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
         return kPartialBytes;
     case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c != 0: caller supplies H
         if (a <= 0 || b <= 0) return 0;
-        size_t part = align_up((size_t)std::max(kMaxPartials, gemm_workgroups(a, b)) * 4, 256);
+        // the GEMM tile (hence the number of per-workgroup maxima) depends on K, which this query
+        // does not know: reserve for the smallest tile
+        size_t part = align_up((size_t)std::max<int64_t>(kMaxPartials, ((a + 127) / 128) * ((b + 127) / 128)) * 4, 256);
         return part + (c ? 0 : align_up((size_t)a * (size_t)b * 2, 256));
     }
     default:

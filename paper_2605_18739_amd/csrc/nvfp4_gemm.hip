@@ -69,6 +69,15 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// two fp32 -> packed bf16 (round to nearest even), one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+    float2v v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
+}
+
 // Eight codes (one dword, all inside one 16-element block) times the block
 // scale -> eight f16: four conversions (two codes each) and four packed multiplies.
 __device__ __forceinline__ half8v expand_dword(uint32_t w, half2v p)
@@ -106,7 +115,9 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
     const GemmEpilogue &ep = g.ep;
     uint8_t *slab = lds + wave * 16384;
     uint32_t hmax = 0;                            // largest |bf16(H)| pattern seen by this lane
-    const int key = swz_key(lrow);
+    // granule swizzle: XOR with as many key bits as keep the index inside a row
+    constexpr int KEYMASK = (WN % 64 == 0) ? 7 : 3;
+    const int key = swz_key(lrow) & KEYMASK;
     auto epilogue_slab = [&](auto j_c) {
         constexpr int j = decltype(j_c)::value;
         if constexpr (!OUT_BF16) {
@@ -130,7 +141,7 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
 #pragma unroll
             for (int p = 0; p < 32 * GPR / 64; ++p) {
                 const int idx = p * 64 + lane, r = idx / GPR, gi = idx % GPR;
-                float4v o = *(const float4v *)(slab + r * ROWB + ((gi ^ swz_key(r)) << 4));
+                float4v o = *(const float4v *)(slab + r * ROWB + ((gi ^ (swz_key(r) & KEYMASK)) << 4));
                 const int64_t m = wave_m0 + j * 32 + r, n = wave_n0 + gi * 4;
                 if (m < g.M && n < g.N) *(float4v *)((float *)ep.Y + m * ep.ldy + n) = o;
             }
@@ -151,8 +162,8 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
                             y[e] = acc[i][j][(2 * rp + s) * 4 + e] * alpha;
                             if (ep.act == 1) y[e] = gelu_tanh_f32(y[e]);
                         }
-                        pk[s][0] = f32_to_bf16_rne(y[0]) | (f32_to_bf16_rne(y[1]) << 16);
-                        pk[s][1] = f32_to_bf16_rne(y[2]) | (f32_to_bf16_rne(y[3]) << 16);
+                        pk[s][0] = pack_bf16x2(y[0], y[1]);
+                        pk[s][1] = pack_bf16x2(y[2], y[3]);
                     }
                     // lower half keeps run s=0 and receives the upper half's s=0; upper half
                     // keeps s=1 and receives the lower half's s=1
@@ -165,7 +176,7 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
 #pragma unroll
             for (int p = 0; p < 32 * GPR / 64; ++p) {
                 const int idx = p * 64 + lane, r = idx / GPR, gi = idx % GPR;
-                uint4v o = *(const uint4v *)(slab + r * ROWB + ((gi ^ swz_key(r)) << 4));
+                uint4v o = *(const uint4v *)(slab + r * ROWB + ((gi ^ (swz_key(r) & KEYMASK)) << 4));
                 const int64_t m = wave_m0 + j * 32 + r, n = wave_n0 + gi * 8;
                 if (m < g.M && n < g.N) {
                     if (ep.amax_partial) {
@@ -398,26 +409,34 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
 // ============================================================================
 // Register-dequantizing kernel (the fast path for large tiles).
 //
-// The operands stay 4-bit all the way into LDS: every K step of 64 the packed
-// codes of the tile (32 B per row) are copied HBM -> LDS by buffer loads that
-// write LDS directly (no registers, no VALU, no LDS-write instructions), and
-// the E4M3 scales follow every fourth step (16 B per row cover 256 k).  A wave
-// reads its own rows' codes back with one 128-bit LDS read per 32-row tile and
-// step, and expands them in registers right before the MFMAs that consume them:
-// one v_cvt_scalef32_pk_f16_fp4 and one v_pk_mul_f16 per pair of elements.  On
-// this machine VALU instructions issue in the shadow of a running MFMA while
-// LDS instructions largely do not, so trading LDS traffic (4x fewer bytes, 4x
-// fewer instructions than staging f16) for VALU work (each operand element is
+// The operands stay 4-bit all the way into LDS.  Every 128 k the packed codes of
+// the tile (64 B per row) are copied HBM -> LDS by buffer loads that write LDS
+// directly (no registers, no VALU, no LDS-write instructions); four lanes fetch
+// the four 16-byte chunks of one row, so a copy instruction touches 16 rows, not
+// 64.  The E4M3 scales follow every 256 k (16 B per row).  A wave reads its own
+// rows' codes back with one 128-bit LDS read per 32-row tile and 64 k, and
+// expands them in registers right before the MFMAs that consume them: one
+// v_cvt_scalef32_pk_f16_fp4 and one v_pk_mul_f16 per pair of elements.  On this
+// machine VALU instructions issue in the shadow of a running MFMA while LDS and
+// memory instructions largely do not, so trading LDS traffic (4x fewer bytes
+// and instructions than staging f16) for VALU work (each operand element is
 // expanded by the two waves that use it) is what keeps the matrix pipe busy.
 //
-// K order inside a step: lane half h (lanes 32h..32h+31) of an MFMA operand owns
-// codes k = 32h .. 32h+31 of the step, and MFMA sub-step j (0..3) multiplies
-// codes 32h + 8j .. 32h + 8j + 7 -- a permutation of k applied to both operands
-// alike.  Those eight codes sit in dword j of the lane's 16-byte chunk and share
-// block scale 2h + j/2.
+// K order: a "register step" is 64 k = four MFMA sub-steps.  In register step
+// (g, half) -- g counts 128-k copy steps -- lane half h (lanes 32h .. 32h+31) of
+// an MFMA operand owns chunk 2 half + h of its row, i.e. k = 128 g + 32 (2 half
+// + h) + 0..31, and MFMA sub-step j multiplies the eight codes of dword j of that
+// chunk, which share block scale 4 half + 2 h + j/2 of the copy step.  This is a
+// permutation of k applied to both operands alike.
+//
+// LDS: chunk c of staged row r sits in 16-byte slot 4 r + (c ^ ((r >> 2) & 3)) of
+// its stage; the copy instructions fill slots in lane order (lane l of unit u
+// fetches row 16 u + l/4, chunk (l & 3) ^ key), and sixteen consecutive rows of
+// one chunk -- what a fragment read touches per LDS cycle -- fall on distinct
+// banks.
 // ============================================================================
-constexpr int kStages = 3;             // LDS ring of code stages (all copy targets stay below 64 KB)
-constexpr int kScaleGroup = 4;         // K steps covered by one 16-byte run of scales
+constexpr int kCodeStages = 2;         // LDS ring of 128-k code stages
+constexpr int kScaleSteps = 2;         // copy steps covered by one 16-byte run of scales
 
 // s_waitcnt vmcnt(N) alone: vmcnt sits in bits 3:0 and 15:14, expcnt (6:4) and
 // lgkmcnt (11:8) are left at "do not wait".
@@ -437,14 +456,12 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     constexpr int NF = TM + TN;                    // operand fragments per MFMA sub-step
     constexpr int NMF = TM * TN;                   // MFMAs per sub-step
     constexpr int ROWS = BM + BN;                  // staged rows: A rows first, then W rows
-    constexpr int CODE_STAGE = ROWS * 32;          // [2 chunks][ROWS][16 B]
-    constexpr int SCALE_STAGE = ROWS * 16;         // [ROWS][16 B]
-    constexpr int SCALE_BASE = kStages * CODE_STAGE;
-    constexpr int UNITS = ROWS * 2 / 64;           // 1 KB copy instructions per code stage
-    constexpr int UPW = UNITS / 4;                 // ... per wave
-    constexpr int SUNITS = ROWS / 64, SUPW = SUNITS / 4;
-    static_assert(UNITS % 4 == 0 && SUNITS % 4 == 0 && BM % 64 == 0 && BN % 64 == 0, "tile shape");
-    static_assert(2 * NF == NMF || true, "");
+    constexpr int CODE_STAGE = ROWS * 64;          // 128 k of codes per row
+    constexpr int SCALE_STAGE = ROWS * 16;         // 256 k of scales per row
+    constexpr int SCALE_BASE = kCodeStages * CODE_STAGE;
+    constexpr int UNITS = ROWS / 16, UPW = (UNITS + 3) / 4;     // 1 KB code copies per stage / per wave (at most)
+    constexpr int SUNITS = ROWS / 64, SUPW = (SUNITS + 3) / 4;  // 1 KB scale copies
+    static_assert(UNITS % 4 == 0 && BM % 64 == 0 && BN % 64 == 0, "tile shape");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
@@ -454,71 +471,75 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
     const int kbytes = (int)(g.K >> 1), kblocks = (int)(g.K >> 4);
-    const int KT = (int)(g.K / BK);
+    const int KT = (int)(g.K / BK);                // register steps
+    const int GT = (KT + 1) / 2;                   // copy steps
 
+    // Copies are range checked against the operand size: a row past the end of the
+    // operand, and the part of the last copy step past the end of the last row, read
+    // as zeros (all per-lane offsets live in the checked vector offset).
     const __amdgpu_buffer_rsrc_t rcA = __builtin_amdgcn_make_buffer_rsrc((void *)g.codesA, 0, (int)(g.M * kbytes), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesA, 0, (int)(g.M * kblocks), 0x00020000);
     const __amdgpu_buffer_rsrc_t rcW = __builtin_amdgcn_make_buffer_rsrc((void *)g.codesW, 0, (int)(g.N * kbytes), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesW, 0, (int)(g.N * kblocks), 0x00020000);
 
-    // ---- copy units.  Code unit q (0 .. UNITS-1) is 64 consecutive staged rows of
-    // one 16-byte chunk: q = chunk * (ROWS/64) + row group; lane l copies row
-    // 64*group + l.  Wave w issues units w*UPW .. w*UPW+UPW-1.  A row past the end of
-    // its operand gets an offset beyond the buffer and is filled with zeros.
+    // ---- copy units.  Code unit u (0 .. UNITS-1) is 16 consecutive staged rows, 64 B
+    // each; wave w issues units w, w+4, w+8, ...  Scale unit: 64 rows, 16 B each.
     int cvoff[UPW], svoff[SUPW];
 #pragma unroll
     for (int x = 0; x < UPW; ++x) {
-        const int q = wave * UPW + x, chunk = q / (ROWS / 64), srow = (q % (ROWS / 64)) * 64 + lane;
+        const int srow = (wave + 4 * x) * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((srow >> 2) & 3);
         const bool isA = srow < BM;
         const int64_t gr = isA ? m0 + srow : n0 + (srow - BM);
-        cvoff[x] = gr < (isA ? g.M : g.N) ? (int)(gr * kbytes) + chunk * 16 : 0x7FFFFFF0;
+        cvoff[x] = gr < (isA ? g.M : g.N) ? (int)(gr * kbytes) + chunk * 16 : 0x7FF00000;
     }
 #pragma unroll
     for (int x = 0; x < SUPW; ++x) {
-        const int srow = (wave * SUPW + x) * 64 + lane;
+        const int srow = (wave + 4 * x) * 64 + lane;
         const bool isA = srow < BM;
         const int64_t gr = isA ? m0 + srow : n0 + (srow - BM);
-        svoff[x] = gr < (isA ? g.M : g.N) ? (int)(gr * kblocks) : 0x7FFFFFF0;
+        svoff[x] = (srow < ROWS && gr < (isA ? g.M : g.N)) ? (int)(gr * kblocks) : 0x7FF00000;
     }
-    auto copy_codes = [&](int kt, int stage) {      // K step kt -> ring stage `stage` (= kt % kStages)
+    auto copy_codes = [&](int gs) {                 // copy step gs -> code stage gs & 1
 #pragma unroll
         for (int x = 0; x < UPW; ++x) {
-            const int q = wave * UPW + x;
-            const bool isA = (q % (ROWS / 64)) * 64 < BM;
-            uint8_t *dst = lds + stage * CODE_STAGE + q * 1024;
-            if (isA) __builtin_amdgcn_raw_ptr_buffer_load_lds(rcA, (lds_ptr_t)dst, 16, cvoff[x], kt * 32, 0, 0);
-            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rcW, (lds_ptr_t)dst, 16, cvoff[x], kt * 32, 0, 0);
+            const int u = wave + 4 * x;
+            uint8_t *dst = lds + (gs & 1) * CODE_STAGE + u * 1024;
+            if (u * 16 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rcA, (lds_ptr_t)dst, 16, cvoff[x] + gs * 64, 0, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rcW, (lds_ptr_t)dst, 16, cvoff[x] + gs * 64, 0, 0, 0);
         }
     };
-    auto copy_scales = [&](int grp) {               // scale group grp (steps 4 grp .. 4 grp + 3) -> stage grp & 1
+    auto copy_scales = [&](int grp) {               // scale group grp (copy steps 2 grp, 2 grp + 1) -> scale stage grp & 1
 #pragma unroll
         for (int x = 0; x < SUPW; ++x) {
-            const int u = wave * SUPW + x;
-            const bool isA = u * 64 < BM;
-            uint8_t *dst = lds + SCALE_BASE + (grp & 1) * SCALE_STAGE + u * 1024;
-            if (isA) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)dst, 16, svoff[x], grp * 16, 0, 0);
-            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsW, (lds_ptr_t)dst, 16, svoff[x], grp * 16, 0, 0);
+            const int u = wave + 4 * x;
+            if (u < SUNITS) {                        // wave-uniform
+                uint8_t *dst = lds + SCALE_BASE + (grp & 1) * SCALE_STAGE + u * 1024;
+                if (u * 64 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)dst, 16, svoff[x] + grp * 16, 0, 0, 0);
+                else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsW, (lds_ptr_t)dst, 16, svoff[x] + grp * 16, 0, 0, 0);
+            }
         }
     };
 
-    // ---- what this lane reads back: fragment f (0..TM-1: A tiles, TM..NF-1: W tiles)
-    // is staged row frow[f]; its codes are chunk lhalf of that row.
-    int code_off[NF], scale_off[NF];
+    // ---- what this lane reads back.  Fragment f (0..TM-1: A tiles, TM..NF-1: W tiles)
+    // is staged row frag_row(f); all of a lane's rows share the swizzle key.
+    const int key = (lrow >> 2) & 3;
+    int code_lane[2];                               // byte offset inside a stage for half 0 / 1, tile 0 of A
 #pragma unroll
-    for (int f = 0; f < NF; ++f) {
-        const int srow = f < TM ? wm * WM + f * 32 + lrow : BM + wn * WN + (f - TM) * 32 + lrow;
-        code_off[f] = (lhalf * ROWS + srow) * 16;
-        scale_off[f] = SCALE_BASE + srow * 16 + 2 * lhalf;
-    }
-    uint4v codes[2][NF];          // packed codes of the step being multiplied / the next one
-    uint32_t scl[2][NF];          // their two block scales (E4M3 bytes) ...
+    for (int half = 0; half < 2; ++half) code_lane[half] = lrow * 64 + (((2 * half + lhalf) ^ key) << 4);
+    const int scale_lane = lrow * 16 + 2 * lhalf;
+    auto frag_row0 = [&](int f) { return f < TM ? wm * WM + f * 32 : BM + wn * WN + (f - TM) * 32; };
+    uint4v codes[2][NF];          // packed codes of the register step being multiplied / the next one
+    uint16_t scl[2][NF];          // their two block scales (E4M3 bytes) ...
     uint32_t scf[2][NF];          // ... and the same as a pair of f16
-    auto read_step = [&](int kt, int stage, int set) {
-        const int sbase = ((kt / kScaleGroup) & 1) * SCALE_STAGE + (kt & (kScaleGroup - 1)) * 4;
+    auto read_step = [&](int rs, int set) {         // register step rs = 2 gs + half
+        const int gs = rs >> 1, half = rs & 1;
+        const uint8_t *cbase = lds + (gs & 1) * CODE_STAGE + code_lane[half];
+        const uint8_t *sbase = lds + SCALE_BASE + ((gs >> 1) & 1) * SCALE_STAGE + (gs & 1) * 8 + half * 4 + scale_lane;
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
-            codes[set][f] = *(const uint4v *)(lds + stage * CODE_STAGE + code_off[f]);
-            scl[set][f] = *(const uint16_t *)(lds + sbase + scale_off[f]);
+            codes[set][f] = *(const uint4v *)(cbase + frag_row0(f) * 64);
+            scl[set][f] = *(const uint16_t *)(sbase + frag_row0(f) * 16);
         }
     };
 
@@ -548,51 +569,55 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
         frag[j & 1][f][d0] = x0;
         frag[j & 1][f][d1] = x1;
     };
-
     auto convert_scales = [&](int set, int f) {     // E4M3 pair -> f16 pair, pinned where it is written
-        uint32_t raw = scl[set][f];
-        NVFP4_PIN1(raw);               // do not start before this point (the LDS read may still be in flight)
+        uint16_t raw16 = scl[set][f];
+        NVFP4_PIN1(raw16);                          // do not touch it before this point (the LDS read may still be in flight)
+        uint32_t raw = raw16;
         uint32_t x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(raw, 1.0f, false));
         NVFP4_PIN1(x);
         scf[set][f] = x;
     };
 
-    // ---- prologue: steps 0 .. kStages-1 in flight, step 0 in registers and expanded.
-    // Copies never reach past the last K step: a step index is clamped to KT-1 (the
-    // clamped copy lands in a stage nobody multiplies from).
-    const int last_kt = KT - 1, last_grp = last_kt / kScaleGroup;
+    // ---- prologue: copy steps 0 and 1 in flight, register step 0 read and expanded
     copy_scales(0);
-#pragma unroll
-    for (int s = 0; s < kStages; ++s) copy_codes(min(s, last_kt), s);
-    wait_vmcnt_le<(kStages - 1) * UPW>();          // step 0 (and the scales before it) has landed
+    copy_codes(0);
+    copy_codes(min(1, GT - 1));
+    wait_vmcnt_le<UPW>();                           // scales and copy step 0 have landed
     NVFP4_COMPILER_FENCE();
     __builtin_amdgcn_s_barrier();
     NVFP4_COMPILER_FENCE();
-    read_step(0, 0, 0);
+    read_step(0, 0);
 #pragma unroll
     for (int f = 0; f < NF; ++f) convert_scales(0, f);
 #pragma unroll
     for (int pc = 0; pc < 2 * NF; ++pc) expand_piece(0, 0, pc);
 
-    // ---- main loop.  Iteration kt: wait for the copies of step kt+1 (issued two
-    // iterations ago; only the newest batch may still be in flight), barrier, read
-    // step kt+1 into the other register set, start the copies of step kt+kStages into
-    // the stage step kt occupied (every wave finished reading it before the barrier),
-    // then four sub-steps of NMF MFMAs, each interleaved with the expansion of the
-    // next sub-step's fragments.
-    int stage_next = 1 % kStages;                  // ring stage of step kt+1
-    auto iteration = [&](int kt, auto set_c) {
-        constexpr int set = decltype(set_c)::value;
-        wait_vmcnt_le<UPW>();
-        NVFP4_COMPILER_FENCE();
-        __builtin_amdgcn_s_barrier();
-        NVFP4_COMPILER_FENCE();
-        read_step(kt + 1, stage_next, set ^ 1);
-        const int stage_free = stage_next == 0 ? kStages - 1 : stage_next - 1;   // stage of step kt
-        const int nk = kt + kStages;
-        if ((nk & (kScaleGroup - 1)) == 0) copy_scales(min(nk / kScaleGroup, last_grp));
-        copy_codes(min(nk, last_kt), stage_free);
-        stage_next = stage_next == kStages - 1 ? 0 : stage_next + 1;
+    // ---- main loop over register steps.  Iteration rs reads register step rs+1 into
+    // the other register set and multiplies step rs.  When rs+1 opens a new copy step
+    // (rs odd) its copies -- issued two iterations earlier -- are awaited and a
+    // barrier makes them visible; the stage of copy step rs/2, which every wave has
+    // finished reading by then, is refilled with copy step rs/2 + 2.
+    auto iteration = [&](int rs, auto half_c) {
+        constexpr int half = decltype(half_c)::value;      // rs & 1; also the register set of step rs
+        constexpr int set = half;
+        if constexpr (half == 1) {
+#if !(NVFP4_EXPERIMENT & 1)
+            wait_vmcnt_le<0>();
+#endif
+            NVFP4_COMPILER_FENCE();
+#if !(NVFP4_EXPERIMENT & 2)
+            __builtin_amdgcn_s_barrier();
+#endif
+            NVFP4_COMPILER_FENCE();
+        }
+        read_step(rs + 1, set ^ 1);
+        if constexpr (half == 1) {
+#if !(NVFP4_EXPERIMENT & 4)
+            const int ng = (rs >> 1) + 2;                   // copy step to start (clamped at the end of K)
+            if ((ng & 1) == 0) copy_scales(min(ng, GT - 1) >> 1);
+            copy_codes(min(ng, GT - 1));
+#endif
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
 #pragma unroll
@@ -604,7 +629,7 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
                 // next sub-step's fragments: 2 NF pieces dealt over the NMF MFMAs
 #pragma unroll
                 for (int pc = 0; pc < 2 * NF; ++pc)
-                    if (pc * NMF / (2 * NF) == t) {
+                    if (pc * NMF / (2 * NF) == t && !(NVFP4_EXPERIMENT & 8)) {
                         if (j < 3) expand_piece(set, j + 1, pc);
                         else expand_piece(set ^ 1, 0, pc);
                     }
@@ -617,14 +642,14 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
         }
     };
     {
-        using S0 = std::integral_constant<int, 0>;
-        using S1 = std::integral_constant<int, 1>;
-        int kt = 0;
-        for (; kt + 1 < KT; kt += 2) {
-            iteration(kt, S0{});
-            iteration(kt + 1, S1{});
+        using H0 = std::integral_constant<int, 0>;
+        using H1 = std::integral_constant<int, 1>;
+        int rs = 0;
+        for (; rs + 1 < KT; rs += 2) {
+            iteration(rs, H0{});
+            iteration(rs + 1, H1{});
         }
-        if (kt < KT) iteration(kt, S0{});
+        if (rs < KT) iteration(rs, H0{});
     }
     wait_vmcnt_le<0>();                            // no copy may still be writing LDS when the epilogue reuses it
     __syncthreads();
@@ -681,7 +706,7 @@ static hipError_t launch_tiled(const GemmArgs &g, hipStream_t s)
 template <int BM, int BN, bool OUT_BF16>
 static hipError_t launch_regdq(const GemmArgs &g, hipStream_t s)
 {
-    constexpr int smem_main = kStages * (BM + BN) * 32 + 2 * (BM + BN) * 16, smem_epi = 4 * 16384;
+    constexpr int smem_main = kCodeStages * (BM + BN) * 64 + 2 * (BM + BN) * 16, smem_epi = 4 * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
     static bool attr_set = false;
     if (!attr_set) {
@@ -695,23 +720,43 @@ static hipError_t launch_regdq(const GemmArgs &g, hipStream_t s)
     return hipGetLastError();
 }
 
-static bool use_big_tile(int64_t M, int64_t N)
+// Tile choice.  Cost of a launch in units of "one 64-k step of a 256x256 tile":
+// waves of workgroups over the 256 CUs times (steps per tile * relative step cost +
+// a fixed per-tile overhead worth about 8 steps).
+enum TileKind { kTile128 = 0, kTile256x256 = 1, kTile256x192 = 2 };
+
+static double tile_cost(int64_t M, int64_t N, int64_t K, int bm, int bn, double step_cost)
 {
-    // 256x256 tiles once they fill the 256 CUs at least ~2 times over; else 128x128
-    int64_t big = ((M + 255) / 256) * ((N + 255) / 256);
-    return big >= 512;
+    const double tiles = (double)((M + bm - 1) / bm) * (double)((N + bn - 1) / bn);
+    const double waves = (double)(int64_t)((tiles + 255.0) / 256.0);
+    return waves * ((double)(K / BK) * step_cost + 8.0);
+}
+
+static TileKind choose_tile(int64_t M, int64_t N, int64_t K)
+{
+    // relative step costs measured on MI355X: 128x128 f16-staging kernel about 0.45
+    // of a 256x256 register-dequantizing step for a quarter of the work
+    const double c128 = tile_cost(M, N, K, 128, 128, 0.45);
+    const double c256 = tile_cost(M, N, K, 256, 256, 1.0);
+    const double c192 = tile_cost(M, N, K, 256, 192, 0.80);
+    if (c256 <= c128 && c256 <= c192) return kTile256x256;
+    if (c192 <= c128) return kTile256x192;
+    return kTile128;
 }
 
 static bool tiled_ok(int64_t M, int64_t N, int64_t K)
 {
     // 32-bit buffer offsets and zero-fill of out-of-range rows need operands below 2 GiB
-    return K % BK == 0 && N % 8 == 0 && M * (K >> 1) < 0x7FFFFFF0LL && N * (K >> 1) < 0x7FFFFFF0LL;
+    return K % BK == 0 && N % 8 == 0 && M * (K >> 1) < 0x7FF00000LL && N * (K >> 1) < 0x7FF00000LL;
 }
 
-int gemm_workgroups(int64_t M, int64_t N)
+int gemm_workgroups(int64_t M, int64_t N, int64_t K)
 {
-    if (use_big_tile(M, N)) return (int)(((M + 255) / 256) * ((N + 255) / 256));
-    return (int)(((M + 127) / 128) * ((N + 127) / 128));
+    switch (choose_tile(M, N, K)) {
+    case kTile256x256: return (int)(((M + 255) / 256) * ((N + 255) / 256));
+    case kTile256x192: return (int)(((M + 255) / 256) * ((N + 191) / 192));
+    default: return (int)(((M + 127) / 128) * ((N + 127) / 128));
+    }
 }
 
 hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const float *gsA,
@@ -725,10 +770,13 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
         gemm_generic_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(g);
         return hipGetLastError();
     }
-    if (n_wg) *n_wg = gemm_workgroups(M, N);
+    if (n_wg) *n_wg = gemm_workgroups(M, N, K);
     const bool bf16 = ep.out_dtype != 0;
-    if (use_big_tile(M, N)) return bf16 ? launch_regdq<256, 256, true>(g, s) : launch_regdq<256, 256, false>(g, s);
-    return bf16 ? launch_tiled<128, 128, true>(g, s) : launch_tiled<128, 128, false>(g, s);
+    switch (choose_tile(M, N, K)) {
+    case kTile256x256: return bf16 ? launch_regdq<256, 256, true>(g, s) : launch_regdq<256, 256, false>(g, s);
+    case kTile256x192: return bf16 ? launch_regdq<256, 192, true>(g, s) : launch_regdq<256, 192, false>(g, s);
+    default: return bf16 ? launch_tiled<128, 128, true>(g, s) : launch_tiled<128, 128, false>(g, s);
+    }
 }
 
 }  // namespace nvfp4

@@ -34,6 +34,6 @@ struct GemmEpilogue {
 hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const float *gsA,
                        const uint8_t *codesW, const uint8_t *scalesW, const float *gsW, int64_t M,
                        int64_t N, int64_t K, const GemmEpilogue &ep, int *n_wg, hipStream_t s);
-int gemm_workgroups(int64_t M, int64_t N);
+int gemm_workgroups(int64_t M, int64_t N, int64_t K);
 
 }  // namespace nvfp4

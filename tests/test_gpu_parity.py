@@ -283,11 +283,32 @@ def test_full_size_projection_config2(oracle):
     assert torch.isfinite(y).all()
 
 
-def test_gemm_large_tile_path(oracle):
-    """A shape large enough for the 256x256 workgroup tile, with ragged M and N tails."""
-    M, N, K = 4100, 8196, 128
-    g = np.random.default_rng(77)
+@pytest.mark.parametrize("M,N,K", [(4100, 8200, 128),      # 256x192 tiles, ragged M and N tails
+                                   (8200, 8192, 192),      # 256x256 tiles, odd number of 64-k steps
+                                   (3520, 3072, 320),      # the projection shape, 5 steps
+                                   (700, 1544, 64)])       # single step
+def test_gemm_large_tile_paths(oracle, M, N, K):
+    """Shapes that take the register-dequantizing kernels (256-row tiles)."""
+    g = np.random.default_rng(M + K)
     ab = wl.activation_with_outliers(M, K, 7, 0)
     wb = wl.normal((N, K), 0.02, 7, 1)
-    rows = np.unique(np.concatenate([[0, 255, 256, 4095, 4096, 4099], g.integers(0, M, 20)])).astype(np.int64)
-    _gemm_case(oracle, ab, wb, "large tile", rows=rows)
+    edge = [0, 127, 128, 255, 256, M - 257, M - 256, M - 1]
+    rows = np.unique(np.concatenate([edge, g.integers(0, M, 20)])).astype(np.int64)
+    _gemm_case(oracle, ab, wb, f"large tile {M}x{N}x{K}", rows=rows)
+
+
+def test_gemm_subnormal_and_extreme_block_scales(oracle):
+    """Raw operands with every E4M3 scale byte 0x00..0x7E (subnormal scales included)."""
+    g = np.random.default_rng(99)
+    M, N, K = 512, 768, 256
+    def raw(rows):
+        codes = g.integers(0, 256, size=(rows, K // 2)).astype(np.uint8)
+        scales = g.integers(0, 127, size=(rows, K // 16)).astype(np.uint8)
+        scales[:, ::3] = g.integers(0, 9, size=scales[:, ::3].shape)       # many subnormal / zero scales
+        return codes, scales
+    ca, sa = raw(M)
+    cw, sw = raw(N)
+    gsa, gsw = np.float32(2.0 ** -8), np.float32(1.5 * 2.0 ** -9)
+    Y, S = oracle.gemm(oracle.Q(ca, sa, gsa), oracle.Q(cw, sw, gsw))
+    y = nv.nvfp4_gemm(nv.NVFP4Tensor.from_host(ca, sa, gsa), nv.NVFP4Tensor.from_host(cw, sw, gsw)).cpu().numpy()
+    assert_gemm_close(y, Y, S, "raw scales")
