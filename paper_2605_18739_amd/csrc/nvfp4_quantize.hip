@@ -5,6 +5,22 @@
 #include "nvfp4_device.h"
 #include "nvfp4_kernels.h"
 
+#ifndef NVFP4_Q_PLAIN_STORE
+#define NVFP4_Q_PLAIN_STORE 0
+#endif
+#ifndef NVFP4_Q_UNROLL
+#define NVFP4_Q_UNROLL 2
+#endif
+#ifndef NVFP4_DQ_UNROLL
+#define NVFP4_DQ_UNROLL 2
+#endif
+#ifndef NVFP4_DQ_GRID
+#define NVFP4_DQ_GRID 8192
+#endif
+#ifndef NVFP4_Q_GRID
+#define NVFP4_Q_GRID 16384
+#endif
+
 namespace nvfp4 {
 
 // --------------------------------------------------------------------------
@@ -83,26 +99,45 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
     const int64_t nb_row = C >> 4;
     const int64_t nblk = R * nb_row;
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < nblk; g += stride) {
-        int64_t off;
-        if (CONTIG) off = g << 4;
-        else {
-            int64_t r = g / nb_row;
-            off = r * ld + ((g - r * nb_row) << 4);
-        }
-        const uint4v *p = (const uint4v *)(x + off);
-        uint4v v0 = __builtin_nontemporal_load(p), v1 = __builtin_nontemporal_load(p + 1);
-        uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-        uint32_t acc = 0;
+    constexpr int U = NVFP4_Q_UNROLL;              // blocks in flight per lane
+    for (int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x; g0 < nblk; g0 += stride * U) {
+        uint4v v0[U], v1[U];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
-        float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
-        uint32_t sbyte = block_scale_exact(bmax, sg, inv_6sg);
-        uint32_t c0, c1;
-        encode_block16(w, e4m3_to_f32(sbyte), sg, c0, c1);
-        uint2v cc = {c0, c1};
-        __builtin_nontemporal_store(cc, (uint2v *)(codes + (g << 3)));
-        scales[g] = (uint8_t)sbyte;
+        for (int u = 0; u < U; ++u) {
+            const int64_t g = g0 + u * stride;
+            if (g < nblk) {
+                int64_t off;
+                if (CONTIG) off = g << 4;
+                else {
+                    int64_t r = g / nb_row;
+                    off = r * ld + ((g - r * nb_row) << 4);
+                }
+                const uint4v *p = (const uint4v *)(x + off);
+                v0[u] = __builtin_nontemporal_load(p);
+                v1[u] = __builtin_nontemporal_load(p + 1);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t g = g0 + u * stride;
+            if (g < nblk) {
+                uint32_t w[8] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w, v1[u].x, v1[u].y, v1[u].z, v1[u].w};
+                uint32_t acc = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
+                float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
+                uint32_t sbyte = block_scale_exact(bmax, sg, inv_6sg);
+                uint32_t c0, c1;
+                encode_block16(w, e4m3_to_f32(sbyte), sg, c0, c1);
+                uint2v cc = {c0, c1};
+#if NVFP4_Q_PLAIN_STORE
+                *(uint2v *)(codes + (g << 3)) = cc;
+#else
+                __builtin_nontemporal_store(cc, (uint2v *)(codes + (g << 3)));
+#endif
+                scales[g] = (uint8_t)sbyte;
+            }
+        }
     }
 }
 
@@ -201,34 +236,52 @@ __global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__rest
     }
     __syncthreads();
     const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < nblk; g += stride) {
-        uint2v cc = __builtin_nontemporal_load((const uint2v *)(codes + (g << 3)));
-        uint4v t = table[scales[g] & 0x7Fu];
-        uint32_t o[8];
+    constexpr int U = NVFP4_DQ_UNROLL;             // blocks in flight per lane
+    for (int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x; g0 < nblk; g0 += stride * U) {
+        uint2v ccs[U];
+        uint32_t sbs[U];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            uint32_t cw = h ? cc.y : cc.x;
-            // selectors: magnitude index of the even / odd elements, one per byte
-            uint32_t se = cw & 0x07070707u, so = (cw >> 4) & 0x07070707u;
-            uint32_t lo_e = __builtin_amdgcn_perm(t.y, t.x, se), lo_o = __builtin_amdgcn_perm(t.y, t.x, so);
-            uint32_t hi_e = __builtin_amdgcn_perm(t.w, t.z, se), hi_o = __builtin_amdgcn_perm(t.w, t.z, so);
-            hi_e |= (cw << 4) & 0x80808080u;      // sign of even elements: bit 3 of each byte
-            hi_o |= cw & 0x80808080u;             // sign of odd elements: bit 7
-            // element 2b = (hi_e.b, lo_e.b), element 2b+1 = (hi_o.b, lo_o.b); dword b = elems 2b, 2b+1
-            uint32_t e01 = __builtin_amdgcn_perm(hi_e, lo_e, 0x05010400u);  // even elems 0,1 -> b0 b1
-            uint32_t e23 = __builtin_amdgcn_perm(hi_e, lo_e, 0x07030602u);
-            uint32_t o01 = __builtin_amdgcn_perm(hi_o, lo_o, 0x05010400u);
-            uint32_t o23 = __builtin_amdgcn_perm(hi_o, lo_o, 0x07030602u);
-            // e01 = [even(byte0) | even(byte1)<<16] ; o01 likewise for the odd nibbles
-            o[4 * h + 0] = __builtin_amdgcn_perm(o01, e01, 0x05040100u);
-            o[4 * h + 1] = __builtin_amdgcn_perm(o01, e01, 0x07060302u);
-            o[4 * h + 2] = __builtin_amdgcn_perm(o23, e23, 0x05040100u);
-            o[4 * h + 3] = __builtin_amdgcn_perm(o23, e23, 0x07060302u);
+        for (int u = 0; u < U; ++u) {
+            const int64_t g = g0 + u * stride;
+            if (g < nblk) {
+                ccs[u] = __builtin_nontemporal_load((const uint2v *)(codes + (g << 3)));
+                sbs[u] = scales[g];
+            }
         }
-        uint4v a = {o[0], o[1], o[2], o[3]}, b = {o[4], o[5], o[6], o[7]};
-        uint4v *q = (uint4v *)(out + (g << 4));
-        __builtin_nontemporal_store(a, q);
-        __builtin_nontemporal_store(b, q + 1);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t g = g0 + u * stride;
+            if (g >= nblk) continue;
+            const uint2v cc = ccs[u];
+            uint4v t = table[sbs[u] & 0x7Fu];
+            uint32_t o[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                uint32_t cw = h ? cc.y : cc.x;
+                // selectors: magnitude index of the even / odd elements, one per byte
+                uint32_t se = cw & 0x07070707u, so = (cw >> 4) & 0x07070707u;
+                uint32_t lo_e = __builtin_amdgcn_perm(t.y, t.x, se), lo_o = __builtin_amdgcn_perm(t.y, t.x, so);
+                uint32_t hi_e = __builtin_amdgcn_perm(t.w, t.z, se), hi_o = __builtin_amdgcn_perm(t.w, t.z, so);
+                hi_e |= (cw << 4) & 0x80808080u;      // sign of even elements: bit 3 of each byte
+                hi_o |= cw & 0x80808080u;             // sign of odd elements: bit 7
+                // element 2b = (hi_e.b, lo_e.b), element 2b+1 = (hi_o.b, lo_o.b); dword b = elems 2b, 2b+1
+                uint32_t e01 = __builtin_amdgcn_perm(hi_e, lo_e, 0x05010400u);  // even elems of bytes 0, 1
+                uint32_t e23 = __builtin_amdgcn_perm(hi_e, lo_e, 0x07030602u);
+                uint32_t o01 = __builtin_amdgcn_perm(hi_o, lo_o, 0x05010400u);
+                uint32_t o23 = __builtin_amdgcn_perm(hi_o, lo_o, 0x07030602u);
+                o[4 * h + 0] = __builtin_amdgcn_perm(o01, e01, 0x05040100u);
+                o[4 * h + 1] = __builtin_amdgcn_perm(o01, e01, 0x07060302u);
+                o[4 * h + 2] = __builtin_amdgcn_perm(o23, e23, 0x05040100u);
+                o[4 * h + 3] = __builtin_amdgcn_perm(o23, e23, 0x07060302u);
+            }
+            uint4v a = {o[0], o[1], o[2], o[3]}, b = {o[4], o[5], o[6], o[7]};
+            // plain stores: a lane writes two 16-byte halves of a 32-byte run, and the
+            // cache merges neighbouring lanes' halves into full lines (streaming stores
+            // of half lines reach only about 2 TB/s here)
+            uint4v *q = (uint4v *)(out + (g << 4));
+            q[0] = a;
+            q[1] = b;
+        }
     }
 }
 
@@ -256,7 +309,7 @@ hipError_t launch_quantize_rows(const uint16_t *x, int64_t R, int64_t C, int64_t
                                 const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
                                 float *gs_out, hipStream_t s)
 {
-    int grid = grid_for(R * (C >> 4), 2048);
+    int grid = grid_for(R * (C >> 4), NVFP4_Q_GRID);
     if (ld == C)
         quantize_rows_kernel<true><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes,
                                                         scales, gs_out);
@@ -279,7 +332,7 @@ hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, cons
                                int64_t K, uint16_t *out, hipStream_t s)
 {
     int64_t nblk = rows * (K >> 4);
-    int grid = grid_for(nblk, 2048);
+    int grid = grid_for(nblk, NVFP4_DQ_GRID);
     dequant_bf16_kernel<<<grid, 256, 0, s>>>(codes, scales, gs, nblk, out);
     return hipGetLastError();
 }
