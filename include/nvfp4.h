@@ -106,7 +106,10 @@ int nvfp4_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y, int64_t ld
  *   is given.  NULL: H's amax is only known when the GEMM ends, so H is staged
  *   in the workspace (or h_bf16_opt) and packed by a second light kernel.
  * out: rows = M, K = N (N % 16 == 0).  h_bf16_opt: NULL or device bf16 [M, N].
- * workspace: nvfp4_workspace_bytes(NVFP4_OP_GEMM_ACT_QUANT, M, N, 0).
+ * workspace: nvfp4_workspace_bytes(NVFP4_OP_GEMM_ACT_QUANT, M, N, flags) with flags
+ *   bit 0 set when h_bf16_opt is given and bit 1 set when global_scale_in is
+ *   given (bit 1 assumes K % 64 == 0; other K fall back to staging H, leave it
+ *   clear for them).
  */
 int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
                          const float *global_scale_in, nvfp4_tensor *out, void *h_bf16_opt,

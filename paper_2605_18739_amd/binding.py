@@ -139,7 +139,8 @@ def nvfp4_gemm_act_quant(A, W, act=ACT_GELU_TANH, global_scale_in=None, out=None
     if out is None:
         out = NVFP4Tensor(M, N, dev)
     if workspace is None:
-        workspace = _workspace(nvfp4_workspace_bytes(OP_GEMM_ACT_QUANT, M, N, 1 if h_bf16 is not None else 0), dev)
+        flags = (1 if h_bf16 is not None else 0) | (2 if (global_scale_in is not None and A.K % 64 == 0) else 0)
+        workspace = _workspace(nvfp4_workspace_bytes(OP_GEMM_ACT_QUANT, M, N, flags), dev)
     ca, cw, co = A.c(), W.c(), out.c()
     _check(lib().nvfp4_gemm_act_quant(ctypes.byref(ca), ctypes.byref(cw), act, _ptr(global_scale_in),
                                       ctypes.byref(co), _ptr(h_bf16), _ptr(workspace), workspace.numel(),

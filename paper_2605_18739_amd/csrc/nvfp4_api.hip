@@ -162,7 +162,10 @@ int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
     const int64_t M = A->rows, N = W->rows;
     if (out->rows != M || out->K != N) return NVFP4_ERR_SHAPE;
     if (h_bf16_opt && !aligned16(h_bf16_opt)) return NVFP4_ERR_ALIGN;
-    const size_t need = nvfp4_workspace_bytes(NVFP4_OP_GEMM_ACT_QUANT, M, N, h_bf16_opt ? 1 : 0);
+    const bool tiled = gemm_is_tiled(M, N, A->K);
+    const bool single_pass = global_scale_in && tiled;          // the epilogue quantizes, H is not staged
+    const size_t part_bytes = align_up((size_t)std::max<int64_t>(kMaxPartials, ((M + 127) / 128) * ((N + 127) / 128)) * 4, 256);
+    const size_t need = part_bytes + ((h_bf16_opt || single_pass) ? 0 : align_up((size_t)M * (size_t)N * 2, 256));
     if (!workspace || workspace_bytes < need) return NVFP4_ERR_WORKSPACE;
     if (!aligned16(workspace)) return NVFP4_ERR_ALIGN;
 
@@ -171,15 +174,29 @@ int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
     Timed t(s, NVFP4_OP_GEMM_ACT_QUANT);
     // workspace: [partials][H if not supplied]
     uint32_t *partial = static_cast<uint32_t *>(workspace);
-    const size_t part_bytes = align_up((size_t)std::max<int64_t>(kMaxPartials, ((M + 127) / 128) * ((N + 127) / 128)) * 4, 256);
     uint16_t *H = h_bf16_opt ? static_cast<uint16_t *>(h_bf16_opt)
                              : reinterpret_cast<uint16_t *>(static_cast<uint8_t *>(workspace) + part_bytes);
+    if (single_pass) {
+        // single pass: the GEMM epilogue quantizes its own bf16 tile; H is written only on request
+        GemmEpilogue ep{};
+        ep.out_dtype = NVFP4_OUT_BF16;
+        ep.act = act;
+        ep.Y = h_bf16_opt;
+        ep.ldy = N;
+        ep.q_scale = global_scale_in;
+        ep.q_scale_out = out->global_scale;
+        ep.q_codes = out->codes;
+        ep.q_scales = out->scales;
+        hipError_t e = launch_gemm(A->codes, A->scales, A->global_scale, W->codes, W->scales,
+                                   W->global_scale, M, N, A->K, ep, nullptr, s);
+        return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+    }
     GemmEpilogue ep{};
     ep.out_dtype = NVFP4_OUT_BF16;
     ep.act = act;
     ep.Y = H;
     ep.ldy = N;
-    ep.amax_partial = global_scale_in ? nullptr : partial;
+    ep.amax_partial = (global_scale_in || !tiled) ? nullptr : partial;
     int n_wg = 0;
     if (launch_gemm(A->codes, A->scales, A->global_scale, W->codes, W->scales, W->global_scale, M, N,
                     A->K, ep, &n_wg, s) != hipSuccess)
@@ -199,12 +216,16 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
     case NVFP4_OP_QUANTIZE:
     case NVFP4_OP_KV_QUANT:
         return kPartialBytes;
-    case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c != 0: caller supplies H
+    case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c: bit 0 = caller supplies H, bit 1 = caller supplies the scale
         if (a <= 0 || b <= 0) return 0;
         // the GEMM tile (hence the number of per-workgroup maxima) depends on K, which this query
         // does not know: reserve for the smallest tile
         size_t part = align_up((size_t)std::max<int64_t>(kMaxPartials, ((a + 127) / 128) * ((b + 127) / 128)) * 4, 256);
-        return part + (c ? 0 : align_up((size_t)a * (size_t)b * 2, 256));
+        // with a given scale the fused epilogue needs no staging of H -- unless the shape falls back
+        // to the untiled kernel (K % 64 != 0 or N % 8 != 0), which this query cannot see either:
+        // only skip the H area when N is a multiple of 16 and leave K to the caller's contract
+        const bool need_h = !(c & 1) && !((c & 2) && (b & 15) == 0);
+        return part + (need_h ? align_up((size_t)a * (size_t)b * 2, 256) : 0);
     }
     default:
         return 0;

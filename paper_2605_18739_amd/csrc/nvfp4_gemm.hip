@@ -44,6 +44,8 @@ namespace nvfp4 {
 constexpr int BK = 64;                 // K elements per pipeline step
 constexpr int ROW_BYTES = BK * 2;      // one staged f16 row
 
+enum { kEpiF32 = 0, kEpiBF16 = 1, kEpiQuant = 2 };   // epilogue: fp32 out, bf16 out, bf16 + fused re-quantization
+
 struct GemmArgs {
     const uint8_t *codesA, *scalesA;
     const uint8_t *codesW, *scalesW;
@@ -103,7 +105,7 @@ __device__ __forceinline__ int lds_chunk_off(int row, int c) { return row * ROW_
 // through a private 16 KB slab of LDS, 32 output rows at a time: a lane owns (row
 // m, four consecutive n) after the MFMA, and (row m, 16 consecutive bytes) when
 // it stores, so whole rows of the wave tile leave as contiguous runs.
-template <int TM, int TN, bool OUT_BF16>
+template <int TM, int TN, int EPI>
 __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const GemmArgs &g, uint8_t *lds,
                                               int64_t wave_m0, int64_t wave_n0)
 {
@@ -115,12 +117,19 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
     const GemmEpilogue &ep = g.ep;
     uint8_t *slab = lds + wave * 16384;
     uint32_t hmax = 0;                            // largest |bf16(H)| pattern seen by this lane
+    // fused quantizer: the tensor scale comes from the caller
+    float q_sg = 1.0f, q_inv_6sg = 1.0f;
+    if constexpr (EPI == kEpiQuant) {
+        q_sg = *ep.q_scale;
+        q_inv_6sg = 1.0f / (6.0f * q_sg);
+        if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *ep.q_scale_out = q_sg;
+    }
     // granule swizzle: XOR with as many key bits as keep the index inside a row
     constexpr int KEYMASK = (WN % 64 == 0) ? 7 : 3;
     const int key = swz_key(lrow) & KEYMASK;
     auto epilogue_slab = [&](auto j_c) {
         constexpr int j = decltype(j_c)::value;
-        if constexpr (!OUT_BF16) {
+        if constexpr (EPI == kEpiF32) {
             // fp32: slab row = WN * 4 bytes, granule = 4 floats
             constexpr int ROWB = WN * 4, GPR = WN / 4;       // granules per row
 #pragma unroll
@@ -173,19 +182,47 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
                     const int gi = 4 * i + 2 * rp + lhalf;
                     *(uint4v *)(slab + lrow * ROWB + ((gi ^ key) << 4)) = o;
                 }
+            if (EPI == kEpiBF16 || ep.Y != nullptr) {
 #pragma unroll
-            for (int p = 0; p < 32 * GPR / 64; ++p) {
-                const int idx = p * 64 + lane, r = idx / GPR, gi = idx % GPR;
-                uint4v o = *(const uint4v *)(slab + r * ROWB + ((gi ^ (swz_key(r) & KEYMASK)) << 4));
-                const int64_t m = wave_m0 + j * 32 + r, n = wave_n0 + gi * 8;
-                if (m < g.M && n < g.N) {
-                    if (ep.amax_partial) {
-                        hmax = pk_absmax_u16(hmax, o.x);
-                        hmax = pk_absmax_u16(hmax, o.y);
-                        hmax = pk_absmax_u16(hmax, o.z);
-                        hmax = pk_absmax_u16(hmax, o.w);
+                for (int p = 0; p < 32 * GPR / 64; ++p) {
+                    const int idx = p * 64 + lane, r = idx / GPR, gi = idx % GPR;
+                    uint4v o = *(const uint4v *)(slab + r * ROWB + ((gi ^ (swz_key(r) & KEYMASK)) << 4));
+                    const int64_t m = wave_m0 + j * 32 + r, n = wave_n0 + gi * 8;
+                    if (m < g.M && n < g.N) {
+                        if (ep.amax_partial) {
+                            hmax = pk_absmax_u16(hmax, o.x);
+                            hmax = pk_absmax_u16(hmax, o.y);
+                            hmax = pk_absmax_u16(hmax, o.z);
+                            hmax = pk_absmax_u16(hmax, o.w);
+                        }
+                        *(uint4v *)((uint16_t *)ep.Y + m * ep.ldy + n) = o;
                     }
-                    *(uint4v *)((uint16_t *)ep.Y + m * ep.ldy + n) = o;
+                }
+            }
+            if constexpr (EPI == kEpiQuant) {
+                // fused re-quantization along n: a lane takes one 16-element block (two
+                // granules) of the bf16 slab and runs the exact block quantizer on it
+                constexpr int BPR = WN / 16;                  // blocks per slab row
+#pragma unroll
+                for (int p = 0; p < 32 * BPR / 64; ++p) {
+                    const int idx = p * 64 + lane, r = idx / BPR, b = idx % BPR;
+                    const int kr = swz_key(r) & KEYMASK;
+                    uint4v lo = *(const uint4v *)(slab + r * ROWB + (((2 * b) ^ kr) << 4));
+                    uint4v hi = *(const uint4v *)(slab + r * ROWB + (((2 * b + 1) ^ kr) << 4));
+                    const int64_t m = wave_m0 + j * 32 + r, n = wave_n0 + b * 16;
+                    if (m < g.M && n < g.N) {                 // N % 16 == 0: a block is all in or all out
+                        uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                        uint32_t am = 0;
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) am = pk_absmax_u16(am, w[q]);
+                        const float bmax = __uint_as_float(pk_hmax_u16(am) << 16);
+                        const uint32_t sbyte = block_scale_exact(bmax, q_sg, q_inv_6sg);
+                        uint32_t c0, c1;
+                        encode_block16(w, e4m3_to_f32(sbyte), q_sg, c0, c1);
+                        uint2v cc = {c0, c1};
+                        *(uint2v *)(ep.q_codes + m * (g.N >> 1) + (n >> 1)) = cc;
+                        ep.q_scales[m * (g.N >> 4) + (n >> 4)] = (uint8_t)sbyte;
+                    }
                 }
             }
         }
@@ -228,7 +265,7 @@ __device__ __forceinline__ void sched_phase()
     }
 }
 
-template <int BM, int BN, bool OUT_BF16>
+template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
 {
     constexpr int WM = BM / 2, WN = BN / 2;        // per-wave tile (2 x 2 waves)
@@ -403,7 +440,7 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
         if (kt < KT) iteration(kt, B0{}, T{}, T{});
     }
 
-    gemm_epilogue<TM, TN, OUT_BF16>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
+    gemm_epilogue<TM, TN, EPI>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
 }
 
 // ============================================================================
@@ -447,7 +484,7 @@ __device__ __forceinline__ void wait_vmcnt_le()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
 }
 
-template <int BM, int BN, bool OUT_BF16>
+template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
@@ -653,7 +690,7 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     }
     wait_vmcnt_le<0>();                            // no copy may still be writing LDS when the epilogue reuses it
     __syncthreads();
-    gemm_epilogue<TM, TN, OUT_BF16>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
+    gemm_epilogue<TM, TN, EPI>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
 #else
     (void)g;
 #endif
@@ -686,37 +723,37 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g)
     else ((uint16_t *)g.ep.Y)[m * g.ep.ldy + n] = (uint16_t)f32_to_bf16_rne(y);
 }
 
-template <int BM, int BN, bool OUT_BF16>
+template <int BM, int BN, int EPI>
 static hipError_t launch_tiled(const GemmArgs &g, hipStream_t s)
 {
     constexpr int smem_main = 2 * (BM + BN) * ROW_BYTES, smem_epi = 4 * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_ldsf16_kernel<BM, BN, OUT_BF16>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_ldsf16_kernel<BM, BN, EPI>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM));
-    gemm_ldsf16_kernel<BM, BN, OUT_BF16><<<grid, 256, smem, s>>>(g);
+    gemm_ldsf16_kernel<BM, BN, EPI><<<grid, 256, smem, s>>>(g);
     return hipGetLastError();
 }
 
-template <int BM, int BN, bool OUT_BF16>
+template <int BM, int BN, int EPI>
 static hipError_t launch_regdq(const GemmArgs &g, hipStream_t s)
 {
     constexpr int smem_main = kCodeStages * (BM + BN) * 64 + 2 * (BM + BN) * 16, smem_epi = 4 * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_regdq_kernel<BM, BN, OUT_BF16>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_regdq_kernel<BM, BN, EPI>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM));
-    gemm_regdq_kernel<BM, BN, OUT_BF16><<<grid, 256, smem, s>>>(g);
+    gemm_regdq_kernel<BM, BN, EPI><<<grid, 256, smem, s>>>(g);
     return hipGetLastError();
 }
 
@@ -750,6 +787,8 @@ static bool tiled_ok(int64_t M, int64_t N, int64_t K)
     return K % BK == 0 && N % 8 == 0 && M * (K >> 1) < 0x7FF00000LL && N * (K >> 1) < 0x7FF00000LL;
 }
 
+bool gemm_is_tiled(int64_t M, int64_t N, int64_t K) { return tiled_ok(M, N, K); }
+
 int gemm_workgroups(int64_t M, int64_t N, int64_t K)
 {
     switch (choose_tile(M, N, K)) {
@@ -771,12 +810,16 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
         return hipGetLastError();
     }
     if (n_wg) *n_wg = gemm_workgroups(M, N, K);
-    const bool bf16 = ep.out_dtype != 0;
+    const int epi = ep.q_scale ? kEpiQuant : (ep.out_dtype != 0 ? kEpiBF16 : kEpiF32);
+#define NVFP4_LAUNCH(FN, BM_, BN_)                                                          \
+    (epi == kEpiQuant ? FN<BM_, BN_, kEpiQuant>(g, s)                                       \
+                      : (epi == kEpiBF16 ? FN<BM_, BN_, kEpiBF16>(g, s) : FN<BM_, BN_, kEpiF32>(g, s)))
     switch (choose_tile(M, N, K)) {
-    case kTile256x256: return bf16 ? launch_regdq<256, 256, true>(g, s) : launch_regdq<256, 256, false>(g, s);
-    case kTile256x192: return bf16 ? launch_regdq<256, 192, true>(g, s) : launch_regdq<256, 192, false>(g, s);
-    default: return bf16 ? launch_tiled<128, 128, true>(g, s) : launch_tiled<128, 128, false>(g, s);
+    case kTile256x256: return NVFP4_LAUNCH(launch_regdq, 256, 256);
+    case kTile256x192: return NVFP4_LAUNCH(launch_regdq, 256, 192);
+    default: return NVFP4_LAUNCH(launch_tiled, 128, 128);
     }
+#undef NVFP4_LAUNCH
 }
 
 }  // namespace nvfp4

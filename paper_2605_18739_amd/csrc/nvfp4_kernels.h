@@ -27,6 +27,7 @@ struct GemmEpilogue {
     int64_t ldy;
     uint32_t *amax_partial;   // per-workgroup |bf16(H)| maxima, or nullptr
     const float *q_scale;     // global scale for the fused quantizer, or nullptr (no fused quantize)
+    float *q_scale_out;       // receives the scale that was used
     uint8_t *q_codes;         // [M, N/2]
     uint8_t *q_scales;        // [M, N/16]
 };
@@ -35,5 +36,6 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
                        const uint8_t *codesW, const uint8_t *scalesW, const float *gsW, int64_t M,
                        int64_t N, int64_t K, const GemmEpilogue &ep, int *n_wg, hipStream_t s);
 int gemm_workgroups(int64_t M, int64_t N, int64_t K);
+bool gemm_is_tiled(int64_t M, int64_t N, int64_t K);   // false: the untiled fallback kernel (no fused epilogues)
 
 }  // namespace nvfp4

@@ -269,6 +269,9 @@ def _act_quant_case(oracle, M, N, K, given_scale, what):
 def test_gemm_act_quant(oracle, given_scale):
     _act_quant_case(oracle, 200, 272, 256, given_scale, "small")
     _act_quant_case(oracle, 520, 1040, 128, given_scale, "multi-tile")
+    _act_quant_case(oracle, 2100, 2064, 256, given_scale, "256x192 tiles")
+    _act_quant_case(oracle, 4200, 3072, 128, given_scale, "256x256 tiles")
+    _act_quant_case(oracle, 40, 48, 48, given_scale, "untiled K")
 
 
 # -------------------------------------------------------- full benchmark sizes
