@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row extras (KV, training triplet)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
@@ -69,27 +71,45 @@ def main():
     t1 = time.perf_counter()
     n_gemm, ms_gemm = nv.nvfp4_timing_read(nv.OP_GEMM)
     n_fused, ms_fused = nv.nvfp4_timing_read(nv.OP_GEMM_ACT_QUANT)
+    n_up, ms_up = nv.nvfp4_timing_read(nv.OP_GEMM_ACT_QUANT_GEMM)
     n_q, ms_q = nv.nvfp4_timing_read(nv.OP_QUANTIZE)
     nv.nvfp4_set_timing(False)
 
     ms_step = (t1 - t0) * 1e3 / args.steps
     flops_gemm = 2.0 * M * F * D
     value = 2 * flops_gemm / (ms_step * 1e-3) / 1e12
-    # dominant kernel: the down-projection GEMM launch (one kernel per nvfp4_gemm call)
-    gemm_ms = ms_gemm / max(n_gemm, 1)
-    achieved = flops_gemm / (gemm_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_f16mfma_kernel (down projection 3520x3072x14336)",
+    # dominant kernel: the up-projection GEMM launch (GELU + bf16 H + amax in its epilogue),
+    # timed by HIP events around that one kernel on the stream it runs on
+    up_ms = ms_up / max(n_up, 1)
+    achieved = flops_gemm / (up_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_regdq_kernel<256,256,bf16> (up projection 3520x14336x3072, f16 MFMA)",
                 "achieved": round(achieved, 1), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4), "traffic": None,
-                "avg_launch_ms": round(gemm_ms, 4), "launches": n_gemm}
+                "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4), "traffic": profile_traffic(),
+                "avg_launch_ms": round(up_ms, 4), "launches": n_up}
+    gemm_ms = ms_gemm / max(n_gemm, 1)
     fused_ms = ms_fused / max(n_fused, 1)
     q_ms = ms_q / max(n_q, 1)
     kernels = {
-        "up_gemm_gelu_requant": {"ms": round(fused_ms, 4), "tflops": round(flops_gemm / (fused_ms * 1e-3) / 1e12, 1)},
+        "up_gemm_gelu_h_amax": {"ms": round(up_ms, 4), "tflops": round(achieved, 1)},
+        "up_gemm_gelu_requant_total": {"ms": round(fused_ms, 4), "tflops": round(flops_gemm / (fused_ms * 1e-3) / 1e12, 1)},
+        "down_gemm_3520x3072x14336": {"ms": round(gemm_ms, 4), "tflops": round(flops_gemm / (gemm_ms * 1e-3) / 1e12, 1),
+                                      "frac_mfma": round(flops_gemm / (gemm_ms * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS, 4)},
         "quantize_A_3520x3072": {"ms": round(q_ms, 4),
                                  "GBs": round(B_PER_ELEM * M * D / (q_ms * 1e-3) / 1e9, 1)},
     }
+    # the same up projection with the activation scale supplied by the caller: one pass, H never written
+    gs_h = qH.global_scale.clone()
+    ms1 = _time_op(nv, torch, nv.OP_GEMM_ACT_QUANT,
+                   lambda: nv.nvfp4_gemm_act_quant(qA, W1, nv.ACT_GELU_TANH, global_scale_in=gs_h, out=qH, workspace=ws_g), 20)
+    kernels["up_gemm_gelu_requant_given_scale"] = {"ms": round(ms1, 4), "tflops": round(flops_gemm / (ms1 * 1e-3) / 1e12, 1)}
 
+    if args.copy_calib:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     rows = None if args.no_rows else measure_rows(nv, wl, torch, np)
     cpu = None if args.no_cpu else cpu_baseline(cfg, wl, np)
 
@@ -104,6 +124,18 @@ def main():
         "roofline": roofline, "kernels": kernels, "rows": rows, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
+
+
+def profile_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", "gemm_up_projection_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def _time_op(nv, torch, op_id, fn, iters, warm=2):

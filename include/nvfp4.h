@@ -64,7 +64,8 @@ typedef struct nvfp4_tensor {
 enum { NVFP4_OUT_F32 = 0, NVFP4_OUT_BF16 = 1 };
 enum { NVFP4_ACT_NONE = 0, NVFP4_ACT_GELU_TANH = 1 };
 enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2, NVFP4_OP_GEMM = 3,
-       NVFP4_OP_KV_DEQUANT = 4 };
+       NVFP4_OP_KV_DEQUANT = 4,
+       NVFP4_OP_GEMM_ACT_QUANT_GEMM = 5 /* timing only: the GEMM kernel inside nvfp4_gemm_act_quant */ };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).

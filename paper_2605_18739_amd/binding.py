@@ -16,7 +16,7 @@ _lib = None
 
 OUT_F32, OUT_BF16 = 0, 1
 ACT_NONE, ACT_GELU_TANH = 0, 1
-OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT = 0, 1, 2, 3, 4
+OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT, OP_GEMM_ACT_QUANT_GEMM = 0, 1, 2, 3, 4, 5
 
 
 class _CTensor(ctypes.Structure):

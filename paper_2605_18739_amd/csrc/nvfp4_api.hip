@@ -187,6 +187,7 @@ int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
         ep.q_scale_out = out->global_scale;
         ep.q_codes = out->codes;
         ep.q_scales = out->scales;
+        Timed tg(s, NVFP4_OP_GEMM_ACT_QUANT_GEMM);
         hipError_t e = launch_gemm(A->codes, A->scales, A->global_scale, W->codes, W->scales,
                                    W->global_scale, M, N, A->K, ep, nullptr, s);
         return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
@@ -198,9 +199,12 @@ int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
     ep.ldy = N;
     ep.amax_partial = (global_scale_in || !tiled) ? nullptr : partial;
     int n_wg = 0;
-    if (launch_gemm(A->codes, A->scales, A->global_scale, W->codes, W->scales, W->global_scale, M, N,
-                    A->K, ep, &n_wg, s) != hipSuccess)
-        return NVFP4_ERR_LAUNCH;
+    {
+        Timed tg(s, NVFP4_OP_GEMM_ACT_QUANT_GEMM);
+        if (launch_gemm(A->codes, A->scales, A->global_scale, W->codes, W->scales, W->global_scale, M, N,
+                        A->K, ep, &n_wg, s) != hipSuccess)
+            return NVFP4_ERR_LAUNCH;
+    }
     int n_partial = n_wg;
     if (!global_scale_in && n_wg == 0) {   // shape went to the untiled kernel: ordinary amax pass over H
         if (launch_amax(H, M, N, N, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;

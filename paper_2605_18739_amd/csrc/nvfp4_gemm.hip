@@ -54,15 +54,16 @@ struct GemmArgs {
     GemmEpilogue ep;
 };
 
-// tanh-form GELU in fp32
+// tanh-form GELU in fp32: 0.5 y (1 + tanh(u)), u = sqrt(2/pi) (y + 0.044715 y^3), with
+// tanh(u) = 1 - 2 / (exp(2u) + 1), so gelu = y - y / (exp(2u) + 1).  exp and the
+// reciprocal are the hardware approximations (1 ulp); the result is rounded to bf16.
 __device__ __forceinline__ float gelu_tanh_f32(float y)
 {
-    const float c = 0.7978845608028654f;
-    float u = c * (y + 0.044715f * y * y * y);
-    // tanh(u) = 1 - 2 / (exp(2u) + 1)
-    float e = __expf(2.0f * u);
-    float t = 1.0f - 2.0f / (e + 1.0f);
-    return 0.5f * y * (1.0f + t);
+    const float c2 = 2.0f * 0.7978845608028654f * 1.4426950408889634f;   // 2 sqrt(2/pi) log2(e)
+    const float y2 = y * y;
+    const float t = y * (c2 + (c2 * 0.044715f) * y2);                    // 2u log2(e)
+    const float e = __builtin_amdgcn_exp2f(t);
+    return y - y * __builtin_amdgcn_rcpf(e + 1.0f);
 }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
