@@ -315,3 +315,93 @@ def test_gemm_subnormal_and_extreme_block_scales(oracle):
     Y, S = oracle.gemm(oracle.Q(ca, sa, gsa), oracle.Q(cw, sw, gsw))
     y = nv.nvfp4_gemm(nv.NVFP4Tensor.from_host(ca, sa, gsa), nv.NVFP4Tensor.from_host(cw, sw, gsw)).cpu().numpy()
     assert_gemm_close(y, Y, S, "raw scales")
+
+
+# The remaining benchmark configurations at full size, in the launch configurations bench.py
+# times: codes / scales / KV bytes in full, GEMM outputs on sampled rows the oracle computes.
+
+def _sample_rows(M, n, seed):
+    edge = [0, 127, 128, 255, 256, M - 257, M - 256, M - 1]
+    return np.unique(np.concatenate([edge, np.random.default_rng(seed).integers(0, M, n)])).astype(np.int64)
+
+
+def test_full_size_ffn_pair_config3(oracle):
+    cfg = wl.config3()
+    M, D, F = wl.TOKENS_INFER, wl.D_MODEL, wl.D_FFN
+    say("[config3] quantize A, W1, W2")
+    oa, ow1, ow2 = oracle.quantize(cfg["A"]), oracle.quantize(cfg["W1"]), oracle.quantize(cfg["W2"])
+    ga = nv.nvfp4_quantize(dev_bf16(cfg["A"]))
+    gw1 = nv.nvfp4_quantize(dev_bf16(cfg["W1"]))
+    gw2 = nv.nvfp4_quantize(dev_bf16(cfg["W2"]))
+    assert_q_equal(ga, oa, "A")
+    assert_q_equal(gw1, ow1, "W1")
+    assert_q_equal(gw2, ow2, "W2")
+    say("[config3] up projection + GELU + re-quantize (scale from amax)")
+    h = torch.empty((M, F), dtype=torch.bfloat16, device="cuda")
+    gh = nv.nvfp4_gemm_act_quant(ga, gw1, nv.ACT_GELU_TANH, h_bf16=h)
+    torch.cuda.synchronize()
+    hb = nv.bits_from_bf16(h)
+    oh = oracle.quantize(hb)
+    assert_q_equal(gh, oh, "fused H")            # fused bytes == quantizer applied to the H the GPU produced
+    rows = _sample_rows(M, 12, 3)
+    Y1, S1 = oracle.gemm(oa, ow1, rows=rows)
+    want = wl.bf16_bits_to_f32(oracle.gelu_tanh_bf16(Y1)).astype(np.float64)
+    got = wl.bf16_bits_to_f32(hb[rows]).astype(np.float64)
+    assert (np.abs(got - want) <= 2.0 ** -7 * np.abs(want) + 2.0 ** -15 * S1 + 1e-30).all()
+    say("[config3] single-pass variant with the same scale gives the same bytes")
+    gs = gh.global_scale.clone()
+    gh2 = nv.nvfp4_gemm_act_quant(ga, gw1, nv.ACT_GELU_TANH, global_scale_in=gs)
+    a, b = host_q(gh), host_q(gh2)
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all() and a[2] == b[2]
+    say("[config3] down projection")
+    Y2, S2 = oracle.gemm(oh, ow2, rows=rows)
+    y32 = nv.nvfp4_gemm(gh, gw2, nv.OUT_F32)
+    fro, worst = assert_gemm_close(y32.cpu().numpy()[rows], Y2, S2, "down projection")
+    say(f"        rel fro {fro:.2e}  worst err/S {worst:.2e}")
+    y16 = nv.nvfp4_gemm(gh, gw2, nv.OUT_BF16)
+    assert (nv.bits_from_bf16(y16) == nv.bits_from_bf16(y32.to(torch.bfloat16))).all()
+
+
+def test_full_size_kv_cache_config4(oracle):
+    cfg = wl.config4()
+    T, H, d = wl.KV_TOKENS, wl.KV_HEADS, wl.KV_DIM
+    for name in ("K", "V"):
+        say(f"[config4] {name}")
+        oq = oracle.quantize(cfg[name].reshape(T * H, d))
+        gq = nv.nvfp4_kv_quant(dev_bf16(cfg[name]))
+        assert_q_equal(gq, oq, name)
+        back = nv.bits_from_bf16(nv.nvfp4_kv_dequant(gq, T, H, d)).reshape(T * H, d)
+        want = oracle.dequant_bf16(oq)
+        assert (back == want).all()
+        x = wl.bf16_bits_to_f32(cfg[name]).astype(np.float64).reshape(T * H, d)
+        xh = wl.bf16_bits_to_f32(back).astype(np.float64)
+        rel = np.linalg.norm(x - xh) / np.linalg.norm(x)
+        say(f"        round-trip relative Frobenius error {rel:.4f} (reported, no closed form)")
+        assert 0.02 < rel < 0.2
+        # storage: 9/16 byte per element against 2 in bf16
+        assert (gq.codes.numel() + gq.scales.numel()) * 16 == 9 * T * H * d
+
+
+def test_full_size_training_triplet_config5(oracle):
+    cfg = wl.config5()
+    Mt, D, F = wl.TOKENS_TRAIN, wl.D_MODEL, wl.D_FFN
+    x, w, dy = dev_bf16(cfg["X"]), dev_bf16(cfg["W"]), dev_bf16(cfg["dY"])
+    q = {}
+    for name, bits, t in (("X", cfg["X"], x), ("W", cfg["W"], w), ("dY", cfg["dY"], dy)):
+        for axis in (0, 1):
+            say(f"[config5] quantize {name} axis {axis}")
+            oq = oracle.quantize(bits, block_axis=axis)
+            gq = nv.nvfp4_quantize(t, block_axis=axis)
+            assert_q_equal(gq, oq, f"{name} axis {axis}")
+            q[(name, axis)] = (oq, gq)
+    for what, a, b in (("fprop X W^T", ("X", 0), ("W", 0)),          # [Mt, F], K = D
+                       ("dgrad dY W", ("dY", 0), ("W", 1)),          # [Mt, D], K = F
+                       ("wgrad dY^T X", ("dY", 1), ("X", 1))):       # [F, D],  K = Mt
+        (oa, ga), (ob, gb) = q[a], q[b]
+        rows = _sample_rows(oa.rows, 6, 5)
+        say(f"[config5] {what}: {oa.rows}x{ob.rows}x{oa.K}")
+        Y, S = oracle.gemm(oa, ob, rows=rows)
+        y = nv.nvfp4_gemm(ga, gb, nv.OUT_F32)
+        fro, worst = assert_gemm_close(y.cpu().numpy()[rows], Y, S, what)
+        say(f"        rel fro {fro:.2e}  worst err/S {worst:.2e}")
+        del y
