@@ -50,8 +50,11 @@ struct GemmArgs {
     const uint8_t *codesA, *scalesA;
     const uint8_t *codesW, *scalesW;
     const float *gsA, *gsW;
-    int64_t M, N, K;
+    int64_t M, N, K;           // this launch's (sub-)problem
     GemmEpilogue ep;
+    int n_tiles_n;             // tiles along N: workgroup t works on tile (t / n_tiles_n, t % n_tiles_n)
+    int64_t q_pitch;           // row pitch in ELEMENTS of the fused quantizer's output (N of the whole problem)
+    int partial_base;          // first slot of this launch in ep.amax_partial
 };
 
 // tanh-form GELU in fp32: 0.5 y (1 + tanh(u)), u = sqrt(2/pi) (y + 0.044715 y^3), with
@@ -123,7 +126,7 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
     if constexpr (EPI == kEpiQuant) {
         q_sg = *ep.q_scale;
         q_inv_6sg = 1.0f / (6.0f * q_sg);
-        if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *ep.q_scale_out = q_sg;
+        if (blockIdx.x == 0 && tid == 0) *ep.q_scale_out = q_sg;
     }
     // granule swizzle: XOR with as many key bits as keep the index inside a row
     constexpr int KEYMASK = (WN % 64 == 0) ? 7 : 3;
@@ -221,8 +224,8 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
                         uint32_t c0, c1;
                         encode_block16(w, e4m3_to_f32(sbyte), q_sg, c0, c1);
                         uint2v cc = {c0, c1};
-                        *(uint2v *)(ep.q_codes + m * (g.N >> 1) + (n >> 1)) = cc;
-                        ep.q_scales[m * (g.N >> 4) + (n >> 4)] = (uint8_t)sbyte;
+                        *(uint2v *)(ep.q_codes + m * (g.q_pitch >> 1) + (n >> 1)) = cc;
+                        ep.q_scales[m * (g.q_pitch >> 4) + (n >> 4)] = (uint8_t)sbyte;
                     }
                 }
             }
@@ -239,7 +242,7 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
         if (lane == 0) wmax[wave] = mx;
         __syncthreads();
         if (tid == 0)
-            ep.amax_partial[blockIdx.y * gridDim.x + blockIdx.x] = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+            ep.amax_partial[g.partial_base + blockIdx.x] = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
     }
 }
 
@@ -280,7 +283,7 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    const int64_t m0 = (int64_t)(blockIdx.x / g.n_tiles_n) * BM, n0 = (int64_t)(blockIdx.x % g.n_tiles_n) * BN;
     const int kbytes = (int)(g.K >> 1), kblocks = (int)(g.K >> 4);
     const int KT = (int)(g.K / BK);
 
@@ -507,7 +510,7 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: it selects LDS targets of the copies
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    const int64_t m0 = (int64_t)(blockIdx.x / g.n_tiles_n) * BM, n0 = (int64_t)(blockIdx.x % g.n_tiles_n) * BN;
     const int kbytes = (int)(g.K >> 1), kblocks = (int)(g.K >> 4);
     const int KT = (int)(g.K / BK);                // register steps
     const int GT = (KT + 1) / 2;                   // copy steps
@@ -725,7 +728,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g)
 }
 
 template <int BM, int BN, int EPI>
-static hipError_t launch_tiled(const GemmArgs &g, hipStream_t s)
+static hipError_t launch_tiled(const GemmArgs &g, int64_t tiles, hipStream_t s)
 {
     constexpr int smem_main = 2 * (BM + BN) * ROW_BYTES, smem_epi = 4 * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
@@ -736,13 +739,15 @@ static hipError_t launch_tiled(const GemmArgs &g, hipStream_t s)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM));
-    gemm_ldsf16_kernel<BM, BN, EPI><<<grid, 256, smem, s>>>(g);
+    GemmArgs a = g;
+    a.n_tiles_n = (int)((g.N + BN - 1) / BN);
+    const unsigned grid = (unsigned)tiles;          // a prefix of the row-major tile grid
+    gemm_ldsf16_kernel<BM, BN, EPI><<<grid, 256, smem, s>>>(a);
     return hipGetLastError();
 }
 
 template <int BM, int BN, int EPI>
-static hipError_t launch_regdq(const GemmArgs &g, hipStream_t s)
+static hipError_t launch_regdq(const GemmArgs &g, int64_t tiles, hipStream_t s)
 {
     constexpr int smem_main = kCodeStages * (BM + BN) * 64 + 2 * (BM + BN) * 16, smem_epi = 4 * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
@@ -753,33 +758,83 @@ static hipError_t launch_regdq(const GemmArgs &g, hipStream_t s)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM));
-    gemm_regdq_kernel<BM, BN, EPI><<<grid, 256, smem, s>>>(g);
+    GemmArgs a = g;
+    a.n_tiles_n = (int)((g.N + BN - 1) / BN);
+    const unsigned grid = (unsigned)tiles;          // a prefix of the row-major tile grid
+    gemm_regdq_kernel<BM, BN, EPI><<<grid, 256, smem, s>>>(a);
     return hipGetLastError();
 }
 
 // Tile choice.  Cost of a launch in units of "one 64-k step of a 256x256 tile":
 // waves of workgroups over the 256 CUs times (steps per tile * relative step cost +
-// a fixed per-tile overhead worth about 8 steps).
+// a fixed per-tile overhead worth about 8 steps), plus about 4 for the launch itself.
 enum TileKind { kTile128 = 0, kTile256x256 = 1, kTile256x192 = 2 };
+struct TileShape { int bm, bn; double step_cost; };
+static const TileShape kShapes[3] = {{128, 128, 0.45}, {256, 256, 1.0}, {256, 192, 0.80}};
+constexpr int kCUs = 256;
 
-static double tile_cost(int64_t M, int64_t N, int64_t K, int bm, int bn, double step_cost)
+static double tile_cost(int64_t M, int64_t N, int64_t K, const TileShape &t)
 {
-    const double tiles = (double)((M + bm - 1) / bm) * (double)((N + bn - 1) / bn);
-    const double waves = (double)(int64_t)((tiles + 255.0) / 256.0);
-    return waves * ((double)(K / BK) * step_cost + 8.0);
+    const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+    const double waves = (double)((tiles + kCUs - 1) / kCUs);
+    return waves * ((double)(K / BK) * t.step_cost + 8.0) + 4.0;
 }
 
-static TileKind choose_tile(int64_t M, int64_t N, int64_t K)
+static TileKind choose_tile(int64_t M, int64_t N, int64_t K, double *cost = nullptr)
 {
-    // relative step costs measured on MI355X: 128x128 f16-staging kernel about 0.45
-    // of a 256x256 register-dequantizing step for a quarter of the work
-    const double c128 = tile_cost(M, N, K, 128, 128, 0.45);
-    const double c256 = tile_cost(M, N, K, 256, 256, 1.0);
-    const double c192 = tile_cost(M, N, K, 256, 192, 0.80);
-    if (c256 <= c128 && c256 <= c192) return kTile256x256;
-    if (c192 <= c128) return kTile256x192;
-    return kTile128;
+    int best = 0;
+    double c[3];
+    for (int i = 0; i < 3; ++i) {
+        c[i] = tile_cost(M, N, K, kShapes[i]);
+        // prefer the larger tile on ties (order: 256x256, 256x192, 128x128)
+    }
+    best = (c[1] <= c[0] && c[1] <= c[2]) ? 1 : (c[2] <= c[0] ? 2 : 0);
+    if (cost) *cost = c[best];
+    return (TileKind)best;
+}
+
+// A launch plan: the main launch runs whole waves of tiles (in row-major tile
+// order) with one tile shape; what is left of the tile grid -- the tail of one row
+// of tiles and the rows below it -- goes to up to two more launches on the
+// corresponding sub-rectangles of the output, each with the tile shape that suits
+// it, when the cost model says that beats one more, mostly idle, wave.
+struct SubLaunch { int64_t m_lo, m_hi, n_lo, n_hi; TileKind kind; int64_t tiles; };   // tiles: how many of its grid to run (prefix)
+struct LaunchPlan { int n; SubLaunch part[3]; };
+
+static LaunchPlan plan_gemm(int64_t M, int64_t N, int64_t K)
+{
+    LaunchPlan p{};
+    double whole;
+    const TileKind kind = choose_tile(M, N, K, &whole);
+    const TileShape &t = kShapes[kind];
+    const int64_t tm = (M + t.bm - 1) / t.bm, tn = (N + t.bn - 1) / t.bn, tiles = tm * tn;
+    p.n = 1;
+    p.part[0] = {0, M, 0, N, kind, tiles};
+    const int64_t main_tiles = tiles / kCUs * kCUs, rest = tiles - main_tiles;
+    if (main_tiles == 0 || rest == 0) return p;
+    // the remainder in tile order: tail of tile row q (from tile column c) and tile rows q+1 .. tm-1
+    const int64_t q = main_tiles / tn, c = main_tiles % tn;
+    double split = (double)(main_tiles / kCUs) * ((double)(K / BK) * t.step_cost + 8.0) + 4.0;
+    SubLaunch extra[2];
+    int ne = 0;
+    if (c != 0) {
+        const int64_t m_lo = q * t.bm, m_hi = std::min<int64_t>(M, (q + 1) * t.bm);
+        extra[ne++] = {m_lo, m_hi, c * t.bn, N, kTile128, 0};
+    }
+    const int64_t full_from = c == 0 ? q : q + 1;
+    if (full_from < tm) extra[ne++] = {full_from * t.bm, M, 0, N, kTile128, 0};
+    for (int i = 0; i < ne; ++i) {
+        double ci;
+        extra[i].kind = choose_tile(extra[i].m_hi - extra[i].m_lo, extra[i].n_hi - extra[i].n_lo, K, &ci);
+        const TileShape &ts = kShapes[extra[i].kind];
+        extra[i].tiles = ((extra[i].m_hi - extra[i].m_lo + ts.bm - 1) / ts.bm) * ((extra[i].n_hi - extra[i].n_lo + ts.bn - 1) / ts.bn);
+        split += ci;
+    }
+    if (split < whole) {
+        p.part[0].tiles = main_tiles;
+        for (int i = 0; i < ne; ++i) p.part[p.n++] = extra[i];
+    }
+    return p;
 }
 
 static bool tiled_ok(int64_t M, int64_t N, int64_t K)
@@ -792,10 +847,19 @@ bool gemm_is_tiled(int64_t M, int64_t N, int64_t K) { return tiled_ok(M, N, K); 
 
 int gemm_workgroups(int64_t M, int64_t N, int64_t K)
 {
-    switch (choose_tile(M, N, K)) {
-    case kTile256x256: return (int)(((M + 255) / 256) * ((N + 255) / 256));
-    case kTile256x192: return (int)(((M + 255) / 256) * ((N + 191) / 192));
-    default: return (int)(((M + 127) / 128) * ((N + 127) / 128));
+    const LaunchPlan p = plan_gemm(M, N, K);
+    int64_t n = 0;
+    for (int i = 0; i < p.n; ++i) n += p.part[i].tiles;
+    return (int)n;
+}
+
+template <int EPI>
+static hipError_t launch_kind(TileKind kind, const GemmArgs &g, int64_t tiles, hipStream_t s)
+{
+    switch (kind) {
+    case kTile256x256: return launch_regdq<256, 256, EPI>(g, tiles, s);
+    case kTile256x192: return launch_regdq<256, 192, EPI>(g, tiles, s);
+    default: return launch_tiled<128, 128, EPI>(g, tiles, s);
     }
 }
 
@@ -803,24 +867,42 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
                        const uint8_t *codesW, const uint8_t *scalesW, const float *gsW, int64_t M,
                        int64_t N, int64_t K, const GemmEpilogue &ep, int *n_wg, hipStream_t s)
 {
-    GemmArgs g{codesA, scalesA, codesW, scalesW, gsA, gsW, M, N, K, ep};
+    GemmArgs g{codesA, scalesA, codesW, scalesW, gsA, gsW, M, N, K, ep, 0, N, 0};
     if (!tiled_ok(M, N, K)) {
         if (n_wg) *n_wg = 0;
         int64_t total = M * N;
         gemm_generic_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(g);
         return hipGetLastError();
     }
-    if (n_wg) *n_wg = gemm_workgroups(M, N, K);
+    const LaunchPlan plan = plan_gemm(M, N, K);
     const int epi = ep.q_scale ? kEpiQuant : (ep.out_dtype != 0 ? kEpiBF16 : kEpiF32);
-#define NVFP4_LAUNCH(FN, BM_, BN_)                                                          \
-    (epi == kEpiQuant ? FN<BM_, BN_, kEpiQuant>(g, s)                                       \
-                      : (epi == kEpiBF16 ? FN<BM_, BN_, kEpiBF16>(g, s) : FN<BM_, BN_, kEpiF32>(g, s)))
-    switch (choose_tile(M, N, K)) {
-    case kTile256x256: return NVFP4_LAUNCH(launch_regdq, 256, 256);
-    case kTile256x192: return NVFP4_LAUNCH(launch_regdq, 256, 192);
-    default: return NVFP4_LAUNCH(launch_tiled, 128, 128);
+    const int64_t kbytes = K >> 1, kblocks = K >> 4;
+    const int64_t ysize = ep.out_dtype == 0 ? 4 : 2;
+    int wg_total = 0;
+    for (int i = 0; i < plan.n; ++i) {
+        const SubLaunch &p = plan.part[i];
+        GemmArgs a = g;                              // the sub-rectangle [m_lo, m_hi) x [n_lo, n_hi) as a problem of its own
+        a.codesA = codesA + p.m_lo * kbytes;
+        a.scalesA = scalesA + p.m_lo * kblocks;
+        a.codesW = codesW + p.n_lo * kbytes;
+        a.scalesW = scalesW + p.n_lo * kblocks;
+        a.M = p.m_hi - p.m_lo;
+        a.N = p.n_hi - p.n_lo;
+        if (ep.Y) a.ep.Y = (uint8_t *)ep.Y + (p.m_lo * ep.ldy + p.n_lo) * ysize;
+        if (ep.q_codes) {
+            a.ep.q_codes = ep.q_codes + p.m_lo * (N >> 1) + (p.n_lo >> 1);
+            a.ep.q_scales = ep.q_scales + p.m_lo * (N >> 4) + (p.n_lo >> 4);
+        }
+        a.q_pitch = N;
+        a.partial_base = wg_total;
+        hipError_t e = epi == kEpiQuant ? launch_kind<kEpiQuant>(p.kind, a, p.tiles, s)
+                       : (epi == kEpiBF16 ? launch_kind<kEpiBF16>(p.kind, a, p.tiles, s)
+                                          : launch_kind<kEpiF32>(p.kind, a, p.tiles, s));
+        if (e != hipSuccess) return e;
+        wg_total += (int)p.tiles;
     }
-#undef NVFP4_LAUNCH
+    if (n_wg) *n_wg = wg_total;
+    return hipSuccess;
 }
 
 }  // namespace nvfp4
