@@ -44,7 +44,10 @@ namespace nvfp4 {
 constexpr int BK = 64;                 // K elements per pipeline step
 constexpr int ROW_BYTES = BK * 2;      // one staged f16 row
 
-enum { kEpiF32 = 0, kEpiBF16 = 1, kEpiQuant = 2 };   // epilogue: fp32 out, bf16 out, bf16 + fused re-quantization
+// Epilogue variants (kernel template parameter): the kind of output, plus kEpiGelu when the
+// tanh-form GELU is applied (a compile-time choice: as a run-time one the compiler evaluates
+// the activation for every output and selects afterwards).
+enum { kEpiF32 = 0, kEpiBF16 = 1, kEpiQuant = 2, kEpiGelu = 4 };   // fp32 out, bf16 out, bf16 + fused re-quantization
 
 struct GemmArgs {
     const uint8_t *codesA, *scalesA;
@@ -109,10 +112,12 @@ __device__ __forceinline__ int lds_chunk_off(int row, int c) { return row * ROW_
 // through a private 16 KB slab of LDS, 32 output rows at a time: a lane owns (row
 // m, four consecutive n) after the MFMA, and (row m, 16 consecutive bytes) when
 // it stores, so whole rows of the wave tile leave as contiguous runs.
-template <int TM, int TN, int EPI>
+template <int TM, int TN, int EPI_ACT>
 __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const GemmArgs &g, uint8_t *lds,
                                               int64_t wave_m0, int64_t wave_n0)
 {
+    constexpr int EPI = EPI_ACT & 3;
+    constexpr bool GELU = (EPI_ACT & kEpiGelu) != 0;
     constexpr int WN = TN * 32;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lrow = lane & 31, lhalf = lane >> 5;
@@ -144,7 +149,7 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         float y = acc[i][j][rg * 4 + e] * alpha;
-                        if (ep.act == 1) y = gelu_tanh_f32(y);
+                        if constexpr (GELU) y = gelu_tanh_f32(y);
                         o[e] = y;
                     }
                     const int gi = 8 * i + 2 * rg + lhalf;
@@ -173,7 +178,7 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             y[e] = acc[i][j][(2 * rp + s) * 4 + e] * alpha;
-                            if (ep.act == 1) y[e] = gelu_tanh_f32(y[e]);
+                            if constexpr (GELU) y[e] = gelu_tanh_f32(y[e]);
                         }
                         pk[s][0] = pack_bf16x2(y[0], y[1]);
                         pk[s][1] = pack_bf16x2(y[2], y[3]);
@@ -875,7 +880,9 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
         return hipGetLastError();
     }
     const LaunchPlan plan = plan_gemm(M, N, K);
-    const int epi = ep.q_scale ? kEpiQuant : (ep.out_dtype != 0 ? kEpiBF16 : kEpiF32);
+    // (the tiled fp32 output never carries an activation: nvfp4_gemm has none and the fused call emits bf16)
+    const int out_kind = ep.q_scale ? kEpiQuant : (ep.out_dtype != 0 ? kEpiBF16 : kEpiF32);
+    const int epi = out_kind | ((ep.act == 1 && out_kind != kEpiF32) ? kEpiGelu : 0);
     const int64_t kbytes = K >> 1, kblocks = K >> 4;
     const int64_t ysize = ep.out_dtype == 0 ? 4 : 2;
     int wg_total = 0;
@@ -895,9 +902,14 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
         }
         a.q_pitch = N;
         a.partial_base = wg_total;
-        hipError_t e = epi == kEpiQuant ? launch_kind<kEpiQuant>(p.kind, a, p.tiles, s)
-                       : (epi == kEpiBF16 ? launch_kind<kEpiBF16>(p.kind, a, p.tiles, s)
-                                          : launch_kind<kEpiF32>(p.kind, a, p.tiles, s));
+        hipError_t e;
+        switch (epi) {
+        case kEpiF32: e = launch_kind<kEpiF32>(p.kind, a, p.tiles, s); break;
+        case kEpiBF16: e = launch_kind<kEpiBF16>(p.kind, a, p.tiles, s); break;
+        case kEpiBF16 | kEpiGelu: e = launch_kind<kEpiBF16 | kEpiGelu>(p.kind, a, p.tiles, s); break;
+        case kEpiQuant: e = launch_kind<kEpiQuant>(p.kind, a, p.tiles, s); break;
+        default: e = launch_kind<kEpiQuant | kEpiGelu>(p.kind, a, p.tiles, s); break;
+        }
         if (e != hipSuccess) return e;
         wg_total += (int)p.tiles;
     }

@@ -300,6 +300,22 @@ def test_gemm_large_tile_paths(oracle, M, N, K):
     _gemm_case(oracle, ab, wb, f"large tile {M}x{N}x{K}", rows=rows)
 
 
+@pytest.mark.parametrize("K", [128, 256, 384, 448, 640])
+def test_gemm_several_tiles_per_workgroup(oracle, K):
+    """More 256-row tiles than compute units, so a workgroup walks several tiles and starts
+    the copies of the next one while finishing the current one; the K values give every
+    combination of even / odd counts of 64-k steps, 128-k copy steps and 256-k scale groups.
+    One sampled row in every band of 256 rows, plus the band edges."""
+    M, N = 4400, 8192
+    g = np.random.default_rng(K)
+    ab = wl.activation_with_outliers(M, K, 11, 0)
+    wb = wl.normal((N, K), 0.02, 11, 1)
+    bands = np.arange(0, M, 256)
+    rows = np.unique(np.concatenate([bands, np.minimum(bands + g.integers(1, 256, bands.size), M - 1),
+                                     [255, 256, M - 1]])).astype(np.int64)
+    _gemm_case(oracle, ab, wb, f"several tiles per workgroup {M}x{N}x{K}", rows=rows)
+
+
 def test_gemm_subnormal_and_extreme_block_scales(oracle):
     """Raw operands with every E4M3 scale byte 0x00..0x7E (subnormal scales included)."""
     g = np.random.default_rng(99)
