@@ -167,6 +167,11 @@ def measure_rows(nv, wl, torch, np):
     ms = _time_op(nv, torch, nv.OP_KV_QUANT, lambda: nv.nvfp4_kv_quant(kv, out=q, workspace=ws), 20)
     res["kv_quant_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
                                     "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    # the same cache with the Four-over-Six scale search (the variant the paper applies to the cache)
+    ms = _time_op(nv, torch, nv.OP_KV_QUANT_4OVER6, lambda: nv.nvfp4_kv_quant_4over6(kv, out=q, workspace=ws), 20)
+    res["kv_quant_4over6_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
+                                           "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    nv.nvfp4_kv_quant(kv, out=q, workspace=ws)
     ms = _time_op(nv, torch, nv.OP_KV_DEQUANT, lambda: nv.nvfp4_kv_dequant(q, T, H, d, out=back), 20)
     res["kv_dequant_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
                                       "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}

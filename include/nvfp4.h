@@ -65,7 +65,8 @@ enum { NVFP4_OUT_F32 = 0, NVFP4_OUT_BF16 = 1 };
 enum { NVFP4_ACT_NONE = 0, NVFP4_ACT_GELU_TANH = 1 };
 enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2, NVFP4_OP_GEMM = 3,
        NVFP4_OP_KV_DEQUANT = 4,
-       NVFP4_OP_GEMM_ACT_QUANT_GEMM = 5 /* timing only: the GEMM kernel inside nvfp4_gemm_act_quant */ };
+       NVFP4_OP_GEMM_ACT_QUANT_GEMM = 5 /* timing only: the GEMM kernel inside nvfp4_gemm_act_quant */,
+       NVFP4_OP_QUANTIZE_4OVER6 = 6, NVFP4_OP_KV_QUANT_4OVER6 = 7 };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
@@ -84,6 +85,21 @@ enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2
 int nvfp4_quantize(const void *x_bf16, int64_t R, int64_t C, int64_t ld, int block_axis,
                    const float *global_scale_in, nvfp4_tensor *out,
                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Quantizer with the Four-over-Six scale search (Sec. 2.2 "Multi-Shot AR NVFP4
+ * Training"; Appendix "Scale Search NVFP4 Quantization", Eq. 12-13): every
+ * block is encoded twice, with its maximum mapped to 6 and to 4 (block scale =
+ * E4M3 nearest to blockmax / (M * global_scale) for M = 6 and M = 4), and the
+ * encoding with the smaller squared reconstruction error sum_j (x_j - x^_j)^2
+ * is kept; equal errors keep M = 6.  The errors are those of the fp64
+ * evaluation "difference, square, sum in element order, each step rounded".
+ * Arguments, layout, workspace and global scale as nvfp4_quantize with
+ * block_axis 0 (workspace size: NVFP4_OP_QUANTIZE_4OVER6).
+ */
+int nvfp4_quantize_4over6(const void *x_bf16, int64_t R, int64_t C, int64_t ld,
+                          const float *global_scale_in, nvfp4_tensor *out,
+                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Block-scaled FP4 GEMM, FP32 accumulation (Sec. 2.2 / 3.1; Appendix
@@ -124,6 +140,15 @@ int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
  */
 int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * KV-cache quantization with the Four-over-Six scale search, the variant the
+ * paper applies to the cache (Sec. 3.2; Appendix, Eq. 12-13).  Arguments as
+ * nvfp4_kv_quant (workspace size: NVFP4_OP_KV_QUANT_4OVER6); the result is read
+ * back by nvfp4_kv_dequant like any other NVFP4 tensor.
+ */
+int nvfp4_kv_quant_4over6(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
+                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * KV-cache reconstruction (Sec. 3.2): kv_bf16_out[t,h,:] = RN_bf16(code *

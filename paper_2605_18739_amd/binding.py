@@ -17,6 +17,7 @@ _lib = None
 OUT_F32, OUT_BF16 = 0, 1
 ACT_NONE, ACT_GELU_TANH = 0, 1
 OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT, OP_GEMM_ACT_QUANT_GEMM = 0, 1, 2, 3, 4, 5
+OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6 = 6, 7
 
 
 class _CTensor(ctypes.Structure):
@@ -49,6 +50,10 @@ def lib():
         L.nvfp4_kv_quant.argtypes = [vp, i64, i64, i64, tp, vp, sz, vp]
         L.nvfp4_kv_dequant.restype = c.c_int
         L.nvfp4_kv_dequant.argtypes = [tp, vp, i64, i64, i64, vp]
+        L.nvfp4_quantize_4over6.restype = c.c_int
+        L.nvfp4_quantize_4over6.argtypes = [vp, i64, i64, i64, vp, tp, vp, sz, vp]
+        L.nvfp4_kv_quant_4over6.restype = c.c_int
+        L.nvfp4_kv_quant_4over6.argtypes = [vp, i64, i64, i64, tp, vp, sz, vp]
         L.nvfp4_workspace_bytes.restype = sz
         L.nvfp4_workspace_bytes.argtypes = [c.c_int, i64, i64, i64]
         L.nvfp4_status_string.restype = c.c_char_p
@@ -159,6 +164,34 @@ def nvfp4_kv_quant(kv, out=None, workspace=None, stream=None):
     ct = out.c()
     _check(lib().nvfp4_kv_quant(_ptr(kv), T, H, d, ctypes.byref(ct), _ptr(workspace), workspace.numel(),
                                 _stream(stream)))
+    return out
+
+
+def nvfp4_quantize_4over6(x, global_scale_in=None, out=None, workspace=None, stream=None):
+    """x: bf16 [R, C] device tensor with unit stride along C; blocks along C, scale search per block."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1
+    R, C = x.shape
+    if out is None:
+        out = NVFP4Tensor(R, C, x.device)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_QUANTIZE_4OVER6, R, C), x.device)
+    ct = out.c()
+    _check(lib().nvfp4_quantize_4over6(_ptr(x), R, C, x.stride(0), _ptr(global_scale_in), ctypes.byref(ct),
+                                       _ptr(workspace), workspace.numel(), _stream(stream)))
+    return out
+
+
+def nvfp4_kv_quant_4over6(kv, out=None, workspace=None, stream=None):
+    """kv: contiguous bf16 [T, H, d]; scale search per block."""
+    assert kv.dtype == torch.bfloat16 and kv.dim() == 3 and kv.is_contiguous()
+    T, H, d = kv.shape
+    if out is None:
+        out = NVFP4Tensor(T * H, d, kv.device)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_KV_QUANT_4OVER6, T, H, d), kv.device)
+    ct = out.c()
+    _check(lib().nvfp4_kv_quant_4over6(_ptr(kv), T, H, d, ctypes.byref(ct), _ptr(workspace), workspace.numel(),
+                                       _stream(stream)))
     return out
 
 

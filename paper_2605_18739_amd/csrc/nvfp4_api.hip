@@ -58,7 +58,8 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 constexpr size_t kPartialBytes = (size_t)kMaxPartials * sizeof(uint32_t);
 
 int quantize_impl(const void *x, int64_t R, int64_t C, int64_t ld, int block_axis,
-                  const float *gs_in, nvfp4_tensor *out, void *ws, size_t ws_bytes, hipStream_t s)
+                  const float *gs_in, nvfp4_tensor *out, void *ws, size_t ws_bytes, hipStream_t s,
+                  bool scale_search = false)
 {
     if (!x || !out) return NVFP4_ERR_NULL;
     if (int rc = check_tensor(out)) return rc;
@@ -79,7 +80,7 @@ int quantize_impl(const void *x, int64_t R, int64_t C, int64_t ld, int block_axi
     }
     hipError_t e = block_axis == 0
                        ? launch_quantize_rows(xb, R, C, ld, gs_in, partial, n_partial, out->codes,
-                                              out->scales, out->global_scale, s)
+                                              out->scales, out->global_scale, s, scale_search)
                        : launch_quantize_cols(xb, R, C, ld, gs_in, partial, n_partial, out->codes,
                                               out->scales, out->global_scale, s);
     return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
@@ -116,6 +117,26 @@ int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_t
     Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_KV_QUANT);
     return quantize_impl(kv_bf16, T * H, d, d, 0, nullptr, out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(stream));
+}
+
+int nvfp4_quantize_4over6(const void *x_bf16, int64_t R, int64_t C, int64_t ld,
+                          const float *global_scale_in, nvfp4_tensor *out, void *workspace,
+                          size_t workspace_bytes, void *stream)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_QUANTIZE_4OVER6);
+    return quantize_impl(x_bf16, R, C, ld, 0, global_scale_in, out, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(stream), true);
+}
+
+int nvfp4_kv_quant_4over6(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (T <= 0 || H <= 0 || d <= 0) return NVFP4_ERR_SHAPE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_KV_QUANT_4OVER6);
+    return quantize_impl(kv_bf16, T * H, d, d, 0, nullptr, out, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(stream), true);
 }
 
 int nvfp4_kv_dequant(const nvfp4_tensor *in, void *kv_bf16_out, int64_t T, int64_t H, int64_t d,
@@ -219,6 +240,8 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
     switch (op) {
     case NVFP4_OP_QUANTIZE:
     case NVFP4_OP_KV_QUANT:
+    case NVFP4_OP_QUANTIZE_4OVER6:
+    case NVFP4_OP_KV_QUANT_4OVER6:
         return kPartialBytes;
     case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c: bit 0 = caller supplies H, bit 1 = caller supplies the scale
         if (a <= 0 || b <= 0) return 0;

@@ -88,15 +88,16 @@ __device__ __forceinline__ uint32_t e4m3_rne_from_f32(float q)
 constexpr float kBracketLo = 1.0f - 0x1p-20f;
 constexpr float kBracketHi = 1.0f + 0x1p-20f;
 
-// Block scale of Eq. 12 (target 6): E4M3 nearest to bmax / (6 sg), decided exactly.
-__device__ __forceinline__ uint32_t block_scale_exact(float bmax, float sg, float inv_6sg)
+// Block scale of Eq. 12 for target magnitude M (6, or 4 for the second candidate of the
+// scale search): E4M3 nearest to bmax / (M sg), decided exactly.  inv_msg = 1 / (M sg) in fp32.
+__device__ __forceinline__ uint32_t block_scale_exact(float bmax, float sg, float inv_msg, double target = 6.0)
 {
-    float q = bmax * inv_6sg;
+    float q = bmax * inv_msg;
     uint32_t blo = e4m3_rne_from_f32(q * kBracketLo);
     uint32_t bhi = e4m3_rne_from_f32(q * kBracketHi);
     if (__builtin_expect(blo != bhi, 0)) {
         double mid = 0.5 * ((double)e4m3_to_f32(blo) + (double)e4m3_to_f32(bhi));
-        double t = mid * 6.0 * (double)sg;     // <= 5 + 2 + 24 significant bits: exact
+        double t = mid * target * (double)sg;  // <= 5 + 2 + 24 significant bits: exact
         double b = (double)bmax;
         blo = (b > t) ? bhi : ((b < t) ? blo : ((blo & 1u) ? bhi : blo));
     }
@@ -156,6 +157,85 @@ __device__ __forceinline__ void encode_block16(const uint32_t (&w)[8], float sb,
     }
     c0 = l0;
     c1 = l1;
+}
+
+// ---- Four-over-Six scale search (Appendix "Scale Search NVFP4 Quantization", Eq. 12-13) ----
+// Squared reconstruction error of a 16-element block under one candidate encoding, in fp32,
+// plus the sum of |x - x^| that the error bound below needs.  den = s_b * s_g rounded to fp32;
+// the codes carry the sign of x, so the decoded values are subtracted as they are.
+__device__ __forceinline__ void block_error_f32(const uint32_t (&w)[8], uint32_t c0, uint32_t c1, float den,
+                                                float &err, float &sabs)
+{
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    err = 0.0f;
+    sabs = 0.0f;
+#define NVFP4_ERR(W, C, SEL)                                                                  \
+    {                                                                                         \
+        float2v q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(C, 1.0f, SEL);                   \
+        float d0 = __builtin_fmaf(-q.x, den, bf16lo_to_f32(W)), d1 = __builtin_fmaf(-q.y, den, bf16hi_to_f32(W)); \
+        err = __builtin_fmaf(d0, d0, err);                                                    \
+        err = __builtin_fmaf(d1, d1, err);                                                    \
+        sabs += fabsf(d0) + fabsf(d1);                                                        \
+    }
+    NVFP4_ERR(w[0], c0, 0) NVFP4_ERR(w[1], c0, 1) NVFP4_ERR(w[2], c0, 2) NVFP4_ERR(w[3], c0, 3)
+    NVFP4_ERR(w[4], c1, 0) NVFP4_ERR(w[5], c1, 1) NVFP4_ERR(w[6], c1, 2) NVFP4_ERR(w[7], c1, 3)
+#undef NVFP4_ERR
+}
+
+// The same error as the fp64 definition evaluates it: every difference |x| - m s_b s_g taken
+// once in fp64, squared, and summed in element order, each operation rounded on its own (no
+// fused multiply-add), so that "is candidate 4 strictly better" has one answer everywhere.
+__device__ __forceinline__ double block_error_f64(const uint32_t (&w)[8], uint32_t c0, uint32_t c1, float sb, float sg)
+{
+    const double den = (double)sb * (double)sg;     // exact
+    double err = 0.0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const uint32_t ww = w[j >> 1];
+        const double a = (double)fabsf((j & 1) ? bf16hi_to_f32(ww) : bf16lo_to_f32(ww));
+        const uint32_t idx = (((j < 8) ? c0 : c1) >> (4 * (j & 7))) & 7u;
+        const double m = idx < 4u ? 0.5 * (double)idx : (idx == 4u ? 2.0 : (idx == 5u ? 3.0 : (idx == 6u ? 4.0 : 6.0)));
+        const double d = __dsub_rn(a, __dmul_rn(m, den));
+        err = __dadd_rn(err, __dmul_rn(d, d));
+    }
+    return err;
+}
+
+// Scale search for one block: encode with the block maximum mapped to 6 and to 4, keep the
+// encoding with the strictly smaller squared error (equal errors keep 6).  The fp32 errors
+// decide whenever they differ by more than their own uncertainty; otherwise fp64 does.
+__device__ __forceinline__ void encode_block16_4over6(const uint32_t (&w)[8], float bmax, float sg, float inv_6sg,
+                                                      float inv_4sg, uint32_t &sbyte, uint32_t &c0, uint32_t &c1)
+{
+    const uint32_t s6 = block_scale_exact(bmax, sg, inv_6sg, 6.0);
+    const uint32_t s4 = block_scale_exact(bmax, sg, inv_4sg, 4.0);
+    const float sb6 = e4m3_to_f32(s6), sb4 = e4m3_to_f32(s4);
+    uint32_t a0, a1;
+    encode_block16(w, sb6, sg, a0, a1);
+    sbyte = s6;
+    c0 = a0;
+    c1 = a1;
+    if (s4 == s6) return;                          // same scale, same codes, same error (zero blocks, saturated scales)
+    uint32_t b0, b1;
+    encode_block16(w, sb4, sg, b0, b1);
+    const float den6 = sb6 * sg, den4 = sb4 * sg;
+    float e6, t6, e4, t4;
+    block_error_f32(w, a0, a1, den6, e6, t6);
+    block_error_f32(w, b0, b1, den4, e4, t4);
+    // |d~ - d| <= 2^-24 (|x| + |x^| + 6 den) < u; |d~^2 - d^2| <= u (2 |d~| + u); sixteen fused
+    // accumulations add at most 2^-19 of the sum
+    const float u6 = 0x1p-22f * (bmax + 6.0f * den6), u4 = 0x1p-22f * (bmax + 6.0f * den4);
+    const float r6 = u6 * (2.0f * t6 + 16.0f * u6) + 0x1p-19f * e6;
+    const float r4 = u4 * (2.0f * t4 + 16.0f * u4) + 0x1p-19f * e4;
+    bool pick4;
+    if (e4 + r4 < e6 - r6) pick4 = true;
+    else if (e4 - r4 > e6 + r6) pick4 = false;
+    else pick4 = block_error_f64(w, b0, b1, sb4, sg) < block_error_f64(w, a0, a1, sb6, sg);
+    if (pick4) {
+        sbyte = s4;
+        c0 = b0;
+        c1 = b1;
+    }
 }
 
 // Round a non-negative exact product held in a double to bf16 once (nearest

@@ -10,9 +10,10 @@ constexpr int kMaxPartials = 1024;   // workgroups of the amax pass = partial ma
 
 hipError_t launch_amax(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t *partial,
                        int *n_partial, hipStream_t s);
+// scale_search: the Four-over-Six candidate search per block (Appendix, Eq. 12-13)
 hipError_t launch_quantize_rows(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
                                 const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
-                                float *gs_out, hipStream_t s);
+                                float *gs_out, hipStream_t s, bool scale_search = false);
 hipError_t launch_quantize_cols(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
                                 const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
                                 float *gs_out, hipStream_t s);

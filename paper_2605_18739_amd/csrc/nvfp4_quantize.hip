@@ -83,8 +83,9 @@ __device__ __forceinline__ float resolve_global_scale(const float *gs_in, const 
 // --------------------------------------------------------------------------
 // Pass 2, blocks along the contiguous axis: one lane per 16-element block
 // (two 128-bit loads, one 64-bit code store, one scale byte).
+// SEARCH: the Four-over-Six scale search of Eq. 12-13 instead of the plain max -> 6 rule.
 // --------------------------------------------------------------------------
-template <bool CONTIG>
+template <bool CONTIG, bool SEARCH = false>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
                                                             int64_t C, int64_t ld,
                                                             const float *__restrict__ gs_in,
@@ -96,6 +97,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
     __shared__ uint32_t lds4[4];
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
     const float inv_6sg = 1.0f / (6.0f * sg);
+    const float inv_4sg = 1.0f / (4.0f * sg);
     const int64_t nb_row = C >> 4;
     const int64_t nblk = R * nb_row;
     const int64_t stride = (int64_t)gridDim.x * 256;
@@ -126,9 +128,13 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
                 float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
-                uint32_t sbyte = block_scale_exact(bmax, sg, inv_6sg);
-                uint32_t c0, c1;
-                encode_block16(w, e4m3_to_f32(sbyte), sg, c0, c1);
+                uint32_t sbyte, c0, c1;
+                if constexpr (SEARCH) {
+                    encode_block16_4over6(w, bmax, sg, inv_6sg, inv_4sg, sbyte, c0, c1);
+                } else {
+                    sbyte = block_scale_exact(bmax, sg, inv_6sg);
+                    encode_block16(w, e4m3_to_f32(sbyte), sg, c0, c1);
+                }
                 uint2v cc = {c0, c1};
 #if NVFP4_Q_PLAIN_STORE
                 *(uint2v *)(codes + (g << 3)) = cc;
@@ -307,10 +313,17 @@ hipError_t launch_amax(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint
 
 hipError_t launch_quantize_rows(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
                                 const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
-                                float *gs_out, hipStream_t s)
+                                float *gs_out, hipStream_t s, bool scale_search)
 {
     int grid = grid_for(R * (C >> 4), NVFP4_Q_GRID);
-    if (ld == C)
+    if (scale_search) {
+        if (ld == C)
+            quantize_rows_kernel<true, true><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes,
+                                                                  scales, gs_out);
+        else
+            quantize_rows_kernel<false, true><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes,
+                                                                   scales, gs_out);
+    } else if (ld == C)
         quantize_rows_kernel<true><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes,
                                                         scales, gs_out);
     else

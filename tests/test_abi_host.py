@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     L = nv.lib()
     names = _declared_symbols()
     assert {"nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_act_quant", "nvfp4_kv_quant",
-            "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string"} <= set(names)
+            "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string",
+            "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -90,6 +91,12 @@ def test_gemm_and_kv_reject_bad_arguments_on_the_host():
     assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w16), 1, None, ctypes.byref(out), None, ws, 16, None) == -4
     kv = ctypes.c_void_p(0x60000)
     t = _t(rows=6, K=32)
+    # the scale-search variants validate like their plain counterparts
+    assert L.nvfp4_kv_quant_4over6(kv, 0, 3, 32, ctypes.byref(t), ws, 4096, None) == -2
+    assert L.nvfp4_kv_quant_4over6(kv, 2, 3, 32, ctypes.byref(t), None, 0, None) == -4
+    assert L.nvfp4_quantize_4over6(None, 6, 32, 32, None, ctypes.byref(t), ws, 4096, None) == -1
+    assert L.nvfp4_quantize_4over6(kv, 6, 32, 16, None, ctypes.byref(t), ws, 4096, None) == -2     # ld < C
+    assert L.nvfp4_quantize_4over6(kv, 6, 32, 32, None, ctypes.byref(t), ws, 16, None) == -4
     assert L.nvfp4_kv_quant(kv, 0, 3, 32, ctypes.byref(t), ws, 4096, None) == -2
     assert L.nvfp4_kv_quant(kv, 2, 3, 24, ctypes.byref(_t(rows=6, K=24)), ws, 4096, None) == -2
     assert L.nvfp4_kv_dequant(ctypes.byref(t), None, 2, 3, 32, None) == -1

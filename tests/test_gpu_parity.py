@@ -235,6 +235,65 @@ def test_gemm_backward_operands(oracle):
     assert_gemm_close(nv.nvfp4_gemm(g_dyt, g_xt).cpu().numpy(), Y, S, "wgrad")
 
 
+# ------------------------------------------------------------ four over six
+
+def _assert_search_equal(oracle, xb, what, gs=None):
+    say(f"[4over6] {what} {xb.shape}")
+    want = oracle.quantize(xb, four_over_six=True, global_scale_in=gs)
+    gst = None if gs is None else torch.tensor([gs], dtype=torch.float32, device="cuda")
+    got = nv.nvfp4_quantize_4over6(dev_bf16(xb), global_scale_in=gst)
+    assert_q_equal(got, want, what)
+    return want
+
+
+def test_quantize_four_over_six(oracle):
+    """Scale search (Appendix, Eq. 12-13): bytes identical to the oracle's, on data where the
+    choice goes both ways, on ragged shapes, on tie-heavy and degenerate blocks."""
+    cfg = wl.config2(seed=3, M=300)
+    q = _assert_search_equal(oracle, cfg["A"], "activations with outliers")
+    plain = oracle.quantize(cfg["A"])
+    changed = (q.scales != plain.scales).mean()
+    say(f"        blocks that switch to the 4-target scale: {changed:.3f}")
+    assert 0.05 < changed < 0.95
+    _assert_search_equal(oracle, wl.normal((257, 272), 0.02, 3, 1), "small weights, ragged")
+    _assert_search_equal(oracle, wl.normal((64, 4096), 1e-3, 3, 2), "gradients")
+    _assert_search_equal(oracle, wl.normal((1, 16), 1.0, 3, 3), "one block")
+    _assert_search_equal(oracle, cfg["A"], "given scale", gs=0.01)
+    g = np.random.default_rng(46)
+    # blocks where both candidates reconstruct equally well (a lone maximum, exact grids, zeros):
+    # the decision falls to the exact comparison, and equality keeps the 6-target scale
+    x = np.zeros((64, 256), np.float32)
+    x[:, ::16] = (g.integers(1, 200, size=(64, 16)) * 0.25).astype(np.float32)          # one non-zero per block
+    x[5] = 0.0
+    x[6, :128] = np.tile(np.array([0, .5, 1, 1.5, 2, 3, 4, 6, -6, -4, -3, -2, -1.5, -1, -.5, 0], np.float32), 8)
+    x[0, 0] = 2688.0
+    _assert_search_equal(oracle, wl.to_bf16_bits(x), "equal-error blocks")
+    # values on a coarse grid: many exact ties between the two candidates' errors
+    y = (g.integers(-12, 13, size=(128, 512)) * 0.5).astype(np.float32)
+    y[0, 0] = 2688.0 / 64
+    _assert_search_equal(oracle, wl.to_bf16_bits(y), "coarse grid")
+    _assert_search_equal(oracle, wl.to_bf16_bits(np.zeros((16, 64), np.float32)), "all zero")
+
+
+def test_kv_quant_four_over_six(oracle):
+    T, H, d = 129, 24, 128
+    kb = wl.kv_tensor(T, H, d, 4, 0)
+    say(f"[4over6] KV {kb.shape}")
+    want = oracle.quantize(kb.reshape(T * H, d), four_over_six=True)
+    kv = dev_bf16(kb.reshape(T * H, d)).reshape(T, H, d)
+    got = nv.nvfp4_kv_quant_4over6(kv)
+    assert_q_equal(got, want, "KV 4over6")
+    # and the cache reads back through the ordinary dequantizer, bit for bit
+    back = nv.nvfp4_kv_dequant(got, T, H, d)
+    assert (nv.bits_from_bf16(back).reshape(T * H, d) == oracle.dequant_bf16(want)).all()
+    # the search never loses to the plain rule (squared error per block, fp64)
+    x = wl.bf16_bits_to_f32(kb.reshape(T * H, d)).astype(np.float64)
+    e46 = ((x - oracle.dequant_f64(want)) ** 2).sum()
+    e6 = ((x - oracle.dequant_f64(oracle.quantize(kb.reshape(T * H, d)))) ** 2).sum()
+    say(f"        squared error with search / plain: {e46 / e6:.4f}")
+    assert e46 <= e6
+
+
 # --------------------------------------------------- fused activation + quantize
 
 def _act_quant_case(oracle, M, N, K, given_scale, what):
@@ -396,6 +455,15 @@ def test_full_size_kv_cache_config4(oracle):
         assert 0.02 < rel < 0.2
         # storage: 9/16 byte per element against 2 in bf16
         assert (gq.codes.numel() + gq.scales.numel()) * 16 == 9 * T * H * d
+    say("[config4] K with the four-over-six scale search")
+    oq = oracle.quantize(cfg["K"].reshape(T * H, d), four_over_six=True)
+    gq = nv.nvfp4_kv_quant_4over6(dev_bf16(cfg["K"]))
+    assert_q_equal(gq, oq, "K 4over6")
+    back = nv.bits_from_bf16(nv.nvfp4_kv_dequant(gq, T, H, d)).reshape(T * H, d)
+    x = wl.bf16_bits_to_f32(cfg["K"]).astype(np.float64).reshape(T * H, d)
+    rel46 = np.linalg.norm(x - wl.bf16_bits_to_f32(back).astype(np.float64)) / np.linalg.norm(x)
+    say(f"        round-trip relative Frobenius error with the search {rel46:.4f}")
+    assert rel46 < rel          # rel: the plain rule on V above; K and V are drawn alike
 
 
 def test_full_size_training_triplet_config5(oracle):
