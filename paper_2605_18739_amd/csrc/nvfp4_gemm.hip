@@ -481,7 +481,7 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
 // one chunk -- what a fragment read touches per LDS cycle -- fall on distinct
 // banks.
 // ============================================================================
-constexpr int kCodeStages = 2;         // LDS ring of 128-k code stages
+constexpr int kCodeStages = 4;         // LDS ring of 128-k code stages: copies run three copy steps ahead, one barrier per two
 constexpr int kScaleSteps = 2;         // copy steps covered by one 16-byte run of scales
 
 // s_waitcnt vmcnt(N) alone: vmcnt sits in bits 3:0 and 15:14, expcnt (6:4) and
@@ -546,11 +546,11 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
         const int64_t gr = isA ? m0 + srow : n0 + (srow - BM);
         svoff[x] = (srow < ROWS && gr < (isA ? g.M : g.N)) ? (int)(gr * kblocks) : 0x7FF00000;
     }
-    auto copy_codes = [&](int gs) {                 // copy step gs -> code stage gs & 1
+    auto copy_codes = [&](int gs) {                 // copy step gs -> code stage gs % kCodeStages
 #pragma unroll
         for (int x = 0; x < UPW; ++x) {
             const int u = wave + 4 * x;
-            uint8_t *dst = lds + (gs & 1) * CODE_STAGE + u * 1024;
+            uint8_t *dst = lds + (gs & (kCodeStages - 1)) * CODE_STAGE + u * 1024;
             if (u * 16 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rcA, (lds_ptr_t)dst, 16, cvoff[x] + gs * 64, 0, 0, 0);
             else __builtin_amdgcn_raw_ptr_buffer_load_lds(rcW, (lds_ptr_t)dst, 16, cvoff[x] + gs * 64, 0, 0, 0);
         }
@@ -580,7 +580,7 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     uint32_t scf[2][NF];          // ... and the same as a pair of f16
     auto read_step = [&](int rs, int set) {         // register step rs = 2 gs + half
         const int gs = rs >> 1, half = rs & 1;
-        const uint8_t *cbase = lds + (gs & 1) * CODE_STAGE + code_lane[half];
+        const uint8_t *cbase = lds + (gs & (kCodeStages - 1)) * CODE_STAGE + code_lane[half];
         const uint8_t *sbase = lds + SCALE_BASE + ((gs >> 1) & 1) * SCALE_STAGE + (gs & 1) * 8 + half * 4 + scale_lane;
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
@@ -624,11 +624,14 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
         scf[set][f] = x;
     };
 
-    // ---- prologue: copy steps 0 and 1 in flight, register step 0 read and expanded
+    // ---- prologue: copy steps 0, 1, 2 started, 0 and 1 awaited (step 1 is first read in an
+    // iteration without a barrier), register step 0 read and expanded
     copy_scales(0);
     copy_codes(0);
     copy_codes(min(1, GT - 1));
-    wait_vmcnt_le<UPW>();                           // scales and copy step 0 have landed
+    copy_scales(min(2, GT - 1) >> 1);
+    copy_codes(min(2, GT - 1));
+    wait_vmcnt_le<UPW + SUPW>();                    // everything but copy step 2 and its scales has landed
     NVFP4_COMPILER_FENCE();
     __builtin_amdgcn_s_barrier();
     NVFP4_COMPILER_FENCE();
@@ -639,14 +642,18 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     for (int pc = 0; pc < 2 * NF; ++pc) expand_piece(0, 0, pc);
 
     // ---- main loop over register steps.  Iteration rs reads register step rs+1 into
-    // the other register set and multiplies step rs.  When rs+1 opens a new copy step
-    // (rs odd) its copies -- issued two iterations earlier -- are awaited and a
-    // barrier makes them visible; the stage of copy step rs/2, which every wave has
-    // finished reading by then, is refilled with copy step rs/2 + 2.
-    auto iteration = [&](int rs, auto half_c) {
-        constexpr int half = decltype(half_c)::value;      // rs & 1; also the register set of step rs
+    // the other register set and multiplies step rs.  Copy step g lives in stage g mod 4
+    // and is started three copy steps ahead: every odd iteration rs starts copy step
+    // rs/2 + 3 into the stage of copy step rs/2 - 1.  Only every second odd iteration
+    // (rs = 3 mod 4) waits for this wave's copies and joins a barrier: that makes copy
+    // steps rs/2 + 1 and rs/2 + 2 visible (the second one is first read two iterations
+    // later, without a barrier), and no wave can be more than one barrier ahead of
+    // another, which is what keeps a stage from being refilled while it is still read.
+    auto iteration = [&](int rs, auto quarter_c) {
+        constexpr int quarter = decltype(quarter_c)::value;    // rs & 3
+        constexpr int half = quarter & 1;                      // also the register set of step rs
         constexpr int set = half;
-        if constexpr (half == 1) {
+        if constexpr (quarter == 3) {
 #if !(NVFP4_EXPERIMENT & 1)
             wait_vmcnt_le<0>();
 #endif
@@ -659,8 +666,8 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
         read_step(rs + 1, set ^ 1);
         if constexpr (half == 1) {
 #if !(NVFP4_EXPERIMENT & 4)
-            const int ng = (rs >> 1) + 2;                   // copy step to start (clamped at the end of K)
-            if ((ng & 1) == 0) copy_scales(min(ng, GT - 1) >> 1);
+            const int ng = (rs >> 1) + 3;                   // copy step to start (clamped at the end of K)
+            if constexpr (quarter == 3) copy_scales(min(ng, GT - 1) >> 1);   // ng is even here: a new scale group
             copy_codes(min(ng, GT - 1));
 #endif
         }
@@ -688,14 +695,20 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
         }
     };
     {
-        using H0 = std::integral_constant<int, 0>;
-        using H1 = std::integral_constant<int, 1>;
+        using Q0 = std::integral_constant<int, 0>;
+        using Q1 = std::integral_constant<int, 1>;
+        using Q2 = std::integral_constant<int, 2>;
+        using Q3 = std::integral_constant<int, 3>;
         int rs = 0;
-        for (; rs + 1 < KT; rs += 2) {
-            iteration(rs, H0{});
-            iteration(rs + 1, H1{});
+        for (; rs + 3 < KT; rs += 4) {
+            iteration(rs, Q0{});
+            iteration(rs + 1, Q1{});
+            iteration(rs + 2, Q2{});
+            iteration(rs + 3, Q3{});
         }
-        if (rs < KT) iteration(rs, H0{});
+        if (rs < KT) iteration(rs, Q0{});
+        if (rs + 1 < KT) iteration(rs + 1, Q1{});
+        if (rs + 2 < KT) iteration(rs + 2, Q2{});
     }
     wait_vmcnt_le<0>();                            // no copy may still be writing LDS when the epilogue reuses it
     __syncthreads();
