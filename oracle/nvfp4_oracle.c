@@ -290,6 +290,47 @@ void nvfp4o_dequant_bf16(const uint8_t *codes, const uint8_t *scales, float glob
     }
 }
 
+/* ------------------------------------------------------- K-smoothing (KV) */
+
+/* K-smoothing (Sec. 3.2, Eq. 6): every cached key row (one token, one head) has its mean
+ * over the d features removed before it is quantized.  The paper gives the real-number
+ * formula only; the reading taken: the row sum is accumulated in fp64 in element order and
+ * divided by d in fp64 (both exact for any realistic cache row: d a power of two, 8-bit
+ * significands spread over less than 2^40), mean = RN_bf16(that); the smoothed element is
+ * RN_bf16(x_j - mean) with the difference taken in fp64 (exact under the same proviso).
+ * The means are part of the cache entry: reconstruction adds them back. */
+void nvfp4o_kv_smooth(const uint16_t *x, int64_t rows, int64_t d, uint16_t *mean_out,
+                      uint16_t *xbar_out)
+{
+    int64_t r;
+#pragma omp parallel for schedule(static)
+    for (r = 0; r < rows; ++r) {
+        double sum = 0.0, mu;
+        int64_t j;
+        for (j = 0; j < d; ++j) sum += nvfp4o_bf16_decode(x[r * d + j]);
+        mean_out[r] = nvfp4o_bf16_rne(sum / (double)d);
+        mu = nvfp4o_bf16_decode(mean_out[r]);
+        for (j = 0; j < d; ++j)
+            xbar_out[r * d + j] = nvfp4o_bf16_rne(nvfp4o_bf16_decode(x[r * d + j]) - mu);
+    }
+}
+
+/* Reconstruction of a smoothed key cache: RN_bf16(x^_j + mean), x^_j the exact value of
+ * Eq. 2 and the sum taken once in fp64. */
+void nvfp4o_dequant_bf16_smooth(const uint8_t *codes, const uint8_t *scales, float global_scale,
+                                const uint16_t *mean, int64_t rows, int64_t K, uint16_t *out)
+{
+    int64_t r;
+#pragma omp parallel for schedule(static)
+    for (r = 0; r < rows; ++r) {
+        double mu = nvfp4o_bf16_decode(mean[r]);
+        int64_t k;
+        for (k = 0; k < K; ++k)
+            out[r * K + k] = nvfp4o_bf16_rne(
+                dequant_elem(codes, scales, (double)global_scale, K, r, k) + mu);
+    }
+}
+
 /* ----------------------------------------------------------------- GEMM */
 
 /* Y[m,n] = sum_k A^[m,k] W^[n,k] over the dequantized operands, in fp64, and

@@ -45,6 +45,14 @@ void nvfp4o_dequant_f64(const uint8_t *codes, const uint8_t *scales, float globa
 void nvfp4o_dequant_bf16(const uint8_t *codes, const uint8_t *scales, float global_scale,
                          int64_t rows, int64_t K, uint16_t *out);
 
+/* K-smoothing of the key cache (Sec. 3.2, Eq. 6): x bf16 [rows, d] -> per-row mean (bf16) and
+ * the smoothed rows RN_bf16(x - mean) (bf16), which are then quantized like any tensor;
+ * reconstruction RN_bf16(x^ + mean). */
+void nvfp4o_kv_smooth(const uint16_t *x, int64_t rows, int64_t d, uint16_t *mean_out,
+                      uint16_t *xbar_out);
+void nvfp4o_dequant_bf16_smooth(const uint8_t *codes, const uint8_t *scales, float global_scale,
+                                const uint16_t *mean, int64_t rows, int64_t K, uint16_t *out);
+
 /* Y[i,n] = sum_k A^[rows[i],k] W^[n,k]; S = same with absolute values (may be NULL).
  * rows == NULL: all M rows. */
 void nvfp4o_gemm(const uint8_t *codesA, const uint8_t *scalesA, float gsA,

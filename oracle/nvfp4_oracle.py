@@ -55,6 +55,10 @@ def lib():
         L.nvfp4o_dequant_f64.argtypes = [u8p, u8p, c.c_float, i64, i64, f64p]
         L.nvfp4o_dequant_bf16.restype = None
         L.nvfp4o_dequant_bf16.argtypes = [u8p, u8p, c.c_float, i64, i64, u16p]
+        L.nvfp4o_kv_smooth.restype = None
+        L.nvfp4o_kv_smooth.argtypes = [u16p, i64, i64, u16p, u16p]
+        L.nvfp4o_dequant_bf16_smooth.restype = None
+        L.nvfp4o_dequant_bf16_smooth.argtypes = [u8p, u8p, c.c_float, u16p, i64, i64, u16p]
         L.nvfp4o_gemm.restype = None
         L.nvfp4o_gemm.argtypes = [u8p, u8p, c.c_float, u8p, u8p, c.c_float, i64, i64, i64,
                                   i64p, i64, f64p, f64p]
@@ -124,8 +128,26 @@ def dequant_f64(q):
     return out
 
 
-def dequant_bf16(q):
+def kv_smooth(x_bits):
+    """K-smoothing (Sec. 3.2, Eq. 6): x_bits uint16 [rows, d] -> (mean bits [rows], smoothed bits [rows, d])."""
+    x = _u16(x_bits)
+    rows, d = x.shape
+    mean = np.empty(rows, np.uint16)
+    xbar = np.empty((rows, d), np.uint16)
+    lib().nvfp4o_kv_smooth(_p(x, ctypes.c_uint16), rows, d, _p(mean, ctypes.c_uint16), _p(xbar, ctypes.c_uint16))
+    return mean, xbar
+
+
+def dequant_bf16(q, mean_bits=None):
     out = np.empty((q.rows, q.K), np.uint16)
+    if mean_bits is not None:
+        mean = np.ascontiguousarray(mean_bits, dtype=np.uint16)
+        assert mean.shape == (q.rows,)
+        lib().nvfp4o_dequant_bf16_smooth(_p(np.ascontiguousarray(q.codes), ctypes.c_uint8),
+                                         _p(np.ascontiguousarray(q.scales), ctypes.c_uint8),
+                                         ctypes.c_float(float(q.global_scale)), _p(mean, ctypes.c_uint16),
+                                         q.rows, q.K, _p(out, ctypes.c_uint16))
+        return out
     lib().nvfp4o_dequant_bf16(_p(np.ascontiguousarray(q.codes), ctypes.c_uint8),
                               _p(np.ascontiguousarray(q.scales), ctypes.c_uint8),
                               ctypes.c_float(float(q.global_scale)), q.rows, q.K,

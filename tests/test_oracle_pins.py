@@ -440,3 +440,89 @@ def test_four_over_six_equal_error_keeps_six(oracle):
     x[0, 16] = 6.0
     q = oracle.quantize(bits(x), four_over_six=True)
     assert q.scales[0, 1] == 0x38 and (q.codes[0, 8] & 7) == 7
+
+
+# ------------------------------------------------------------ K-smoothing (KV)
+
+def _bf16_of_exact(v):
+    """RNE to bf16 of a value that float32 holds exactly, by torch's own cast."""
+    t = torch.tensor([v], dtype=torch.float64)
+    assert float(t.to(torch.float32)[0]) == v
+    return int(t.to(torch.float32).to(torch.bfloat16).view(torch.int16)[0]) & 0xFFFF
+
+
+def test_kv_smooth_closed_forms(oracle):
+    """Sec. 3.2, Eq. 6: the row mean over the features is removed."""
+    d = 32
+    # (a) a constant row is its own mean: nothing is left to quantize, and it comes back exactly
+    x = np.tile(np.array([[1.5], [-0.375], [96.0], [0.0]], np.float32), (1, d))
+    mean, xbar = oracle.kv_smooth(bits(x))
+    assert (mean == bits(x)[:, 0]).all() and (xbar & 0x7FFF == 0).all()
+    q = oracle.quantize(xbar, four_over_six=True)
+    assert (q.codes & 0x77 == 0).all()
+    assert (oracle.dequant_bf16(q, mean) == bits(x)).all()
+    # (b) antisymmetric rows have mean zero: smoothing changes nothing
+    g = np.random.default_rng(5)
+    h = wl.bf16_bits_to_f32(wl.to_bf16_bits(g.standard_normal((6, d // 2)).astype(np.float32)))
+    y = np.concatenate([h, -h], axis=1)
+    mean, ybar = oracle.kv_smooth(bits(y))
+    assert (mean & 0x7FFF == 0).all() and (ybar == bits(y)).all()
+    # (c) shifting a row by a constant moves the mean and leaves the smoothed row alone
+    #     (small integers: every value, sum and difference is exact in bf16)
+    z = g.integers(-20, 21, size=(5, d)).astype(np.float32)
+    z[:, 0] -= z.sum(axis=1) % d                      # make every row sum a multiple of d: integer means
+    m0, z0 = oracle.kv_smooth(bits(z))
+    m1, z1 = oracle.kv_smooth(bits(z + 7.0))
+    assert (z0 == z1).all()
+    assert (wl.bf16_bits_to_f32(m1) - wl.bf16_bits_to_f32(m0) == 7.0).all()
+    assert (wl.bf16_bits_to_f32(m0) == z.sum(axis=1) / d).all()
+    assert (wl.bf16_bits_to_f32(z0) == z - (z.sum(axis=1) / d)[:, None]).all()
+
+
+def test_kv_smooth_against_rational_arithmetic(oracle):
+    """Mean and smoothed elements against exact rationals rounded by torch's bf16 cast."""
+    g = np.random.default_rng(6)
+    d = 16
+    xb = wl.to_bf16_bits((g.standard_normal((40, d)) * 3).astype(np.float32))
+    x = wl.bf16_bits_to_f32(xb)
+    mean, xbar = oracle.kv_smooth(xb)
+    for r in range(x.shape[0]):
+        s = sum(Fraction(float(v)) for v in x[r]) / d
+        sf = float(s)                                  # d = 16 and 8-bit values within 2^10: exact, and exact in fp32
+        assert Fraction(sf) == s
+        assert mean[r] == _bf16_of_exact(sf)
+        mu = Fraction(float(wl.bf16_bits_to_f32(mean[r:r + 1])[0]))
+        for j in range(d):
+            df = float(Fraction(float(x[r, j])) - mu)
+            assert xbar[r, j] == _bf16_of_exact(df)
+
+
+def test_kv_smooth_reconstruction(oracle):
+    """RN_bf16(x^ + mean): the nearest bf16 to the exact rational sum of the independently
+    decoded value and the mean; smoothing shrinks the error on rows with a large common offset."""
+    g = np.random.default_rng(7)
+    rows, d = 48, 128
+    x = g.standard_normal((rows, d)).astype(np.float32) + g.uniform(-8, 8, size=(rows, 1)).astype(np.float32)
+    xb = wl.to_bf16_bits(x)
+    mean, xbar = oracle.kv_smooth(xb)
+    q = oracle.quantize(xbar, four_over_six=True)
+    got = oracle.dequant_bf16(q, mean)
+    deq = _py_dequant(q)
+    mu = wl.bf16_bits_to_f32(mean).astype(np.float64)
+    o = wl.bf16_bits_to_f32(got).astype(np.float64)
+    nb = lambda b: Fraction(float(wl.bf16_bits_to_f32(np.array([b], np.uint16))[0]))
+    for r in range(rows):
+        for k in range(r % 5, d, 5):
+            exact = Fraction(deq[r, k]) + Fraction(mu[r])       # exact rational sum of the two exact terms
+            b = int(got[r, k])
+            e = abs(exact - Fraction(o[r, k]))
+            up = nb(b + 1)
+            dn = nb(b - 1) if b & 0x7FFF else -up
+            assert e <= abs(exact - up) and e <= abs(exact - dn)
+            if e == abs(exact - up) or e == abs(exact - dn):
+                assert b % 2 == 0                               # a tie went to the even significand
+    xf = wl.bf16_bits_to_f32(xb).astype(np.float64)
+    e_smooth = np.linalg.norm(xf - wl.bf16_bits_to_f32(got))
+    plain = oracle.quantize(xb, four_over_six=True)
+    e_plain = np.linalg.norm(xf - wl.bf16_bits_to_f32(oracle.dequant_bf16(plain)))
+    assert e_smooth < 0.8 * e_plain
