@@ -171,6 +171,26 @@ def measure_rows(nv, wl, torch, np):
     ms = _time_op(nv, torch, nv.OP_KV_QUANT_4OVER6, lambda: nv.nvfp4_kv_quant_4over6(kv, out=q, workspace=ws), 20)
     res["kv_quant_4over6_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
                                            "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    # keys as the paper caches them: row means removed (K-smoothing), then the scale search
+    mean = torch.empty(T * H, dtype=torch.bfloat16, device=dev)
+    ms = _time_op(nv, torch, nv.OP_KV_QUANT_K, lambda: nv.nvfp4_kv_quant_k(kv, out=q, row_mean=mean, workspace=ws), 20)
+    res["kv_quant_k_smooth_4over6_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
+                                                    "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    # gathered reconstruction of a window of 21 chunks of 880 tokens (one launch), plain and smoothed
+    Tc = 880
+    chunks_v, chunks_k = [], []
+    for c in range(T // Tc):
+        part = kv[c * Tc:(c + 1) * Tc]
+        chunks_v.append((nv.nvfp4_kv_quant(part), None, Tc))
+        qk, mk = nv.nvfp4_kv_quant_k(part)
+        chunks_k.append((qk, mk, Tc))
+    ms = _time_op(nv, torch, nv.OP_KV_DEQUANT_GATHER, lambda: nv.nvfp4_kv_dequant_gather(chunks_v, H, d, out=back), 20)
+    res["kv_dequant_gather_21x880x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
+                                              "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    ms = _time_op(nv, torch, nv.OP_KV_DEQUANT_GATHER, lambda: nv.nvfp4_kv_dequant_gather(chunks_k, H, d, out=back), 20)
+    res["kv_dequant_gather_smoothed_21x880x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
+                                                       "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    del chunks_v, chunks_k, mean
     nv.nvfp4_kv_quant(kv, out=q, workspace=ws)
     ms = _time_op(nv, torch, nv.OP_KV_DEQUANT, lambda: nv.nvfp4_kv_dequant(q, T, H, d, out=back), 20)
     res["kv_dequant_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),

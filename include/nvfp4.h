@@ -66,7 +66,8 @@ enum { NVFP4_ACT_NONE = 0, NVFP4_ACT_GELU_TANH = 1 };
 enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2, NVFP4_OP_GEMM = 3,
        NVFP4_OP_KV_DEQUANT = 4,
        NVFP4_OP_GEMM_ACT_QUANT_GEMM = 5 /* timing only: the GEMM kernel inside nvfp4_gemm_act_quant */,
-       NVFP4_OP_QUANTIZE_4OVER6 = 6, NVFP4_OP_KV_QUANT_4OVER6 = 7 };
+       NVFP4_OP_QUANTIZE_4OVER6 = 6, NVFP4_OP_KV_QUANT_4OVER6 = 7, NVFP4_OP_KV_QUANT_K = 8,
+       NVFP4_OP_KV_DEQUANT_GATHER = 9 };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
@@ -149,6 +150,38 @@ int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_t
  */
 int nvfp4_kv_quant_4over6(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Key-cache quantization as the paper applies it to keys (Sec. 3.2, Eq. 6, then
+ * the scale search of Appendix Eq. 12-13): every row [t, h, :] first has its
+ * mean over the d features removed,
+ *   mean[t,h] = RN_bf16( (sum_u K[t,h,u]) / d ),  Kbar[t,h,u] = RN_bf16( K[t,h,u] - mean[t,h] )
+ * (sum, quotient and difference in fp64: exact for rows whose values span less
+ * than 2^40), and Kbar is quantized like nvfp4_kv_quant_4over6, its tensor scale
+ * taken from the amax of Kbar.  The means belong to the cache entry.
+ * row_mean_bf16_out: device, bf16 [T*H].  d / 16 must be a power of two <= 64.
+ * workspace: nvfp4_workspace_bytes(NVFP4_OP_KV_QUANT_K, T, H, d).
+ */
+int nvfp4_kv_quant_k(const void *k_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
+                     void *row_mean_bf16_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Gathered KV-cache reconstruction (Sec. 3.2: with sink tokens and a sliding
+ * window an attention step reads several cached chunks).  `chunks` is a HOST
+ * array of n_chunks (1..NVFP4_KV_MAX_CHUNKS) descriptors of device data; chunk c
+ * holds T tokens (q.rows == T*H, q.K == d) and, for keys stored with
+ * nvfp4_kv_quant_k, its row means (NULL otherwise).  kv_bf16_out [sum_c T_c, H, d]
+ * receives the chunks back to back from one launch:
+ *   out = RN_bf16(code * block_scale * global_scale [+ row mean]), rounded once.
+ */
+#define NVFP4_KV_MAX_CHUNKS 64
+typedef struct nvfp4_kv_chunk {
+    nvfp4_tensor q;
+    const void *row_mean_bf16;   /* device bf16 [T*H], or NULL */
+    int64_t T;
+} nvfp4_kv_chunk;
+int nvfp4_kv_dequant_gather(const nvfp4_kv_chunk *chunks, int n_chunks, void *kv_bf16_out,
+                            int64_t H, int64_t d, void *stream);
 
 /*
  * KV-cache reconstruction (Sec. 3.2): kv_bf16_out[t,h,:] = RN_bf16(code *

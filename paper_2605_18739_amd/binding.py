@@ -17,12 +17,17 @@ _lib = None
 OUT_F32, OUT_BF16 = 0, 1
 ACT_NONE, ACT_GELU_TANH = 0, 1
 OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT, OP_GEMM_ACT_QUANT_GEMM = 0, 1, 2, 3, 4, 5
-OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6 = 6, 7
+OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6, OP_KV_QUANT_K, OP_KV_DEQUANT_GATHER = 6, 7, 8, 9
+KV_MAX_CHUNKS = 64
 
 
 class _CTensor(ctypes.Structure):
     _fields_ = [("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
                 ("global_scale", ctypes.c_void_p), ("rows", ctypes.c_int64), ("K", ctypes.c_int64)]
+
+
+class _CKvChunk(ctypes.Structure):
+    _fields_ = [("q", _CTensor), ("row_mean_bf16", ctypes.c_void_p), ("T", ctypes.c_int64)]
 
 
 class NVFP4Error(RuntimeError):
@@ -54,6 +59,10 @@ def lib():
         L.nvfp4_quantize_4over6.argtypes = [vp, i64, i64, i64, vp, tp, vp, sz, vp]
         L.nvfp4_kv_quant_4over6.restype = c.c_int
         L.nvfp4_kv_quant_4over6.argtypes = [vp, i64, i64, i64, tp, vp, sz, vp]
+        L.nvfp4_kv_quant_k.restype = c.c_int
+        L.nvfp4_kv_quant_k.argtypes = [vp, i64, i64, i64, tp, vp, vp, sz, vp]
+        L.nvfp4_kv_dequant_gather.restype = c.c_int
+        L.nvfp4_kv_dequant_gather.argtypes = [c.POINTER(_CKvChunk), c.c_int, vp, i64, i64, vp]
         L.nvfp4_workspace_bytes.restype = sz
         L.nvfp4_workspace_bytes.argtypes = [c.c_int, i64, i64, i64]
         L.nvfp4_status_string.restype = c.c_char_p
@@ -192,6 +201,38 @@ def nvfp4_kv_quant_4over6(kv, out=None, workspace=None, stream=None):
     ct = out.c()
     _check(lib().nvfp4_kv_quant_4over6(_ptr(kv), T, H, d, ctypes.byref(ct), _ptr(workspace), workspace.numel(),
                                        _stream(stream)))
+    return out
+
+
+def nvfp4_kv_quant_k(k, out=None, row_mean=None, workspace=None, stream=None):
+    """k: contiguous bf16 [T, H, d] keys; K-smoothing then scale search.  Returns (NVFP4Tensor, row means bf16 [T*H])."""
+    assert k.dtype == torch.bfloat16 and k.dim() == 3 and k.is_contiguous()
+    T, H, d = k.shape
+    if out is None:
+        out = NVFP4Tensor(T * H, d, k.device)
+    if row_mean is None:
+        row_mean = torch.empty(T * H, dtype=torch.bfloat16, device=k.device)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_KV_QUANT_K, T, H, d), k.device)
+    ct = out.c()
+    _check(lib().nvfp4_kv_quant_k(_ptr(k), T, H, d, ctypes.byref(ct), _ptr(row_mean), _ptr(workspace),
+                                  workspace.numel(), _stream(stream)))
+    return out, row_mean
+
+
+def nvfp4_kv_dequant_gather(chunks, H, d, out=None, stream=None):
+    """chunks: list of (NVFP4Tensor, row_mean or None, T).  Returns bf16 [sum T, H, d]."""
+    n = len(chunks)
+    arr = (_CKvChunk * n)()
+    total = 0
+    for i, (q, mean, T) in enumerate(chunks):
+        arr[i].q = q.c()
+        arr[i].row_mean_bf16 = mean.data_ptr() if mean is not None else None
+        arr[i].T = T
+        total += T
+    if out is None:
+        out = torch.empty((total, H, d), dtype=torch.bfloat16, device=chunks[0][0].codes.device)
+    _check(lib().nvfp4_kv_dequant_gather(arr, n, _ptr(out), H, d, _stream(stream)))
     return out
 
 

@@ -139,6 +139,55 @@ int nvfp4_kv_quant_4over6(const void *kv_bf16, int64_t T, int64_t H, int64_t d, 
                          static_cast<hipStream_t>(stream), true);
 }
 
+int nvfp4_kv_quant_k(const void *k_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
+                     void *row_mean_bf16_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!k_bf16 || !out || !row_mean_bf16_out) return NVFP4_ERR_NULL;
+    if (int rc = check_tensor(out)) return rc;
+    if (T <= 0 || H <= 0 || d <= 0 || (d & 15) != 0) return NVFP4_ERR_SHAPE;
+    const int64_t nb = d >> 4;
+    if (nb > 64 || (nb & (nb - 1)) != 0) return NVFP4_ERR_SHAPE;       // the lanes of a row reduce by shuffles
+    if (out->rows != T * H || out->K != d) return NVFP4_ERR_SHAPE;
+    if (!aligned16(k_bf16) || (reinterpret_cast<uintptr_t>(row_mean_bf16_out) & 1u)) return NVFP4_ERR_ALIGN;
+    if (!workspace || workspace_bytes < kPartialBytes) return NVFP4_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 3u) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timed t(s, NVFP4_OP_KV_QUANT_K);
+    const uint16_t *x = static_cast<const uint16_t *>(k_bf16);
+    uint16_t *mean = static_cast<uint16_t *>(row_mean_bf16_out);
+    uint32_t *partial = static_cast<uint32_t *>(workspace);
+    int n_partial = 0;
+    if (launch_amax_smooth(x, T * H, (int)d, mean, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
+    hipError_t e = launch_quantize_rows_smooth(x, T * H, (int)d, mean, partial, n_partial, out->codes,
+                                               out->scales, out->global_scale, s);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
+int nvfp4_kv_dequant_gather(const nvfp4_kv_chunk *chunks, int n_chunks, void *kv_bf16_out, int64_t H,
+                            int64_t d, void *stream)
+{
+    if (!chunks || !kv_bf16_out) return NVFP4_ERR_NULL;
+    if (n_chunks < 1 || n_chunks > NVFP4_KV_MAX_CHUNKS || H <= 0 || d <= 0) return NVFP4_ERR_SHAPE;
+    if (!aligned16(kv_bf16_out)) return NVFP4_ERR_ALIGN;
+    KvChunkDesc desc[NVFP4_KV_MAX_CHUNKS];
+    int64_t blocks = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        if (int rc = check_tensor(&chunks[c].q)) return rc;
+        if (chunks[c].T <= 0 || chunks[c].q.rows != chunks[c].T * H || chunks[c].q.K != d) return NVFP4_ERR_SHAPE;
+        if (reinterpret_cast<uintptr_t>(chunks[c].row_mean_bf16) & 1u) return NVFP4_ERR_ALIGN;
+        desc[c] = {chunks[c].q.codes, chunks[c].q.scales, chunks[c].q.global_scale,
+                   static_cast<const uint16_t *>(chunks[c].row_mean_bf16), chunks[c].T};
+        blocks += chunks[c].T * H * (d >> 4);
+    }
+    if (blocks / 512 + n_chunks > 0x7FFFFFFF) return NVFP4_ERR_SHAPE;       // one workgroup per 512 blocks
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timed t(s, NVFP4_OP_KV_DEQUANT_GATHER);
+    hipError_t e = launch_dequant_gather(desc, n_chunks, H, d, static_cast<uint16_t *>(kv_bf16_out), s);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
 int nvfp4_kv_dequant(const nvfp4_tensor *in, void *kv_bf16_out, int64_t T, int64_t H, int64_t d,
                      void *stream)
 {
@@ -242,6 +291,7 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
     case NVFP4_OP_KV_QUANT:
     case NVFP4_OP_QUANTIZE_4OVER6:
     case NVFP4_OP_KV_QUANT_4OVER6:
+    case NVFP4_OP_KV_QUANT_K:
         return kPartialBytes;
     case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c: bit 0 = caller supplies H, bit 1 = caller supplies the scale
         if (a <= 0 || b <= 0) return 0;

@@ -251,6 +251,25 @@ __device__ __forceinline__ uint32_t bf16_rne_from_f64(double p)
     return u >> 16;
 }
 
+// Signed variant: nearest-even bf16 of any finite double (sign kept, also for zero results).
+__device__ __forceinline__ uint32_t bf16_rne_signed_from_f64(double v)
+{
+    const uint32_t sign = (uint32_t)(__double_as_longlong(v) >> 48) & 0x8000u;
+    return sign | bf16_rne_from_f64(fabs(v));
+}
+
+// K-smoothing (Sec. 3.2, Eq. 6) of one 16-element block given its row mean (a bf16 value held
+// in a double): x_j -> RN_bf16(x_j - mean), the difference taken in fp64.
+__device__ __forceinline__ void smooth_block16(uint32_t (&w)[8], double mu)
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t lo = bf16_rne_signed_from_f64((double)bf16lo_to_f32(w[i]) - mu);
+        const uint32_t hi = bf16_rne_signed_from_f64((double)bf16hi_to_f32(w[i]) - mu);
+        w[i] = lo | (hi << 16);
+    }
+}
+
 // global scale from the tensor's largest |bf16| pattern: RN_fp32(amax / 2688), 1 if zero
 __device__ __forceinline__ float global_scale_from_amax_bits(uint32_t amax_bits16)
 {

@@ -20,6 +20,21 @@ hipError_t launch_quantize_cols(const uint16_t *x, int64_t R, int64_t C, int64_t
 hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, const float *gs, int64_t rows,
                                int64_t K, uint16_t *out, hipStream_t s);
 
+// Smoothed key cache (Sec. 3.2, Eq. 6): pass 1 writes the row means and the partial maxima of the
+// smoothed values; pass 2 removes the means again and runs the scale search.  d / 16 must be a
+// power of two, at most 64.
+hipError_t launch_amax_smooth(const uint16_t *x, int64_t rows, int d, uint16_t *mean_out, uint32_t *partial,
+                              int *n_partial, hipStream_t s);
+hipError_t launch_quantize_rows_smooth(const uint16_t *x, int64_t rows, int d, const uint16_t *row_mean,
+                                       const uint32_t *partial, int n_partial, uint8_t *codes,
+                                       uint8_t *scales, float *gs_out, hipStream_t s);
+
+// Gathered KV reconstruction: several chunks, one launch.
+constexpr int kMaxKvChunks = 64;
+struct KvChunkDesc { const uint8_t *codes, *scales; const float *global_scale; const uint16_t *row_mean; int64_t T; };
+hipError_t launch_dequant_gather(const KvChunkDesc *chunks, int n_chunks, int64_t H, int64_t d, uint16_t *out,
+                                 hipStream_t s);
+
 // Epilogue of the GEMM
 struct GemmEpilogue {
     int out_dtype;            // 0 fp32, 1 bf16, 2 none (quantized output only)

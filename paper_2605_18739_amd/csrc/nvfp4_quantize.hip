@@ -58,6 +58,56 @@ __global__ __launch_bounds__(256) void amax_partial_kernel(const uint16_t *__res
         partial[blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
 }
 
+// --------------------------------------------------------------------------
+// Pass 1 of the smoothed key cache (Sec. 3.2, Eq. 6): per row of d features (one token, one
+// head) the mean over the features, rounded to bf16 and stored, and the partial amax of the
+// smoothed values RN_bf16(x - mean).  One lane per 16-element block; the d/16 lanes of a row
+// are neighbours (d/16 a power of two up to 64) and add their fp64 partial sums by shuffles.
+// --------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void amax_smooth_kernel(const uint16_t *__restrict__ x, int64_t rows,
+                                                          int d, uint16_t *__restrict__ mean_out,
+                                                          uint32_t *__restrict__ partial)
+{
+    __shared__ uint32_t wave_max[4];
+    const int nb_row = d >> 4;
+    const int64_t nblk = rows * nb_row;
+    const int64_t stride = (int64_t)gridDim.x * 256;           // a multiple of nb_row
+    uint32_t acc = 0;
+    // the trip count is the same for all lanes of a wave up to the tail, where lanes past the end
+    // contribute zeros to the shuffles (their rows do not exist)
+    for (int64_t g0 = (int64_t)blockIdx.x * 256; g0 < nblk; g0 += stride) {
+        const int64_t g = g0 + threadIdx.x;
+        const bool live = g < nblk;
+        uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (live) {
+            const uint4v *p = (const uint4v *)(x + (g << 4));
+            const uint4v v0 = p[0], v1 = p[1];                 // ordinary loads: pass 2 re-reads x
+            w[0] = v0.x; w[1] = v0.y; w[2] = v0.z; w[3] = v0.w;
+            w[4] = v1.x; w[5] = v1.y; w[6] = v1.z; w[7] = v1.w;
+        }
+        double sum = 0.0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            sum += (double)bf16lo_to_f32(w[i]);
+            sum += (double)bf16hi_to_f32(w[i]);
+        }
+        for (int m = 1; m < nb_row; m <<= 1) sum += __shfl_xor(sum, m, 64);
+        const uint32_t mean_bits = bf16_rne_signed_from_f64(sum / (double)d);
+        const double mu = (double)__uint_as_float(mean_bits << 16);
+        if (live) {
+            if ((g % nb_row) == 0) mean_out[g / nb_row] = (uint16_t)mean_bits;
+            smooth_block16(w, mu);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
+        }
+    }
+    uint32_t m = wave_max_u32(pk_hmax_u16(acc));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        partial[blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+}
+
 // Every workgroup of a pass-2 kernel reduces the partials again (a few KB out
 // of L2) and so knows the tensor scale without a third launch.
 __device__ __forceinline__ float resolve_global_scale(const float *gs_in, const uint32_t *partial,
@@ -84,15 +134,17 @@ __device__ __forceinline__ float resolve_global_scale(const float *gs_in, const 
 // Pass 2, blocks along the contiguous axis: one lane per 16-element block
 // (two 128-bit loads, one 64-bit code store, one scale byte).
 // SEARCH: the Four-over-Six scale search of Eq. 12-13 instead of the plain max -> 6 rule.
+// SMOOTH: the row means of Eq. 6 (row_mean, one bf16 per row) are removed first.
 // --------------------------------------------------------------------------
-template <bool CONTIG, bool SEARCH = false>
+template <bool CONTIG, bool SEARCH = false, bool SMOOTH = false>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
                                                             int64_t C, int64_t ld,
                                                             const float *__restrict__ gs_in,
                                                             const uint32_t *__restrict__ partial,
                                                             int n_partial, uint8_t *__restrict__ codes,
                                                             uint8_t *__restrict__ scales,
-                                                            float *__restrict__ gs_out)
+                                                            float *__restrict__ gs_out,
+                                                            const uint16_t *__restrict__ row_mean = nullptr)
 {
     __shared__ uint32_t lds4[4];
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
@@ -124,6 +176,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
             const int64_t g = g0 + u * stride;
             if (g < nblk) {
                 uint32_t w[8] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w, v1[u].x, v1[u].y, v1[u].z, v1[u].w};
+                if constexpr (SMOOTH) smooth_block16(w, (double)__uint_as_float((uint32_t)row_mean[g / nb_row] << 16));
                 uint32_t acc = 0;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
@@ -219,13 +272,9 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__re
 // low-byte and a high-byte plane per scale, and every element is then two
 // byte-permute lookups.  One lane per 16-element block.
 // --------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__restrict__ codes,
-                                                           const uint8_t *__restrict__ scales,
-                                                           const float *__restrict__ gs, int64_t nblk,
-                                                           uint16_t *__restrict__ out)
+// table[scale byte] = {low bytes of magnitudes 0-3, low bytes 4-7, high bytes 0-3, high bytes 4-7}
+__device__ __forceinline__ void build_dequant_table(uint4v *table, double sg)
 {
-    __shared__ uint4v table[128];        // [scale byte] -> {lo bytes idx0-3, lo idx4-7, hi idx0-3, hi idx4-7}
-    const double sg = (double)*gs;
     if (threadIdx.x < 128) {
         const uint32_t s = threadIdx.x;
         const double sb = (double)e4m3_to_f32(s < 127u ? s : 0u);
@@ -240,6 +289,39 @@ __global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__rest
         uint4v e = {lo0, lo1, hi0, hi1};
         table[s] = e;
     }
+}
+
+// sixteen codes (two dwords) -> sixteen bf16 (eight dwords) through the table row t of their scale
+__device__ __forceinline__ void dequant_block_lookup(uint2v cc, uint4v t, uint32_t (&o)[8])
+{
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t cw = h ? cc.y : cc.x;
+        // selectors: magnitude index of the even / odd elements, one per byte
+        uint32_t se = cw & 0x07070707u, so = (cw >> 4) & 0x07070707u;
+        uint32_t lo_e = __builtin_amdgcn_perm(t.y, t.x, se), lo_o = __builtin_amdgcn_perm(t.y, t.x, so);
+        uint32_t hi_e = __builtin_amdgcn_perm(t.w, t.z, se), hi_o = __builtin_amdgcn_perm(t.w, t.z, so);
+        hi_e |= (cw << 4) & 0x80808080u;      // sign of even elements: bit 3 of each byte
+        hi_o |= cw & 0x80808080u;             // sign of odd elements: bit 7
+        // element 2b = (hi_e.b, lo_e.b), element 2b+1 = (hi_o.b, lo_o.b); dword b = elems 2b, 2b+1
+        uint32_t e01 = __builtin_amdgcn_perm(hi_e, lo_e, 0x05010400u);  // even elems of bytes 0, 1
+        uint32_t e23 = __builtin_amdgcn_perm(hi_e, lo_e, 0x07030602u);
+        uint32_t o01 = __builtin_amdgcn_perm(hi_o, lo_o, 0x05010400u);
+        uint32_t o23 = __builtin_amdgcn_perm(hi_o, lo_o, 0x07030602u);
+        o[4 * h + 0] = __builtin_amdgcn_perm(o01, e01, 0x05040100u);
+        o[4 * h + 1] = __builtin_amdgcn_perm(o01, e01, 0x07060302u);
+        o[4 * h + 2] = __builtin_amdgcn_perm(o23, e23, 0x05040100u);
+        o[4 * h + 3] = __builtin_amdgcn_perm(o23, e23, 0x07060302u);
+    }
+}
+
+__global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__restrict__ codes,
+                                                           const uint8_t *__restrict__ scales,
+                                                           const float *__restrict__ gs, int64_t nblk,
+                                                           uint16_t *__restrict__ out)
+{
+    __shared__ uint4v table[128];
+    build_dequant_table(table, (double)*gs);
     __syncthreads();
     const int64_t stride = (int64_t)gridDim.x * 256;
     constexpr int U = NVFP4_DQ_UNROLL;             // blocks in flight per lane
@@ -258,28 +340,8 @@ __global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__rest
         for (int u = 0; u < U; ++u) {
             const int64_t g = g0 + u * stride;
             if (g >= nblk) continue;
-            const uint2v cc = ccs[u];
-            uint4v t = table[sbs[u] & 0x7Fu];
             uint32_t o[8];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                uint32_t cw = h ? cc.y : cc.x;
-                // selectors: magnitude index of the even / odd elements, one per byte
-                uint32_t se = cw & 0x07070707u, so = (cw >> 4) & 0x07070707u;
-                uint32_t lo_e = __builtin_amdgcn_perm(t.y, t.x, se), lo_o = __builtin_amdgcn_perm(t.y, t.x, so);
-                uint32_t hi_e = __builtin_amdgcn_perm(t.w, t.z, se), hi_o = __builtin_amdgcn_perm(t.w, t.z, so);
-                hi_e |= (cw << 4) & 0x80808080u;      // sign of even elements: bit 3 of each byte
-                hi_o |= cw & 0x80808080u;             // sign of odd elements: bit 7
-                // element 2b = (hi_e.b, lo_e.b), element 2b+1 = (hi_o.b, lo_o.b); dword b = elems 2b, 2b+1
-                uint32_t e01 = __builtin_amdgcn_perm(hi_e, lo_e, 0x05010400u);  // even elems of bytes 0, 1
-                uint32_t e23 = __builtin_amdgcn_perm(hi_e, lo_e, 0x07030602u);
-                uint32_t o01 = __builtin_amdgcn_perm(hi_o, lo_o, 0x05010400u);
-                uint32_t o23 = __builtin_amdgcn_perm(hi_o, lo_o, 0x07030602u);
-                o[4 * h + 0] = __builtin_amdgcn_perm(o01, e01, 0x05040100u);
-                o[4 * h + 1] = __builtin_amdgcn_perm(o01, e01, 0x07060302u);
-                o[4 * h + 2] = __builtin_amdgcn_perm(o23, e23, 0x05040100u);
-                o[4 * h + 3] = __builtin_amdgcn_perm(o23, e23, 0x07060302u);
-            }
+            dequant_block_lookup(ccs[u], table[sbs[u] & 0x7Fu], o);
             uint4v a = {o[0], o[1], o[2], o[3]}, b = {o[4], o[5], o[6], o[7]};
             // plain stores: a lane writes two 16-byte halves of a 32-byte run, and the
             // cache merges neighbouring lanes' halves into full lines (streaming stores
@@ -292,7 +354,86 @@ __global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__rest
 }
 
 // --------------------------------------------------------------------------
-// host-side launchers
+// Gathered reconstruction (Sec. 3.2: with sink tokens and a sliding window an attention step
+// reads several cached chunks): up to kMaxKvChunks NVFP4 chunks, each with its own tensor
+// scale and, for smoothed keys, its row means, are written back to back into one bf16
+// [sum T_c, H, d] buffer by ONE launch.  A workgroup works inside one chunk (it owns
+// kGatherBlocksPerWg consecutive blocks of it), so the table of the plain path is built once
+// per workgroup; a smoothed chunk adds its row mean before the single rounding,
+// RN_bf16(code * s_b * s_g + mean), which takes the exact product and sum in fp64.
+// --------------------------------------------------------------------------
+constexpr int kGatherBlocksPerWg = 256 * 2;    // small workgroups: many loads in flight chip-wide matter more than table reuse
+struct GatherTable {
+    const uint8_t *codes[kMaxKvChunks];
+    const uint8_t *scales[kMaxKvChunks];
+    const float *gs[kMaxKvChunks];
+    const uint16_t *mean[kMaxKvChunks];           // nullptr: not smoothed
+    int64_t blk_start[kMaxKvChunks + 1];          // first block (16 elements) of chunk c in the output
+    int wg_start[kMaxKvChunks + 1];               // first workgroup of chunk c
+    int n_chunks;
+    int nb_row;                                    // blocks per row (d / 16)
+};
+
+__global__ __launch_bounds__(256) void dequant_gather_kernel(GatherTable t, uint16_t *__restrict__ out)
+{
+    __shared__ uint4v table[128];
+    int c = 0;
+    while (c + 1 < t.n_chunks && (int)blockIdx.x >= t.wg_start[c + 1]) ++c;      // uniform
+    const uint8_t *__restrict__ codes = t.codes[c];
+    const uint8_t *__restrict__ scales = t.scales[c];
+    const uint16_t *__restrict__ mean = t.mean[c];
+    const double sg = (double)*t.gs[c];
+    const int64_t nblk = t.blk_start[c + 1] - t.blk_start[c];
+    const int64_t first = (int64_t)((int)blockIdx.x - t.wg_start[c]) * kGatherBlocksPerWg;
+    uint16_t *dst = out + (t.blk_start[c] << 4);
+    if (!mean) {
+        build_dequant_table(table, sg);
+        __syncthreads();
+    }
+    constexpr int U = 2;                                   // blocks in flight per lane
+    for (int it = 0; it < kGatherBlocksPerWg / (256 * U); ++it) {
+        uint2v ccs[U];
+        uint32_t sbs[U];
+        const int64_t g0 = first + it * (256 * U) + threadIdx.x;
+        if (g0 >= nblk) break;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t g = g0 + u * 256;
+            if (g < nblk) {
+                ccs[u] = __builtin_nontemporal_load((const uint2v *)(codes + (g << 3)));
+                sbs[u] = scales[g] & 0x7Fu;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t g = g0 + u * 256;
+            if (g >= nblk) continue;
+            const uint2v cc = ccs[u];
+            uint32_t o[8];
+            if (!mean) {
+                dequant_block_lookup(cc, table[sbs[u]], o);
+            } else {
+                const double mu = (double)__uint_as_float((uint32_t)mean[g / t.nb_row] << 16);
+                const double den = (double)e4m3_to_f32(sbs[u]) * sg;                // exact
+                typedef float float2v __attribute__((ext_vector_type(2)));
+#define NVFP4_GATHER_PAIR(I, C, SEL)                                                              \
+    {                                                                                             \
+        const float2v q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(C, 1.0f, SEL);                 \
+        o[I] = bf16_rne_signed_from_f64((double)q.x * den + mu) |                                 \
+               (bf16_rne_signed_from_f64((double)q.y * den + mu) << 16);                          \
+    }
+                NVFP4_GATHER_PAIR(0, cc.x, 0) NVFP4_GATHER_PAIR(1, cc.x, 1) NVFP4_GATHER_PAIR(2, cc.x, 2) NVFP4_GATHER_PAIR(3, cc.x, 3)
+                NVFP4_GATHER_PAIR(4, cc.y, 0) NVFP4_GATHER_PAIR(5, cc.y, 1) NVFP4_GATHER_PAIR(6, cc.y, 2) NVFP4_GATHER_PAIR(7, cc.y, 3)
+#undef NVFP4_GATHER_PAIR
+            }
+            uint4v a = {o[0], o[1], o[2], o[3]}, b = {o[4], o[5], o[6], o[7]};
+            uint4v *q = (uint4v *)(dst + (g << 4));
+            q[0] = a;
+            q[1] = b;
+        }
+    }
+}
+
 // --------------------------------------------------------------------------
 static int grid_for(int64_t work_items, int max_grid)
 {
@@ -347,6 +488,50 @@ hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, cons
     int64_t nblk = rows * (K >> 4);
     int grid = grid_for(nblk, NVFP4_DQ_GRID);
     dequant_bf16_kernel<<<grid, 256, 0, s>>>(codes, scales, gs, nblk, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_amax_smooth(const uint16_t *x, int64_t rows, int d, uint16_t *mean_out, uint32_t *partial,
+                              int *n_partial, hipStream_t s)
+{
+    int grid = grid_for(rows * (d >> 4), kMaxPartials);
+    *n_partial = grid;
+    amax_smooth_kernel<<<grid, 256, 0, s>>>(x, rows, d, mean_out, partial);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_rows_smooth(const uint16_t *x, int64_t rows, int d, const uint16_t *row_mean,
+                                       const uint32_t *partial, int n_partial, uint8_t *codes,
+                                       uint8_t *scales, float *gs_out, hipStream_t s)
+{
+    int grid = grid_for(rows * (d >> 4), NVFP4_Q_GRID);
+    quantize_rows_kernel<true, true, true><<<grid, 256, 0, s>>>(x, rows, d, d, nullptr, partial, n_partial, codes,
+                                                                scales, gs_out, row_mean);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequant_gather(const KvChunkDesc *chunks, int n_chunks, int64_t H, int64_t d, uint16_t *out,
+                                 hipStream_t s)
+{
+    GatherTable t{};
+    t.n_chunks = n_chunks;
+    t.nb_row = (int)(d >> 4);
+    int64_t blk = 0;
+    int wg = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        t.codes[c] = chunks[c].codes;
+        t.scales[c] = chunks[c].scales;
+        t.gs[c] = chunks[c].global_scale;
+        t.mean[c] = chunks[c].row_mean;
+        t.blk_start[c] = blk;
+        t.wg_start[c] = wg;
+        const int64_t nblk = chunks[c].T * H * (d >> 4);
+        blk += nblk;
+        wg += (int)((nblk + kGatherBlocksPerWg - 1) / kGatherBlocksPerWg);
+    }
+    t.blk_start[n_chunks] = blk;
+    t.wg_start[n_chunks] = wg;
+    dequant_gather_kernel<<<wg, 256, 0, s>>>(t, out);
     return hipGetLastError();
 }
 

@@ -23,7 +23,8 @@ def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
     assert {"nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_act_quant", "nvfp4_kv_quant",
             "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string",
-            "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6"} <= set(names)
+            "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6", "nvfp4_kv_quant_k",
+            "nvfp4_kv_dequant_gather"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -91,6 +92,24 @@ def test_gemm_and_kv_reject_bad_arguments_on_the_host():
     assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w16), 1, None, ctypes.byref(out), None, ws, 16, None) == -4
     kv = ctypes.c_void_p(0x60000)
     t = _t(rows=6, K=32)
+    # smoothed keys: d / 16 must be a power of two <= 64; the means are required
+    mean = ctypes.c_void_p(0x70000)
+    t48 = _t(rows=6, K=48)
+    assert L.nvfp4_kv_quant_k(kv, 2, 3, 48, ctypes.byref(t48), mean, ws, 4096, None) == -2
+    assert L.nvfp4_kv_quant_k(kv, 2, 3, 32, ctypes.byref(t), None, ws, 4096, None) == -1
+    assert L.nvfp4_kv_quant_k(kv, 2, 3, 32, ctypes.byref(t), mean, ws, 8, None) == -4
+    assert L.nvfp4_kv_quant_k(kv, 2, 4, 32, ctypes.byref(t), mean, ws, 4096, None) == -2          # rows != T*H
+    # gathered reconstruction: chunk count and per-chunk shapes
+    from paper_2605_18739_amd.binding import _CKvChunk
+    ch = (_CKvChunk * 2)()
+    ch[0].q, ch[0].row_mean_bf16, ch[0].T = t, None, 2
+    ch[1].q, ch[1].row_mean_bf16, ch[1].T = t, 0x70000, 2
+    assert L.nvfp4_kv_dequant_gather(ch, 0, kv, 3, 32, None) == -2
+    assert L.nvfp4_kv_dequant_gather(ch, 65, kv, 3, 32, None) == -2
+    assert L.nvfp4_kv_dequant_gather(ch, 2, None, 3, 32, None) == -1
+    assert L.nvfp4_kv_dequant_gather(ch, 2, kv, 4, 32, None) == -2                                # rows != T*H
+    ch[1].T = 3
+    assert L.nvfp4_kv_dequant_gather(ch, 2, kv, 3, 32, None) == -2
     # the scale-search variants validate like their plain counterparts
     assert L.nvfp4_kv_quant_4over6(kv, 0, 3, 32, ctypes.byref(t), ws, 4096, None) == -2
     assert L.nvfp4_kv_quant_4over6(kv, 2, 3, 32, ctypes.byref(t), None, 0, None) == -4

@@ -294,6 +294,79 @@ def test_kv_quant_four_over_six(oracle):
     assert e46 <= e6
 
 
+# ------------------------------------------- smoothed keys, gathered reconstruction
+
+def _oracle_k_path(oracle, kb2d):
+    mean, xbar = oracle.kv_smooth(kb2d)
+    return mean, oracle.quantize(xbar, four_over_six=True)
+
+
+@pytest.mark.parametrize("T,H,d", [(1, 1, 16), (37, 24, 128), (130, 3, 64), (9, 5, 256), (3, 2, 1024)])
+def test_kv_quant_k_smoothing(oracle, T, H, d):
+    """Keys as the paper caches them (Sec. 3.2, Eq. 6 + scale search): means, codes, scales and
+    tensor scale identical to the oracle's; reconstruction with the means identical too."""
+    say(f"[kv-k] {T}x{H}x{d}")
+    g = np.random.default_rng(T + d)
+    x = wl.bf16_bits_to_f32(wl.kv_tensor(T, H, d, 8, 0)).reshape(T * H, d)
+    x = x + g.uniform(-6, 6, size=(T * H, 1)).astype(np.float32)        # a per-row offset for the smoothing to remove
+    kb = wl.to_bf16_bits(x)
+    want_mean, want_q = _oracle_k_path(oracle, kb)
+    got_q, got_mean = nv.nvfp4_kv_quant_k(dev_bf16(kb).reshape(T, H, d))
+    torch.cuda.synchronize()
+    assert (nv.bits_from_bf16(got_mean) == want_mean).all()
+    assert_q_equal(got_q, want_q, "smoothed keys")
+    back = nv.nvfp4_kv_dequant_gather([(got_q, got_mean, T)], H, d)
+    assert (nv.bits_from_bf16(back).reshape(T * H, d) == oracle.dequant_bf16(want_q, want_mean)).all()
+
+
+def test_kv_quant_k_degenerate_rows(oracle):
+    T, H, d = 8, 4, 128
+    x = np.zeros((T * H, d), np.float32)
+    x[1] = 3.25                                    # constant row: nothing left after smoothing
+    x[2, ::2], x[2, 1::2] = 1.0, -1.0              # zero mean
+    x[3, 0] = 1000.0                               # one outlier drags the mean
+    x[4] = np.linspace(-4, 4, d, dtype=np.float32)
+    kb = wl.to_bf16_bits(x)
+    want_mean, want_q = _oracle_k_path(oracle, kb)
+    got_q, got_mean = nv.nvfp4_kv_quant_k(dev_bf16(kb).reshape(T, H, d))
+    assert (nv.bits_from_bf16(got_mean) == want_mean).all()
+    assert_q_equal(got_q, want_q, "degenerate rows")
+    # all-zero cache: scale 1, zero codes, zero means
+    z = wl.to_bf16_bits(np.zeros((T * H, d), np.float32))
+    zq, zm = nv.nvfp4_kv_quant_k(dev_bf16(z).reshape(T, H, d))
+    assert_q_equal(zq, oracle.quantize(z, four_over_six=True), "zero cache")
+    assert (nv.bits_from_bf16(zm) == 0).all()
+
+
+def test_kv_dequant_gather_window(oracle):
+    """A sink chunk plus a sliding window of chunks of different lengths, keys smoothed and values
+    plain, reconstructed by one launch each: every byte equals the per-chunk oracle output."""
+    H, d = 24, 128
+    lens = [880, 1, 37, 880, 300]
+    k_chunks, v_chunks, want_k, want_v = [], [], [], []
+    for i, T in enumerate(lens):
+        kb = wl.kv_tensor(T, H, d, 9, 2 * i).reshape(T * H, d)
+        vb = wl.kv_tensor(T, H, d, 9, 2 * i + 1).reshape(T * H, d)
+        if i == 2:
+            kb = wl.to_bf16_bits(wl.bf16_bits_to_f32(kb) * 50.0)       # chunks differ in scale
+        m, q = _oracle_k_path(oracle, kb)
+        want_k.append(oracle.dequant_bf16(q, m))
+        want_v.append(oracle.dequant_bf16(oracle.quantize(vb)))
+        gq, gm = nv.nvfp4_kv_quant_k(dev_bf16(kb).reshape(T, H, d))
+        k_chunks.append((gq, gm, T))
+        v_chunks.append((nv.nvfp4_kv_quant(dev_bf16(vb).reshape(T, H, d)), None, T))
+    say(f"[kv-gather] {len(lens)} chunks, {sum(lens)} tokens")
+    kk = nv.bits_from_bf16(nv.nvfp4_kv_dequant_gather(k_chunks, H, d)).reshape(-1, d)
+    vv = nv.bits_from_bf16(nv.nvfp4_kv_dequant_gather(v_chunks, H, d)).reshape(-1, d)
+    assert (kk == np.concatenate(want_k)).all()
+    assert (vv == np.concatenate(want_v)).all()
+    # mixed list (smoothed and plain chunks in one call), and the single-chunk call equals nvfp4_kv_dequant
+    mixed = nv.bits_from_bf16(nv.nvfp4_kv_dequant_gather([k_chunks[0], v_chunks[1], k_chunks[4]], H, d)).reshape(-1, d)
+    assert (mixed == np.concatenate([want_k[0], want_v[1], want_k[4]])).all()
+    one = nv.nvfp4_kv_dequant_gather([v_chunks[3]], H, d)
+    assert (nv.bits_from_bf16(one) == nv.bits_from_bf16(nv.nvfp4_kv_dequant(v_chunks[3][0], lens[3], H, d))).all()
+
+
 # --------------------------------------------------- fused activation + quantize
 
 def _act_quant_case(oracle, M, N, K, given_scale, what):
@@ -464,6 +537,19 @@ def test_full_size_kv_cache_config4(oracle):
     rel46 = np.linalg.norm(x - wl.bf16_bits_to_f32(back).astype(np.float64)) / np.linalg.norm(x)
     say(f"        round-trip relative Frobenius error with the search {rel46:.4f}")
     assert rel46 < rel          # rel: the plain rule on V above; K and V are drawn alike
+    say("[config4] K with smoothing and the scale search, reconstructed as a window of 21 chunks")
+    Tc = 880
+    chunks, want = [], []
+    for c in range(T // Tc):
+        kb = cfg["K"][c * Tc:(c + 1) * Tc].reshape(Tc * H, d)
+        m, q = _oracle_k_path(oracle, kb)
+        want.append(oracle.dequant_bf16(q, m))
+        gq, gm = nv.nvfp4_kv_quant_k(dev_bf16(kb).reshape(Tc, H, d))
+        assert (nv.bits_from_bf16(gm) == m).all()
+        assert_q_equal(gq, q, f"K chunk {c}")
+        chunks.append((gq, gm, Tc))
+    got = nv.bits_from_bf16(nv.nvfp4_kv_dequant_gather(chunks, H, d)).reshape(T * H, d)
+    assert (got == np.concatenate(want)).all()
 
 
 def test_full_size_training_triplet_config5(oracle):
