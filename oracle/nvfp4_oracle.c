@@ -206,6 +206,54 @@ void nvfp4o_quantize(const uint16_t *x, int64_t R, int64_t C, int64_t ld, int bl
     }
 }
 
+/* 2-D block scaling for weights (Sec. 2.2, the training recipe): one E4M3 scale per 16x16
+ * tile, from the tile's maximum, so that W and W^T carry the same quantized values.  The
+ * tensor format does not change: the scale is written once per row of the tile in
+ * scales[R, C/16] and once per column of the tile in scales_t[C, R/16]; codes_t is the
+ * transpose of codes (the operand K-contiguous along R).  codes_t / scales_t may be NULL. */
+void nvfp4o_quantize_2d(const uint16_t *x, int64_t R, int64_t C, int64_t ld,
+                        const float *global_scale_in, uint8_t *codes, uint8_t *scales,
+                        uint8_t *codes_t, uint8_t *scales_t, float *global_scale_out)
+{
+    int64_t tr = R / 16, tc = C / 16, I;
+    float sgf = global_scale_in ? *global_scale_in : nvfp4o_global_scale(x, R, C, ld);
+    double sg = (double)sgf;
+    init_tables();
+    *global_scale_out = sgf;
+#pragma omp parallel for schedule(static)
+    for (I = 0; I < tr; ++I) {
+        int64_t J;
+        for (J = 0; J < tc; ++J) {
+            double bmax = 0.0, den;
+            uint8_t c[16][16];
+            int i, j, sbyte;
+            for (i = 0; i < 16; ++i)
+                for (j = 0; j < 16; ++j) {
+                    double a = fabs(nvfp4o_bf16_decode(x[(16 * I + i) * ld + 16 * J + j]));
+                    if (a > bmax) bmax = a;
+                }
+            sbyte = nvfp4o_e4m3_cast_ratio(bmax, 6.0 * sg);
+            den = nvfp4o_e4m3_decode((unsigned)sbyte) * sg;
+            for (i = 0; i < 16; ++i)
+                for (j = 0; j < 16; ++j) {
+                    double v = nvfp4o_bf16_decode(x[(16 * I + i) * ld + 16 * J + j]);
+                    c[i][j] = (uint8_t)((signbit(v) ? 8 : 0) | nvfp4o_e2m1_cast_ratio(fabs(v), den));
+                }
+            for (i = 0; i < 16; ++i) {
+                scales[(16 * I + i) * tc + J] = (uint8_t)sbyte;
+                for (j = 0; j < 8; ++j)
+                    codes[(16 * I + i) * (C / 2) + 8 * J + j] = (uint8_t)(c[i][2 * j] | (c[i][2 * j + 1] << 4));
+            }
+            if (codes_t)
+                for (j = 0; j < 16; ++j) {
+                    scales_t[(16 * J + j) * tr + I] = (uint8_t)sbyte;
+                    for (i = 0; i < 8; ++i)
+                        codes_t[(16 * J + j) * (R / 2) + 8 * I + i] = (uint8_t)(c[2 * i][j] | (c[2 * i + 1][j] << 4));
+                }
+        }
+    }
+}
+
 /* Four-over-Six (Appendix, Eq. 12-13): per block also try the scale that maps
  * the block maximum to 4 and keep the candidate with the lower squared
  * reconstruction error; equal error keeps the 6-based encoding (the paper does

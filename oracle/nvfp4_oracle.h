@@ -35,6 +35,12 @@ void nvfp4o_quantize(const uint16_t *x, int64_t R, int64_t C, int64_t ld, int bl
                      const float *global_scale_in, uint8_t *codes, uint8_t *scales,
                      float *global_scale_out);
 
+/* 2-D block scaling for weights (Sec. 2.2 training recipe): one scale per 16x16 tile; the
+ * [R, C] operand (blocks along C) and, if asked for, the [C, R] operand (blocks along R). */
+void nvfp4o_quantize_2d(const uint16_t *x, int64_t R, int64_t C, int64_t ld,
+                        const float *global_scale_in, uint8_t *codes, uint8_t *scales,
+                        uint8_t *codes_t, uint8_t *scales_t, float *global_scale_out);
+
 /* Four-over-Six scale search (Appendix, Eq. 12-13); blocks along C only. */
 void nvfp4o_quantize_4over6(const uint16_t *x, int64_t R, int64_t C, int64_t ld,
                             const float *global_scale_in, uint8_t *codes, uint8_t *scales,

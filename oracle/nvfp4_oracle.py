@@ -49,6 +49,8 @@ def lib():
         L.nvfp4o_global_scale.argtypes = [u16p, i64, i64, i64]
         L.nvfp4o_quantize.restype = None
         L.nvfp4o_quantize.argtypes = [u16p, i64, i64, i64, c.c_int, f32p, u8p, u8p, f32p]
+        L.nvfp4o_quantize_2d.restype = None
+        L.nvfp4o_quantize_2d.argtypes = [u16p, i64, i64, i64, f32p, u8p, u8p, u8p, u8p, f32p]
         L.nvfp4o_quantize_4over6.restype = None
         L.nvfp4o_quantize_4over6.argtypes = [u16p, i64, i64, i64, f32p, u8p, u8p, f32p]
         L.nvfp4o_dequant_f64.restype = None
@@ -126,6 +128,23 @@ def dequant_f64(q):
                              ctypes.c_float(float(q.global_scale)), q.rows, q.K,
                              _p(out, ctypes.c_double))
     return out
+
+
+def quantize_2d(x_bits, global_scale_in=None):
+    """Weights with one scale per 16x16 tile (Sec. 2.2 training recipe): returns (Q of [R, C], Q of [C, R])."""
+    x = _u16(x_bits)
+    R, C = x.shape
+    assert R % 16 == 0 and C % 16 == 0
+    codes, scales = np.empty((R, C // 2), np.uint8), np.empty((R, C // 16), np.uint8)
+    codes_t, scales_t = np.empty((C, R // 2), np.uint8), np.empty((C, R // 16), np.uint8)
+    gs_out = ctypes.c_float(0)
+    gs_in = None
+    if global_scale_in is not None:
+        gs_in = ctypes.pointer(ctypes.c_float(float(global_scale_in)))
+    lib().nvfp4o_quantize_2d(_p(x, ctypes.c_uint16), R, C, C, gs_in, _p(codes, ctypes.c_uint8),
+                             _p(scales, ctypes.c_uint8), _p(codes_t, ctypes.c_uint8),
+                             _p(scales_t, ctypes.c_uint8), ctypes.byref(gs_out))
+    return Q(codes, scales, gs_out.value), Q(codes_t, scales_t, gs_out.value)
 
 
 def kv_smooth(x_bits):

@@ -24,9 +24,6 @@
 #ifndef NVFP4_SCHED
 #define NVFP4_SCHED 2     // VALU instructions requested after every MFMA of the main loop
 #endif
-#ifndef NVFP4_EXPERIMENT
-#define NVFP4_EXPERIMENT 0   // timing experiments only: bit 0 no refetch, 1 no staging, 2 no fragment reads, 3 no barrier
-#endif
 
 // Empty inline-asm statements that tie values (or memory) to a point of the
 // instruction stream; register constraints only exist in the device pass.
@@ -393,19 +390,13 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
         constexpr int NH = 2 * NU;                  // half-units to stage
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-#if !(NVFP4_EXPERIMENT & 4)
             if (kk < 3) read_frags(buf, kk + 1, (kk + 1) & 1);
-#endif
             if (kStage) {
 #pragma unroll
                 for (int x = 0; x < NH; ++x) {
                     if (phase_of_half_unit(x, NH) == kk) {
-#if !(NVFP4_EXPERIMENT & 2)
                         stage_half(x >> 1, x & 1, buf ^ 1);
-#endif
-#if !(NVFP4_EXPERIMENT & 1)
                         if (kLoad && (x & 1)) load_unit(x >> 1, kt + 2);
-#endif
                     }
                 }
             }
@@ -413,12 +404,8 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
                 mfma_range(kk, 0, TN * TM);
             } else {
                 mfma_range(kk, 0, TN * TM / 2);
-#if !(NVFP4_EXPERIMENT & 8)
                 __syncthreads();
-#endif
-#if !(NVFP4_EXPERIMENT & 4)
                 if (kStage) read_frags(buf ^ 1, 0, 0);
-#endif
                 mfma_range(kk, TN * TM / 2, TN * TM);
             }
         }
@@ -654,22 +641,16 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
         constexpr int half = quarter & 1;                      // also the register set of step rs
         constexpr int set = half;
         if constexpr (quarter == 3) {
-#if !(NVFP4_EXPERIMENT & 1)
             wait_vmcnt_le<0>();
-#endif
             NVFP4_COMPILER_FENCE();
-#if !(NVFP4_EXPERIMENT & 2)
             __builtin_amdgcn_s_barrier();
-#endif
             NVFP4_COMPILER_FENCE();
         }
         read_step(rs + 1, set ^ 1);
         if constexpr (half == 1) {
-#if !(NVFP4_EXPERIMENT & 4)
             const int ng = (rs >> 1) + 3;                   // copy step to start (clamped at the end of K)
             if constexpr (quarter == 3) copy_scales(min(ng, GT - 1) >> 1);   // ng is even here: a new scale group
             copy_codes(min(ng, GT - 1));
-#endif
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -682,7 +663,7 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
                 // next sub-step's fragments: 2 NF pieces dealt over the NMF MFMAs
 #pragma unroll
                 for (int pc = 0; pc < 2 * NF; ++pc)
-                    if (pc * NMF / (2 * NF) == t && !(NVFP4_EXPERIMENT & 8)) {
+                    if (pc * NMF / (2 * NF) == t) {
                         if (j < 3) expand_piece(set, j + 1, pc);
                         else expand_piece(set ^ 1, 0, pc);
                     }

@@ -526,3 +526,55 @@ def test_kv_smooth_reconstruction(oracle):
     plain = oracle.quantize(xb, four_over_six=True)
     e_plain = np.linalg.norm(xf - wl.bf16_bits_to_f32(oracle.dequant_bf16(plain)))
     assert e_smooth < 0.8 * e_plain
+
+
+# ------------------------------------------------- 2-D block scaling (weights)
+
+def test_quantize_2d_tiles_against_rational_brute_force(oracle):
+    """Sec. 2.2 training recipe: one scale per 16x16 tile.  Exact rationals: the tile's scale is
+    the E4M3 value nearest to tilemax / (6 s_g), every code the E2M1 value nearest to x / (s s_g)."""
+    xb = wl.normal((32, 48), 0.02, 21, 0)
+    xb[5, 7] = wl.to_bf16_bits(np.array([0.31], np.float32))[0]           # an outlier inside one tile
+    x = wl.bf16_bits_to_f32(xb).astype(np.float64)
+    q, qt = oracle.quantize_2d(xb)
+    sg = _fp32_nearest(Fraction(float(np.abs(x).max())) / 2688)
+    assert np.float32(q.global_scale) == sg and np.float32(qt.global_scale) == sg
+    sgF = Fraction(float(sg))
+    e4 = [Fraction(float(v)) for v in E4M3_VALUES[:127]]
+    mags = [Fraction(v) for v in _gold_e2m1()]
+    for I in range(2):
+        for J in range(3):
+            tile = x[16 * I:16 * I + 16, 16 * J:16 * J + 16]
+            sb = _nearest_brute(e4, Fraction(float(np.abs(tile).max())) / (6 * sgF))
+            assert (q.scales[16 * I:16 * I + 16, J] == sb).all()           # the same byte on all 16 rows of the tile
+            assert (qt.scales[16 * J:16 * J + 16, I] == sb).all()          # and on all 16 columns
+            den = e4[sb] * sgF
+            for i in range(16):
+                for j in range(16):
+                    idx = _nearest_brute(mags, Fraction(float(abs(tile[i, j]))) / den) | (8 if np.signbit(tile[i, j]) else 0)
+                    byte = q.codes[16 * I + i, (16 * J + j) // 2]
+                    assert (byte >> (4 * (j % 2))) & 15 == idx
+                    byte_t = qt.codes[16 * J + j, (16 * I + i) // 2]
+                    assert (byte_t >> (4 * (i % 2))) & 15 == idx
+
+
+def test_quantize_2d_serves_the_transposed_operand(oracle):
+    """The point of 2-D scaling: W and W^T dequantize to the same matrix, and quantizing the
+    transposed matrix gives the transposed pair."""
+    xb = wl.normal((64, 96), 0.02, 22, 0)
+    q, qt = oracle.quantize_2d(xb)
+    assert (oracle.dequant_f64(qt) == oracle.dequant_f64(q).T).all()
+    q2, q2t = oracle.quantize_2d(np.ascontiguousarray(xb.T))
+    assert (q2.codes == qt.codes).all() and (q2.scales == qt.scales).all()
+    assert (q2t.codes == q.codes).all() and (q2t.scales == q.scales).all()
+    # a tile whose rows all share the tile maximum is quantized like sixteen 1-D blocks
+    x = wl.bf16_bits_to_f32(xb).copy()
+    x[:16, :16] = np.clip(x[:16, :16], -0.01, 0.01)
+    x[:16, 0] = 0.05
+    yb = wl.to_bf16_bits(x)
+    a, _ = oracle.quantize_2d(yb)
+    b = oracle.quantize(yb)
+    assert (a.scales[:16, 0] == b.scales[:16, 0]).all() and (a.codes[:16, :8] == b.codes[:16, :8]).all()
+    # 1-D scales can only be finer: the 2-D error is never smaller in total
+    xf = wl.bf16_bits_to_f32(xb).astype(np.float64)
+    assert np.linalg.norm(xf - oracle.dequant_f64(q)) >= np.linalg.norm(xf - oracle.dequant_f64(oracle.quantize(xb))) * 0.999
