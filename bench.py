@@ -217,6 +217,10 @@ def measure_rows(nv, wl, torch, np):
     qWt = qtime(W, 1, "quantize_T_W_14336x3072")
     qdYt = qtime(dY, 1, "quantize_T_dY_17600x14336")
     qXt = qtime(X, 1, "quantize_T_X_17600x3072")
+    # weights with one scale per 16x16 tile: W and W^T from one pass (2.5625 B/element per operand written)
+    ms = _time_op(nv, torch, nv.OP_QUANTIZE_2D, lambda: nv.nvfp4_quantize_2d(W, workspace=ws), 10)
+    res["quantize_2d_W_and_WT_14336x3072"] = {"ms": round(ms, 4), "GBs": round((2.0 + 2 * 0.5625) * F * D / ms / 1e6, 1),
+                                              "frac_hbm": round((2.0 + 2 * 0.5625) * F * D / ms / 1e6 / PEAK_HBM_GBS, 4)}
     gs = torch.tensor([float(qdY.global_scale.item())], dtype=torch.float32, device=dev)
     out = nv.NVFP4Tensor(Mt, F, dev)
     ms = _time_op(nv, torch, nv.OP_QUANTIZE, lambda: nv.nvfp4_quantize(dY, global_scale_in=gs, out=out, workspace=ws), 10)

@@ -67,7 +67,7 @@ enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2
        NVFP4_OP_KV_DEQUANT = 4,
        NVFP4_OP_GEMM_ACT_QUANT_GEMM = 5 /* timing only: the GEMM kernel inside nvfp4_gemm_act_quant */,
        NVFP4_OP_QUANTIZE_4OVER6 = 6, NVFP4_OP_KV_QUANT_4OVER6 = 7, NVFP4_OP_KV_QUANT_K = 8,
-       NVFP4_OP_KV_DEQUANT_GATHER = 9 };
+       NVFP4_OP_KV_DEQUANT_GATHER = 9, NVFP4_OP_QUANTIZE_2D = 10 };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
@@ -101,6 +101,22 @@ int nvfp4_quantize(const void *x_bf16, int64_t R, int64_t C, int64_t ld, int blo
 int nvfp4_quantize_4over6(const void *x_bf16, int64_t R, int64_t C, int64_t ld,
                           const float *global_scale_in, nvfp4_tensor *out,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Weight quantizer with 2-D block scaling (Sec. 2.2 "Multi-Shot AR NVFP4
+ * Training": 2-D block scaling for weights, 1-D for activations and gradients):
+ * one E4M3 scale per 16 x 16 tile, from the tile's maximum, so that the forward
+ * operand W [R, C] (blocks along C) and the backward operand W^T [C, R] (blocks
+ * along R) contain the same quantized values.  The tensor format is unchanged:
+ * the tile's scale byte is repeated on its 16 rows in out->scales and on its 16
+ * columns in out_t->scales; out_t->codes is the transpose of out->codes.
+ * R % 16 == 0, C % 16 == 0.  out: rows = R, K = C.  out_t: NULL, or rows = C,
+ * K = R; both receive the same global scale.  global_scale_in and workspace as
+ * nvfp4_quantize (workspace size: NVFP4_OP_QUANTIZE_2D).
+ */
+int nvfp4_quantize_2d(const void *w_bf16, int64_t R, int64_t C, int64_t ld,
+                      const float *global_scale_in, nvfp4_tensor *out, nvfp4_tensor *out_t,
+                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Block-scaled FP4 GEMM, FP32 accumulation (Sec. 2.2 / 3.1; Appendix

@@ -19,6 +19,7 @@ ACT_NONE, ACT_GELU_TANH = 0, 1
 OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT, OP_GEMM_ACT_QUANT_GEMM = 0, 1, 2, 3, 4, 5
 OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6, OP_KV_QUANT_K, OP_KV_DEQUANT_GATHER = 6, 7, 8, 9
 KV_MAX_CHUNKS = 64
+OP_QUANTIZE_2D = 10
 
 
 class _CTensor(ctypes.Structure):
@@ -59,6 +60,8 @@ def lib():
         L.nvfp4_quantize_4over6.argtypes = [vp, i64, i64, i64, vp, tp, vp, sz, vp]
         L.nvfp4_kv_quant_4over6.restype = c.c_int
         L.nvfp4_kv_quant_4over6.argtypes = [vp, i64, i64, i64, tp, vp, sz, vp]
+        L.nvfp4_quantize_2d.restype = c.c_int
+        L.nvfp4_quantize_2d.argtypes = [vp, i64, i64, i64, vp, tp, tp, vp, sz, vp]
         L.nvfp4_kv_quant_k.restype = c.c_int
         L.nvfp4_kv_quant_k.argtypes = [vp, i64, i64, i64, tp, vp, vp, sz, vp]
         L.nvfp4_kv_dequant_gather.restype = c.c_int
@@ -202,6 +205,23 @@ def nvfp4_kv_quant_4over6(kv, out=None, workspace=None, stream=None):
     _check(lib().nvfp4_kv_quant_4over6(_ptr(kv), T, H, d, ctypes.byref(ct), _ptr(workspace), workspace.numel(),
                                        _stream(stream)))
     return out
+
+
+def nvfp4_quantize_2d(w, global_scale_in=None, transposed=True, workspace=None, stream=None):
+    """w: bf16 [R, C] weights (R, C multiples of 16), one scale per 16x16 tile.
+    Returns (NVFP4Tensor [R, C], NVFP4Tensor [C, R] or None)."""
+    assert w.dtype == torch.bfloat16 and w.dim() == 2 and w.stride(1) == 1
+    R, C = w.shape
+    out = NVFP4Tensor(R, C, w.device)
+    out_t = NVFP4Tensor(C, R, w.device) if transposed else None
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_QUANTIZE_2D, R, C), w.device)
+    co = out.c()
+    ct = out_t.c() if transposed else None
+    _check(lib().nvfp4_quantize_2d(_ptr(w), R, C, w.stride(0), _ptr(global_scale_in), ctypes.byref(co),
+                                   ctypes.byref(ct) if transposed else None, _ptr(workspace), workspace.numel(),
+                                   _stream(stream)))
+    return out, out_t
 
 
 def nvfp4_kv_quant_k(k, out=None, row_mean=None, workspace=None, stream=None):

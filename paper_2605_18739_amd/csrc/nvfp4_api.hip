@@ -139,6 +139,35 @@ int nvfp4_kv_quant_4over6(const void *kv_bf16, int64_t T, int64_t H, int64_t d, 
                          static_cast<hipStream_t>(stream), true);
 }
 
+int nvfp4_quantize_2d(const void *w_bf16, int64_t R, int64_t C, int64_t ld, const float *global_scale_in,
+                      nvfp4_tensor *out, nvfp4_tensor *out_t, void *workspace, size_t workspace_bytes,
+                      void *stream)
+{
+    if (!w_bf16 || !out) return NVFP4_ERR_NULL;
+    if (int rc = check_tensor(out)) return rc;
+    if (out_t)
+        if (int rc = check_tensor(out_t)) return rc;
+    if (R <= 0 || C <= 0 || ld < C || (R & 15) != 0 || (C & 15) != 0) return NVFP4_ERR_SHAPE;
+    if (out->rows != R || out->K != C) return NVFP4_ERR_SHAPE;
+    if (out_t && (out_t->rows != C || out_t->K != R)) return NVFP4_ERR_SHAPE;
+    if (!aligned16(w_bf16) || (ld & 7) != 0) return NVFP4_ERR_ALIGN;
+    if (!global_scale_in && (!workspace || workspace_bytes < kPartialBytes)) return NVFP4_ERR_WORKSPACE;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 3u)) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timed t(s, NVFP4_OP_QUANTIZE_2D);
+    const uint16_t *xb = static_cast<const uint16_t *>(w_bf16);
+    uint32_t *partial = static_cast<uint32_t *>(workspace);
+    int n_partial = 0;
+    if (!global_scale_in)
+        if (launch_amax(xb, R, C, ld, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
+    if (launch_quantize_tiles(xb, R, C, ld, global_scale_in, partial, n_partial, out->codes, out->scales,
+                              out_t ? out_t->codes : nullptr, out_t ? out_t->scales : nullptr,
+                              out->global_scale, out_t ? out_t->global_scale : nullptr, s) != hipSuccess)
+        return NVFP4_ERR_LAUNCH;
+    return NVFP4_OK;
+}
+
 int nvfp4_kv_quant_k(const void *k_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
                      void *row_mean_bf16_out, void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -292,6 +321,7 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
     case NVFP4_OP_QUANTIZE_4OVER6:
     case NVFP4_OP_KV_QUANT_4OVER6:
     case NVFP4_OP_KV_QUANT_K:
+    case NVFP4_OP_QUANTIZE_2D:
         return kPartialBytes;
     case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c: bit 0 = caller supplies H, bit 1 = caller supplies the scale
         if (a <= 0 || b <= 0) return 0;

@@ -20,6 +20,12 @@ hipError_t launch_quantize_cols(const uint16_t *x, int64_t R, int64_t C, int64_t
 hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, const float *gs, int64_t rows,
                                int64_t K, uint16_t *out, hipStream_t s);
 
+// 2-D block scaling (one scale per 16x16 tile); codes_t / scales_t: the transposed operand, or nullptr
+hipError_t launch_quantize_tiles(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
+                                 const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
+                                 uint8_t *codes_t, uint8_t *scales_t, float *gs_out, float *gs_out_t,
+                                 hipStream_t s);
+
 // Smoothed key cache (Sec. 3.2, Eq. 6): pass 1 writes the row means and the partial maxima of the
 // smoothed values; pass 2 removes the means again and runs the scale search.  d / 16 must be a
 // power of two, at most 64.

@@ -266,6 +266,71 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__re
 }
 
 // --------------------------------------------------------------------------
+// 2-D block scaling for weights (Sec. 2.2, the training recipe): one scale per 16x16 tile,
+// so that the operand [R, C] (blocks along C) and the operand [C, R] (blocks along R) hold
+// the same quantized values.  A lane owns a whole tile (sixteen 32-byte row loads, 128
+// registers), a workgroup a square of 16 x 16 tiles; lane = 16 tj + ti, so the transposed
+// output leaves in 128-byte runs (ti fastest) and the plain one in 32-byte runs that
+// neighbouring waves complete in the cache.
+// --------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint16_t *__restrict__ x, int64_t R,
+                                                             int64_t C, int64_t ld,
+                                                             const float *__restrict__ gs_in,
+                                                             const uint32_t *__restrict__ partial,
+                                                             int n_partial, uint8_t *__restrict__ codes,
+                                                             uint8_t *__restrict__ scales,
+                                                             uint8_t *__restrict__ codes_t,
+                                                             uint8_t *__restrict__ scales_t,
+                                                             float *__restrict__ gs_out,
+                                                             float *__restrict__ gs_out_t)
+{
+    __shared__ uint32_t lds4[4];
+    const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
+    if (gs_out_t && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *gs_out_t = sg;
+    const float inv_6sg = 1.0f / (6.0f * sg);
+    const int64_t I = (int64_t)blockIdx.y * 16 + (threadIdx.x & 15), J = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int64_t tr = R >> 4, tc = C >> 4;
+    if (I >= tr || J >= tc) return;
+    uint32_t w[16][8];
+    uint32_t acc = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint4v *p = (const uint4v *)(x + (16 * I + i) * ld + 16 * J);
+        const uint4v v0 = __builtin_nontemporal_load(p), v1 = __builtin_nontemporal_load(p + 1);
+        w[i][0] = v0.x; w[i][1] = v0.y; w[i][2] = v0.z; w[i][3] = v0.w;
+        w[i][4] = v1.x; w[i][5] = v1.y; w[i][6] = v1.z; w[i][7] = v1.w;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc = pk_absmax_u16(acc, w[i][k]);
+    }
+    const float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
+    const uint32_t sbyte = block_scale_exact(bmax, sg, inv_6sg);
+    const float sb = e4m3_to_f32(sbyte);
+    uint32_t c0[16], c1[16];                       // row i of the tile: codes of columns 0-7, 8-15
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        encode_block16(w[i], sb, sg, c0[i], c1[i]);
+        const int64_t row = 16 * I + i;
+        *(uint2v *)(codes + row * (C >> 1) + 8 * J) = uint2v{c0[i], c1[i]};
+        scales[row * tc + J] = (uint8_t)sbyte;
+    }
+    if (codes_t) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            // column j of the tile = 16 codes of row 16 J + j of the transposed operand
+            uint32_t t0 = 0, t1 = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                t0 |= (((j < 8 ? c0[i] : c1[i]) >> (4 * (j & 7))) & 15u) << (4 * i);
+                t1 |= (((j < 8 ? c0[i + 8] : c1[i + 8]) >> (4 * (j & 7))) & 15u) << (4 * i);
+            }
+            const int64_t row = 16 * J + j;
+            *(uint2v *)(codes_t + row * (R >> 1) + 8 * I) = uint2v{t0, t1};
+            scales_t[row * tr + I] = (uint8_t)sbyte;
+        }
+    }
+}
+
+// --------------------------------------------------------------------------
 // KV-cache reconstruction: x^ = RN_bf16(code * s_b * s_g), the product exact,
 // one rounding.  For a given tensor there are only 127 * 8 distinct magnitudes,
 // so each workgroup builds that table exactly (fp64) in LDS once, split into a
@@ -488,6 +553,17 @@ hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, cons
     int64_t nblk = rows * (K >> 4);
     int grid = grid_for(nblk, NVFP4_DQ_GRID);
     dequant_bf16_kernel<<<grid, 256, 0, s>>>(codes, scales, gs, nblk, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_tiles(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
+                                 const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
+                                 uint8_t *codes_t, uint8_t *scales_t, float *gs_out, float *gs_out_t,
+                                 hipStream_t s)
+{
+    dim3 grid((unsigned)((C + 255) / 256), (unsigned)((R + 255) / 256));
+    quantize_tiles_kernel<<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes, scales, codes_t,
+                                               scales_t, gs_out, gs_out_t);
     return hipGetLastError();
 }
 

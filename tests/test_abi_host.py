@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert {"nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_act_quant", "nvfp4_kv_quant",
             "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string",
             "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6", "nvfp4_kv_quant_k",
-            "nvfp4_kv_dequant_gather"} <= set(names)
+            "nvfp4_kv_dequant_gather", "nvfp4_quantize_2d"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -92,6 +92,14 @@ def test_gemm_and_kv_reject_bad_arguments_on_the_host():
     assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w16), 1, None, ctypes.byref(out), None, ws, 16, None) == -4
     kv = ctypes.c_void_p(0x60000)
     t = _t(rows=6, K=32)
+    # 2-D weight scaling: both sides multiples of 16, shapes of both outputs
+    w2 = _t(rows=32, K=48)
+    w2t = _t(rows=48, K=32)
+    q2 = lambda R, C, o, ot, wsp, wb: L.nvfp4_quantize_2d(kv, R, C, C, None, ctypes.byref(o), ctypes.byref(ot) if ot else None, wsp, wb, None)
+    assert q2(32, 48, w2, _t(rows=32, K=48), ws, 4096) == -2         # transposed output has the wrong shape
+    assert q2(24, 48, _t(rows=24, K=48), None, ws, 4096) == -2       # R % 16
+    assert q2(32, 48, w2, w2t, None, 0) == -4
+    assert L.nvfp4_quantize_2d(None, 32, 48, 48, None, ctypes.byref(w2), None, ws, 4096, None) == -1
     # smoothed keys: d / 16 must be a power of two <= 64; the means are required
     mean = ctypes.c_void_p(0x70000)
     t48 = _t(rows=6, K=48)

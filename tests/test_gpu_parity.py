@@ -294,6 +294,49 @@ def test_kv_quant_four_over_six(oracle):
     assert e46 <= e6
 
 
+# ------------------------------------------------- 2-D block scaling (weights)
+
+@pytest.mark.parametrize("R,C", [(16, 16), (48, 272), (256, 256), (1040, 528), (3072, 1024)])
+def test_quantize_2d_weights(oracle, R, C):
+    """One scale per 16x16 tile (Sec. 2.2 training recipe): both operands byte-identical to the oracle's."""
+    say(f"[2d] {R}x{C}")
+    wb = wl.normal((R, C), 0.02, 23, R + C)
+    want, want_t = oracle.quantize_2d(wb)
+    got, got_t = nv.nvfp4_quantize_2d(dev_bf16(wb))
+    assert_q_equal(got, want, "W")
+    assert_q_equal(got_t, want_t, "W^T")
+    only, none = nv.nvfp4_quantize_2d(dev_bf16(wb), transposed=False)
+    assert none is None
+    assert_q_equal(only, want, "W without the transposed operand")
+
+
+def test_quantize_2d_serves_fprop_and_dgrad(oracle):
+    """The reason for 2-D scaling: dgrad multiplies by exactly the weights fprop used.  fprop
+    Y = X W^T uses W [N, K]; dgrad dX = dY W uses W^T [K, N]: both from one quantization."""
+    M, N, K = 160, 272, 192
+    xb = wl.activation_with_outliers(M, K, 24, 0)
+    wb = wl.normal((N, K), 0.02, 24, 1)
+    dyb = wl.normal((M, N), 1e-3, 24, 2)
+    ow, owt = oracle.quantize_2d(wb)
+    gw, gwt = nv.nvfp4_quantize_2d(dev_bf16(wb))
+    assert_q_equal(gw, ow, "W")
+    assert_q_equal(gwt, owt, "W^T")
+    ox, ody = oracle.quantize(xb), oracle.quantize(dyb)
+    gx, gdy = nv.nvfp4_quantize(dev_bf16(xb)), nv.nvfp4_quantize(dev_bf16(dyb))
+    Y, S = oracle.gemm(ox, ow)
+    assert_gemm_close(nv.nvfp4_gemm(gx, gw).cpu().numpy(), Y, S, "fprop on 2-D weights")
+    Y, S = oracle.gemm(ody, owt)
+    assert_gemm_close(nv.nvfp4_gemm(gdy, gwt).cpu().numpy(), Y, S, "dgrad on the same weights")
+    # given scale, strided input
+    big = torch.zeros((N, K + 64), dtype=torch.bfloat16, device="cuda")
+    big[:, :K] = dev_bf16(wb)
+    gs = torch.tensor([0.003], dtype=torch.float32, device="cuda")
+    a, at = nv.nvfp4_quantize_2d(big[:, :K], global_scale_in=gs)
+    b, bt = oracle.quantize_2d(wb, global_scale_in=0.003)
+    assert_q_equal(a, b, "strided, given scale")
+    assert_q_equal(at, bt, "strided, given scale, transposed")
+
+
 # ------------------------------------------- smoothed keys, gathered reconstruction
 
 def _oracle_k_path(oracle, kb2d):
