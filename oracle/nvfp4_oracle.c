@@ -338,6 +338,40 @@ void nvfp4o_dequant_bf16(const uint8_t *codes, const uint8_t *scales, float glob
     }
 }
 
+/* ------------------------------------------- random Hadamard transform */
+
+/* Random Hadamard transform of a weight-gradient operand (Sec. 2.2: "RHT before quantization
+ * on the operands of the weight-gradient GEMM").  X [R, C] is contracted over R (tokens); every
+ * group of 16 consecutive rows of a column, v = X[16g .. 16g+15, c], becomes
+ *   y = (1/4) H16 diag(s) v,   H16[i][j] = (-1)^popcount(i & j),   s_j = -1 if bit j of
+ * sign_mask is set, else +1
+ * (the sign vector is the caller's random draw).  (1/4) H16 diag(s) is orthogonal, so applying
+ * it to both operands of the GEMM leaves their product unchanged.  The paper gives no
+ * arithmetic; the reading: the sums in fp64 (exact for columns whose 16 values span less than
+ * 2^40), one rounding to bf16; the result is then quantized along R like any operand. */
+void nvfp4o_rht_rows(const uint16_t *x, int64_t R, int64_t C, int64_t ld, unsigned sign_mask,
+                     uint16_t *out)
+{
+    int64_t g;
+#pragma omp parallel for schedule(static)
+    for (g = 0; g < R / 16; ++g) {
+        int64_t c;
+        for (c = 0; c < C; ++c) {
+            double v[16];
+            int i, j;
+            for (j = 0; j < 16; ++j) {
+                v[j] = nvfp4o_bf16_decode(x[(16 * g + j) * ld + c]);
+                if ((sign_mask >> j) & 1u) v[j] = -v[j];
+            }
+            for (i = 0; i < 16; ++i) {
+                double y = 0.0;
+                for (j = 0; j < 16; ++j) y += (__builtin_popcount((unsigned)(i & j)) & 1) ? -v[j] : v[j];
+                out[(16 * g + i) * C + c] = nvfp4o_bf16_rne(0.25 * y);
+            }
+        }
+    }
+}
+
 /* ------------------------------------------------------- K-smoothing (KV) */
 
 /* K-smoothing (Sec. 3.2, Eq. 6): every cached key row (one token, one head) has its mean

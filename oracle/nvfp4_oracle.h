@@ -51,6 +51,11 @@ void nvfp4o_dequant_f64(const uint8_t *codes, const uint8_t *scales, float globa
 void nvfp4o_dequant_bf16(const uint8_t *codes, const uint8_t *scales, float global_scale,
                          int64_t rows, int64_t K, uint16_t *out);
 
+/* Random Hadamard transform along the rows (groups of 16) of a weight-gradient operand
+ * (Sec. 2.2): out [R, C] bf16 = RN_bf16((1/4) H16 diag(s) x) per group and column. */
+void nvfp4o_rht_rows(const uint16_t *x, int64_t R, int64_t C, int64_t ld, unsigned sign_mask,
+                     uint16_t *out);
+
 /* K-smoothing of the key cache (Sec. 3.2, Eq. 6): x bf16 [rows, d] -> per-row mean (bf16) and
  * the smoothed rows RN_bf16(x - mean) (bf16), which are then quantized like any tensor;
  * reconstruction RN_bf16(x^ + mean). */

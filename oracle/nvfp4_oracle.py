@@ -57,6 +57,8 @@ def lib():
         L.nvfp4o_dequant_f64.argtypes = [u8p, u8p, c.c_float, i64, i64, f64p]
         L.nvfp4o_dequant_bf16.restype = None
         L.nvfp4o_dequant_bf16.argtypes = [u8p, u8p, c.c_float, i64, i64, u16p]
+        L.nvfp4o_rht_rows.restype = None
+        L.nvfp4o_rht_rows.argtypes = [u16p, i64, i64, i64, c.c_uint, u16p]
         L.nvfp4o_kv_smooth.restype = None
         L.nvfp4o_kv_smooth.argtypes = [u16p, i64, i64, u16p, u16p]
         L.nvfp4o_dequant_bf16_smooth.restype = None
@@ -145,6 +147,16 @@ def quantize_2d(x_bits, global_scale_in=None):
                              _p(scales, ctypes.c_uint8), _p(codes_t, ctypes.c_uint8),
                              _p(scales_t, ctypes.c_uint8), ctypes.byref(gs_out))
     return Q(codes, scales, gs_out.value), Q(codes_t, scales_t, gs_out.value)
+
+
+def rht_rows(x_bits, sign_mask):
+    """Random Hadamard transform along the rows (groups of 16) of x_bits [R, C]; returns bf16 bits [R, C]."""
+    x = _u16(x_bits)
+    R, C = x.shape
+    assert R % 16 == 0
+    out = np.empty((R, C), np.uint16)
+    lib().nvfp4o_rht_rows(_p(x, ctypes.c_uint16), R, C, C, int(sign_mask) & 0xFFFF, _p(out, ctypes.c_uint16))
+    return out
 
 
 def kv_smooth(x_bits):

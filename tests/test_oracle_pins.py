@@ -578,3 +578,58 @@ def test_quantize_2d_serves_the_transposed_operand(oracle):
     # 1-D scales can only be finer: the 2-D error is never smaller in total
     xf = wl.bf16_bits_to_f32(xb).astype(np.float64)
     assert np.linalg.norm(xf - oracle.dequant_f64(q)) >= np.linalg.norm(xf - oracle.dequant_f64(oracle.quantize(xb))) * 0.999
+
+
+# ----------------------------------------------------- random Hadamard transform
+
+def _h16():
+    i = np.arange(16)
+    return np.where(np.array([[bin(a & b).count("1") & 1 for b in i] for a in i]), -1.0, 1.0)
+
+
+def test_rht_is_the_scaled_sylvester_matrix(oracle):
+    """Sec. 2.2: the transform of unit vectors spells out (1/4) H16 diag(s); H16 is the Kronecker
+    power of [[1, 1], [1, -1]] (scipy's construction), and the transform is orthogonal."""
+    from scipy.linalg import hadamard
+    assert (_h16() == hadamard(16)).all()
+    mask = 0b1010_0011_0101_1100
+    s = np.array([-1.0 if (mask >> j) & 1 else 1.0 for j in range(16)])
+    eye = np.eye(16, dtype=np.float32) * 4.0                       # 4 e_j: the images are exact in bf16
+    y = wl.bf16_bits_to_f32(oracle.rht_rows(bits(eye), mask))
+    assert (y == hadamard(16) * s[None, :]).all()
+    T = hadamard(16) * s[None, :] / 4.0
+    assert (T @ T.T == np.eye(16)).all()
+
+
+def test_rht_on_integers_is_exact_and_preserves_the_product(oracle):
+    """Small-integer operands: every sum is exact in bf16 after the 1/4 only if divisible, so use
+    multiples of 4; then (T a)^T (T b) = a^T b exactly, column by column, group by group."""
+    g = np.random.default_rng(31)
+    mask = int(g.integers(0, 1 << 16))
+    a = (g.integers(-3, 4, size=(64, 5)) * 4).astype(np.float32)
+    b = (g.integers(-3, 4, size=(64, 7)) * 4).astype(np.float32)
+    ta = wl.bf16_bits_to_f32(oracle.rht_rows(bits(a), mask)).astype(np.float64)
+    tb = wl.bf16_bits_to_f32(oracle.rht_rows(bits(b), mask)).astype(np.float64)
+    s = np.array([-1.0 if (mask >> j) & 1 else 1.0 for j in range(16)])
+    T = _h16() * s[None, :] / 4.0
+    for grp in range(4):
+        assert (ta[16 * grp:16 * grp + 16] == T @ a[16 * grp:16 * grp + 16].astype(np.float64)).all()
+    assert (ta.T @ tb == a.astype(np.float64).T @ b.astype(np.float64)).all()
+
+
+def test_rht_rounds_once_to_bf16(oracle):
+    g = np.random.default_rng(32)
+    mask = 0x9A3C
+    xb = wl.to_bf16_bits(g.standard_normal((32, 6)).astype(np.float32))
+    x = wl.bf16_bits_to_f32(xb)
+    y = oracle.rht_rows(xb, mask)
+    s = [(-1 if (mask >> j) & 1 else 1) for j in range(16)]
+    H = _h16()
+    for grp in range(2):
+        for c in range(6):
+            v = [Fraction(float(x[16 * grp + j, c])) * s[j] for j in range(16)]
+            for i in range(16):
+                exact = sum(v[j] * int(H[i, j]) for j in range(16)) / 4
+                ef = float(exact)
+                assert Fraction(ef) == exact                   # fits fp32 here: torch's cast is then the single rounding
+                assert y[16 * grp + i, c] == _bf16_of_exact(ef)
