@@ -217,6 +217,12 @@ def measure_rows(nv, wl, torch, np):
     qWt = qtime(W, 1, "quantize_T_W_14336x3072")
     qdYt = qtime(dY, 1, "quantize_T_dY_17600x14336")
     qXt = qtime(X, 1, "quantize_T_X_17600x3072")
+    # weight-gradient operand with the random Hadamard transform in front of the transposed quantizer
+    qrht = nv.NVFP4Tensor(F, Mt, dev)
+    ms = _time_op(nv, torch, nv.OP_QUANTIZE_RHT, lambda: nv.nvfp4_quantize_rht(dY, 0x9A3C, out=qrht, workspace=ws), 5)
+    res["quantize_rht_T_dY_17600x14336"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * Mt * F / ms / 1e6, 1),
+                                            "frac_hbm": round(B_PER_ELEM * Mt * F / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    del qrht
     # weights with one scale per 16x16 tile: W and W^T from one pass (2.5625 B/element per operand written)
     ms = _time_op(nv, torch, nv.OP_QUANTIZE_2D, lambda: nv.nvfp4_quantize_2d(W, workspace=ws), 10)
     res["quantize_2d_W_and_WT_14336x3072"] = {"ms": round(ms, 4), "GBs": round((2.0 + 2 * 0.5625) * F * D / ms / 1e6, 1),

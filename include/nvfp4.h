@@ -67,7 +67,8 @@ enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2
        NVFP4_OP_KV_DEQUANT = 4,
        NVFP4_OP_GEMM_ACT_QUANT_GEMM = 5 /* timing only: the GEMM kernel inside nvfp4_gemm_act_quant */,
        NVFP4_OP_QUANTIZE_4OVER6 = 6, NVFP4_OP_KV_QUANT_4OVER6 = 7, NVFP4_OP_KV_QUANT_K = 8,
-       NVFP4_OP_KV_DEQUANT_GATHER = 9, NVFP4_OP_QUANTIZE_2D = 10 };
+       NVFP4_OP_KV_DEQUANT_GATHER = 9, NVFP4_OP_QUANTIZE_2D = 10,
+       NVFP4_OP_QUANTIZE_RHT = 11 };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
@@ -101,6 +102,26 @@ int nvfp4_quantize(const void *x_bf16, int64_t R, int64_t C, int64_t ld, int blo
 int nvfp4_quantize_4over6(const void *x_bf16, int64_t R, int64_t C, int64_t ld,
                           const float *global_scale_in, nvfp4_tensor *out,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Quantizer for the operands of the weight-gradient GEMM with the Random
+ * Hadamard Transform in front (Sec. 2.2 "Multi-Shot AR NVFP4 Training": RHT
+ * before quantization on the operands of the weight-gradient GEMM).  x_bf16
+ * [R, C] is contracted over R (tokens).  Every group of 16 consecutive rows of a
+ * column, v = x[16g .. 16g+15, c], is replaced by
+ *   y = RN_bf16( (1/4) H16 diag(s) v ),  H16[i][j] = (-1)^popcount(i & j),
+ *   s_j = -1 where bit j of sign_mask is set, +1 otherwise
+ * (sums in fp64: exact for groups whose values span less than 2^40), and y is
+ * quantized along R exactly as nvfp4_quantize(block_axis = 1) would: out has
+ * rows = C, K = R, the tensor scale comes from the amax of y.  The transform
+ * is orthogonal: applied with the SAME sign_mask to both operands (dY and X) it
+ * leaves the product dY^T X unchanged while spreading outliers over 16 tokens.
+ * sign_mask: the caller's random draw, low 16 bits.  R % 16 == 0, C % 8 == 0.
+ * workspace: nvfp4_workspace_bytes(NVFP4_OP_QUANTIZE_RHT, R, C, 0).
+ */
+int nvfp4_quantize_rht(const void *x_bf16, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
+                       const float *global_scale_in, nvfp4_tensor *out,
+                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Weight quantizer with 2-D block scaling (Sec. 2.2 "Multi-Shot AR NVFP4

@@ -19,7 +19,7 @@ ACT_NONE, ACT_GELU_TANH = 0, 1
 OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT, OP_GEMM_ACT_QUANT_GEMM = 0, 1, 2, 3, 4, 5
 OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6, OP_KV_QUANT_K, OP_KV_DEQUANT_GATHER = 6, 7, 8, 9
 KV_MAX_CHUNKS = 64
-OP_QUANTIZE_2D = 10
+OP_QUANTIZE_2D, OP_QUANTIZE_RHT = 10, 11
 
 
 class _CTensor(ctypes.Structure):
@@ -60,6 +60,8 @@ def lib():
         L.nvfp4_quantize_4over6.argtypes = [vp, i64, i64, i64, vp, tp, vp, sz, vp]
         L.nvfp4_kv_quant_4over6.restype = c.c_int
         L.nvfp4_kv_quant_4over6.argtypes = [vp, i64, i64, i64, tp, vp, sz, vp]
+        L.nvfp4_quantize_rht.restype = c.c_int
+        L.nvfp4_quantize_rht.argtypes = [vp, i64, i64, i64, c.c_uint32, vp, tp, vp, sz, vp]
         L.nvfp4_quantize_2d.restype = c.c_int
         L.nvfp4_quantize_2d.argtypes = [vp, i64, i64, i64, vp, tp, tp, vp, sz, vp]
         L.nvfp4_kv_quant_k.restype = c.c_int
@@ -204,6 +206,21 @@ def nvfp4_kv_quant_4over6(kv, out=None, workspace=None, stream=None):
     ct = out.c()
     _check(lib().nvfp4_kv_quant_4over6(_ptr(kv), T, H, d, ctypes.byref(ct), _ptr(workspace), workspace.numel(),
                                        _stream(stream)))
+    return out
+
+
+def nvfp4_quantize_rht(x, sign_mask, global_scale_in=None, out=None, workspace=None, stream=None):
+    """x: bf16 [R, C], contracted over R.  Random Hadamard transform along R (groups of 16) with the
+    16-bit sign mask, then the transposed quantizer: returns NVFP4Tensor [C, R]."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.stride(1) == 1
+    R, C = x.shape
+    if out is None:
+        out = NVFP4Tensor(C, R, x.device)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_QUANTIZE_RHT, R, C), x.device)
+    ct = out.c()
+    _check(lib().nvfp4_quantize_rht(_ptr(x), R, C, x.stride(0), int(sign_mask), _ptr(global_scale_in),
+                                    ctypes.byref(ct), _ptr(workspace), workspace.numel(), _stream(stream)))
     return out
 
 

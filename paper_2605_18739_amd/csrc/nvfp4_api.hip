@@ -139,6 +139,30 @@ int nvfp4_kv_quant_4over6(const void *kv_bf16, int64_t T, int64_t H, int64_t d, 
                          static_cast<hipStream_t>(stream), true);
 }
 
+int nvfp4_quantize_rht(const void *x_bf16, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
+                       const float *global_scale_in, nvfp4_tensor *out, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    if (!x_bf16 || !out) return NVFP4_ERR_NULL;
+    if (int rc = check_tensor(out)) return rc;
+    if (R <= 0 || C <= 0 || ld < C || (R & 15) != 0 || (C & 7) != 0 || (sign_mask >> 16) != 0) return NVFP4_ERR_SHAPE;
+    if (out->rows != C || out->K != R) return NVFP4_ERR_SHAPE;
+    if (!aligned16(x_bf16) || (ld & 7) != 0) return NVFP4_ERR_ALIGN;
+    if (!global_scale_in && (!workspace || workspace_bytes < kPartialBytes)) return NVFP4_ERR_WORKSPACE;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 3u)) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timed t(s, NVFP4_OP_QUANTIZE_RHT);
+    const uint16_t *xb = static_cast<const uint16_t *>(x_bf16);
+    uint32_t *partial = static_cast<uint32_t *>(workspace);
+    int n_partial = 0;
+    if (!global_scale_in)
+        if (launch_amax_rht(xb, R, C, ld, sign_mask, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
+    hipError_t e = launch_quantize_cols_rht(xb, R, C, ld, sign_mask, global_scale_in, partial, n_partial,
+                                            out->codes, out->scales, out->global_scale, s);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
 int nvfp4_quantize_2d(const void *w_bf16, int64_t R, int64_t C, int64_t ld, const float *global_scale_in,
                       nvfp4_tensor *out, nvfp4_tensor *out_t, void *workspace, size_t workspace_bytes,
                       void *stream)
@@ -322,6 +346,7 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
     case NVFP4_OP_KV_QUANT_4OVER6:
     case NVFP4_OP_KV_QUANT_K:
     case NVFP4_OP_QUANTIZE_2D:
+    case NVFP4_OP_QUANTIZE_RHT:
         return kPartialBytes;
     case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c: bit 0 = caller supplies H, bit 1 = caller supplies the scale
         if (a <= 0 || b <= 0) return 0;

@@ -270,6 +270,35 @@ __device__ __forceinline__ void smooth_block16(uint32_t (&w)[8], double mu)
     }
 }
 
+// Random Hadamard transform (Sec. 2.2, weight-gradient operands) of one group of 16 values
+// held as eight packed bf16 pairs: y = (1/4) H16 diag(s) v, H16[i][j] = (-1)^popcount(i & j),
+// s_j = -1 where bit j of sign_mask is set.  Fast Walsh-Hadamard butterflies in fp64 (exact
+// while the 16 values span less than 2^40), one rounding to bf16.
+__device__ __forceinline__ void rht_block16(uint32_t (&w)[8], uint32_t sign_mask)
+{
+    double v[16];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        v[2 * i] = (double)bf16lo_to_f32(w[i]);
+        v[2 * i + 1] = (double)bf16hi_to_f32(w[i]);
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if ((sign_mask >> j) & 1u) v[j] = -v[j];
+#pragma unroll
+    for (int h = 1; h < 16; h <<= 1)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if ((i & h) == 0) {
+                const double a = v[i], b = v[i + h];
+                v[i] = a + b;
+                v[i + h] = a - b;
+            }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        w[i] = bf16_rne_signed_from_f64(0.25 * v[2 * i]) | (bf16_rne_signed_from_f64(0.25 * v[2 * i + 1]) << 16);
+}
+
 // global scale from the tensor's largest |bf16| pattern: RN_fp32(amax / 2688), 1 if zero
 __device__ __forceinline__ float global_scale_from_amax_bits(uint32_t amax_bits16)
 {

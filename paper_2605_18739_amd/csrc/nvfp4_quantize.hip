@@ -209,13 +209,61 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
 // output row is written in 64-byte runs.
 // --------------------------------------------------------------------------
 constexpr int kTR = 128, kTC = 256;
+
+// a thread's 16 rows x 8 columns -> column j as eight packed pairs (rows 2i in the low half)
+__device__ __forceinline__ void column_of(const uint4v (&v)[16], int j, uint32_t (&w)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        uint32_t a = v[2 * i][j >> 1], b = v[2 * i + 1][j >> 1];
+        w[i] = (j & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+    }
+}
+
+// Pass 1 for a weight-gradient operand that is Hadamard-transformed along its rows before it is
+// quantized (Sec. 2.2): partial amax of the TRANSFORMED values, same tiles and thread layout as
+// the pass-2 kernel below, tiles dealt over at most kMaxPartials workgroups.
+__global__ __launch_bounds__(256) void amax_rht_kernel(const uint16_t *__restrict__ x, int64_t R, int64_t C,
+                                                       int64_t ld, uint32_t sign_mask,
+                                                       uint32_t *__restrict__ partial)
+{
+    __shared__ uint32_t wave_max[4];
+    const int cg = threadIdx.x & 31, rb = threadIdx.x >> 5;
+    const int64_t tiles_x = (C + kTC - 1) / kTC, tiles_y = (R + kTR - 1) / kTR;
+    uint32_t acc = 0;
+    for (int64_t tile = blockIdx.x; tile < tiles_x * tiles_y; tile += gridDim.x) {
+        const int64_t r = (tile / tiles_x) * kTR + rb * 16, c = (tile % tiles_x) * kTC + cg * 8;
+        if (r < R && c < C) {
+            uint4v v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = *(const uint4v *)(x + (r + i) * ld + c);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                uint32_t w[8];
+                column_of(v, j, w);
+                rht_block16(w, sign_mask);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
+            }
+        }
+    }
+    uint32_t m = wave_max_u32(pk_hmax_u16(acc));
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        partial[blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+}
+
+// RHT: every 16-row group of a column goes through the random Hadamard transform first.
+template <bool RHT = false>
 __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__restrict__ x, int64_t R,
                                                             int64_t C, int64_t ld,
                                                             const float *__restrict__ gs_in,
                                                             const uint32_t *__restrict__ partial,
                                                             int n_partial, uint8_t *__restrict__ codes,
                                                             uint8_t *__restrict__ scales,
-                                                            float *__restrict__ gs_out)
+                                                            float *__restrict__ gs_out,
+                                                            uint32_t sign_mask = 0)
 {
     __shared__ uint32_t lds4[4];
     __shared__ uint2v lds_codes[kTC][kTR / 16 + 1];     // [column][row block], padded
@@ -234,12 +282,8 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__re
 #pragma unroll
         for (int j = 0; j < 8; ++j) {      // column c + j: element j of every loaded vector
             uint32_t w[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                uint32_t a = v[2 * i][j >> 1], b = v[2 * i + 1][j >> 1];
-                // pack rows 2i (low half) and 2i+1 (high half) of this column
-                w[i] = (j & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
-            }
+            column_of(v, j, w);
+            if constexpr (RHT) rht_block16(w, sign_mask);
             uint32_t acc = 0;
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
@@ -543,7 +587,27 @@ hipError_t launch_quantize_cols(const uint16_t *x, int64_t R, int64_t C, int64_t
                                 float *gs_out, hipStream_t s)
 {
     dim3 grid((unsigned)((C + kTC - 1) / kTC), (unsigned)((R + kTR - 1) / kTR));
-    quantize_cols_kernel<<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes, scales, gs_out);
+    quantize_cols_kernel<false><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes, scales, gs_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_amax_rht(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
+                           uint32_t *partial, int *n_partial, hipStream_t s)
+{
+    const int64_t tiles = ((C + kTC - 1) / kTC) * ((R + kTR - 1) / kTR);
+    const int grid = (int)(tiles < kMaxPartials ? tiles : kMaxPartials);
+    *n_partial = grid;
+    amax_rht_kernel<<<grid, 256, 0, s>>>(x, R, C, ld, sign_mask, partial);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_cols_rht(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
+                                    const float *gs_in, const uint32_t *partial, int n_partial,
+                                    uint8_t *codes, uint8_t *scales, float *gs_out, hipStream_t s)
+{
+    dim3 grid((unsigned)((C + kTC - 1) / kTC), (unsigned)((R + kTR - 1) / kTR));
+    quantize_cols_kernel<true><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes, scales,
+                                                    gs_out, sign_mask);
     return hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert {"nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_act_quant", "nvfp4_kv_quant",
             "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string",
             "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6", "nvfp4_kv_quant_k",
-            "nvfp4_kv_dequant_gather", "nvfp4_quantize_2d"} <= set(names)
+            "nvfp4_kv_dequant_gather", "nvfp4_quantize_2d", "nvfp4_quantize_rht"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -92,6 +92,13 @@ def test_gemm_and_kv_reject_bad_arguments_on_the_host():
     assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w16), 1, None, ctypes.byref(out), None, ws, 16, None) == -4
     kv = ctypes.c_void_p(0x60000)
     t = _t(rows=6, K=32)
+    # Hadamard-transformed weight-gradient operand: out is [C, R]; the sign mask has 16 bits
+    rt = _t(rows=48, K=32)
+    qr = lambda R, C, mask, o, wsp, wb: L.nvfp4_quantize_rht(kv, R, C, C, mask, None, ctypes.byref(o), wsp, wb, None)
+    assert qr(32, 48, 0x1FFFF, rt, ws, 4096) == -2
+    assert qr(32, 48, 0x5A5A, w2 if False else _t(rows=32, K=48), ws, 4096) == -2      # out not transposed
+    assert qr(24, 48, 0x5A5A, _t(rows=48, K=24), ws, 4096) == -2                      # R % 16
+    assert qr(32, 48, 0x5A5A, rt, None, 0) == -4
     # 2-D weight scaling: both sides multiples of 16, shapes of both outputs
     w2 = _t(rows=32, K=48)
     w2t = _t(rows=48, K=32)

@@ -294,6 +294,48 @@ def test_kv_quant_four_over_six(oracle):
     assert e46 <= e6
 
 
+# ----------------------------------------------------- random Hadamard transform
+
+@pytest.mark.parametrize("R,C,mask", [(16, 8, 0), (48, 24, 0xFFFF), (128, 256, 0x9A3C), (400, 520, 0x0F5A), (1024, 3072, 0x6D21)])
+def test_quantize_rht(oracle, R, C, mask):
+    """Weight-gradient operand: Hadamard transform along the contraction axis, then the transposed
+    quantizer (Sec. 2.2).  Bytes identical to the oracle's transform followed by its quantizer."""
+    say(f"[rht] {R}x{C} mask {mask:#06x}")
+    xb = wl.activation_with_outliers(R, C, 25, R) if C >= 256 else wl.normal((R, C), 1.0, 25, R)
+    want = oracle.quantize(oracle.rht_rows(xb, mask), block_axis=1)
+    got = nv.nvfp4_quantize_rht(dev_bf16(xb), mask)
+    assert_q_equal(got, want, "rht")
+    gs = torch.tensor([0.0125], dtype=torch.float32, device="cuda")
+    got = nv.nvfp4_quantize_rht(dev_bf16(xb), mask, global_scale_in=gs)
+    assert_q_equal(got, oracle.quantize(oracle.rht_rows(xb, mask), block_axis=1, global_scale_in=0.0125), "rht, given scale")
+
+
+def test_wgrad_with_rht(oracle):
+    """dW = dY^T X with both operands transformed by the same signs: the GEMM equals the oracle's on
+    the oracle's transformed operands; both quantized products approximate the unquantized one (the
+    transform is orthogonal), their errors are reported."""
+    M, N, K = 512, 144, 272
+    g = np.random.default_rng(26)
+    x = g.standard_normal((M, K)).astype(np.float32)
+    x[g.choice(M, 5, replace=False)] *= 40.0                      # a few outlier tokens
+    xb = wl.to_bf16_bits(x)
+    dyb = wl.normal((M, N), 1e-3, 26, 1)
+    mask = 0xB7C5
+    o_dy = oracle.quantize(oracle.rht_rows(dyb, mask), block_axis=1)
+    o_x = oracle.quantize(oracle.rht_rows(xb, mask), block_axis=1)
+    g_dy, g_x = nv.nvfp4_quantize_rht(dev_bf16(dyb), mask), nv.nvfp4_quantize_rht(dev_bf16(xb), mask)
+    assert_q_equal(g_dy, o_dy, "dY")
+    assert_q_equal(g_x, o_x, "X")
+    Y, S = oracle.gemm(o_dy, o_x)
+    got = nv.nvfp4_gemm(g_dy, g_x).cpu().numpy()
+    assert_gemm_close(got, Y, S, "wgrad with RHT")
+    exact = wl.bf16_bits_to_f32(dyb).astype(np.float64).T @ wl.bf16_bits_to_f32(xb).astype(np.float64)
+    plain, _ = oracle.gemm(oracle.quantize(dyb, block_axis=1), oracle.quantize(xb, block_axis=1), want_abs=False)
+    e_rht, e_plain = np.linalg.norm(Y - exact), np.linalg.norm(plain - exact)
+    say(f"        wgrad error vs unquantized product: with RHT {e_rht:.3e}, without {e_plain:.3e}")
+    assert e_rht < 0.2 * np.linalg.norm(exact) and e_plain < 0.2 * np.linalg.norm(exact)
+
+
 # ------------------------------------------------- 2-D block scaling (weights)
 
 @pytest.mark.parametrize("R,C", [(16, 16), (48, 272), (256, 256), (1040, 528), (3072, 1024)])
