@@ -68,7 +68,7 @@ enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2
        NVFP4_OP_GEMM_ACT_QUANT_GEMM = 5 /* timing only: the GEMM kernel inside nvfp4_gemm_act_quant */,
        NVFP4_OP_QUANTIZE_4OVER6 = 6, NVFP4_OP_KV_QUANT_4OVER6 = 7, NVFP4_OP_KV_QUANT_K = 8,
        NVFP4_OP_KV_DEQUANT_GATHER = 9, NVFP4_OP_QUANTIZE_2D = 10,
-       NVFP4_OP_QUANTIZE_RHT = 11 };
+       NVFP4_OP_QUANTIZE_RHT = 11, NVFP4_OP_QUANTIZE_A2A = 12 };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
@@ -219,6 +219,23 @@ typedef struct nvfp4_kv_chunk {
 } nvfp4_kv_chunk;
 int nvfp4_kv_dequant_gather(const nvfp4_kv_chunk *chunks, int n_chunks, void *kv_bf16_out,
                             int64_t H, int64_t d, void *stream);
+
+/*
+ * Packer for the NVFP4 pre-attention all-to-all of sequence-parallel inference
+ * (Appendix "Sequence Parallelism Inference", Eq. 11): the local Q (or K, V)
+ * [T = L/P, H, d] is cast to NVFP4 along d and laid out as P slabs, one per
+ * destination device, slab p holding heads p*H/P .. (p+1)*H/P - 1 of every
+ * local token:
+ *   out row (p * T + t) * (H/P) + h'  <-  x[t, p*H/P + h', :]
+ * so that each slab (T*(H/P) rows of codes, of scales) is one contiguous
+ * send buffer at ~4.5 bit per element; all slabs share the call's global
+ * scale.  The exchange itself is not part of this library.  H % P == 0;
+ * out: rows = T*H, K = d.  global_scale_in and workspace as nvfp4_quantize
+ * (workspace size: NVFP4_OP_QUANTIZE_A2A).
+ */
+int nvfp4_quantize_for_all_to_all(const void *x_bf16, int64_t T, int64_t H, int64_t d, int64_t P,
+                                  const float *global_scale_in, nvfp4_tensor *out,
+                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * KV-cache reconstruction (Sec. 3.2): kv_bf16_out[t,h,:] = RN_bf16(code *

@@ -19,7 +19,7 @@ ACT_NONE, ACT_GELU_TANH = 0, 1
 OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT, OP_GEMM_ACT_QUANT_GEMM = 0, 1, 2, 3, 4, 5
 OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6, OP_KV_QUANT_K, OP_KV_DEQUANT_GATHER = 6, 7, 8, 9
 KV_MAX_CHUNKS = 64
-OP_QUANTIZE_2D, OP_QUANTIZE_RHT = 10, 11
+OP_QUANTIZE_2D, OP_QUANTIZE_RHT, OP_QUANTIZE_A2A = 10, 11, 12
 
 
 class _CTensor(ctypes.Structure):
@@ -60,6 +60,8 @@ def lib():
         L.nvfp4_quantize_4over6.argtypes = [vp, i64, i64, i64, vp, tp, vp, sz, vp]
         L.nvfp4_kv_quant_4over6.restype = c.c_int
         L.nvfp4_kv_quant_4over6.argtypes = [vp, i64, i64, i64, tp, vp, sz, vp]
+        L.nvfp4_quantize_for_all_to_all.restype = c.c_int
+        L.nvfp4_quantize_for_all_to_all.argtypes = [vp, i64, i64, i64, i64, vp, tp, vp, sz, vp]
         L.nvfp4_quantize_rht.restype = c.c_int
         L.nvfp4_quantize_rht.argtypes = [vp, i64, i64, i64, c.c_uint32, vp, tp, vp, sz, vp]
         L.nvfp4_quantize_2d.restype = c.c_int
@@ -206,6 +208,20 @@ def nvfp4_kv_quant_4over6(kv, out=None, workspace=None, stream=None):
     ct = out.c()
     _check(lib().nvfp4_kv_quant_4over6(_ptr(kv), T, H, d, ctypes.byref(ct), _ptr(workspace), workspace.numel(),
                                        _stream(stream)))
+    return out
+
+
+def nvfp4_quantize_for_all_to_all(x, P, global_scale_in=None, out=None, workspace=None, stream=None):
+    """x: contiguous bf16 [T, H, d]; NVFP4 along d, rows regrouped into P per-destination slabs of H/P heads."""
+    assert x.dtype == torch.bfloat16 and x.dim() == 3 and x.is_contiguous()
+    T, H, d = x.shape
+    if out is None:
+        out = NVFP4Tensor(T * H, d, x.device)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_QUANTIZE_A2A, T, H, d), x.device)
+    ct = out.c()
+    _check(lib().nvfp4_quantize_for_all_to_all(_ptr(x), T, H, d, P, _ptr(global_scale_in), ctypes.byref(ct),
+                                               _ptr(workspace), workspace.numel(), _stream(stream)))
     return out
 
 

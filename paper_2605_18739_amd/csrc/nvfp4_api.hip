@@ -139,6 +139,30 @@ int nvfp4_kv_quant_4over6(const void *kv_bf16, int64_t T, int64_t H, int64_t d, 
                          static_cast<hipStream_t>(stream), true);
 }
 
+int nvfp4_quantize_for_all_to_all(const void *x_bf16, int64_t T, int64_t H, int64_t d, int64_t P,
+                                  const float *global_scale_in, nvfp4_tensor *out, void *workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    if (!x_bf16 || !out) return NVFP4_ERR_NULL;
+    if (int rc = check_tensor(out)) return rc;
+    if (T <= 0 || H <= 0 || d <= 0 || P <= 0 || (d & 15) != 0 || H % P != 0) return NVFP4_ERR_SHAPE;
+    if (out->rows != T * H || out->K != d) return NVFP4_ERR_SHAPE;
+    if (!aligned16(x_bf16)) return NVFP4_ERR_ALIGN;
+    if (!global_scale_in && (!workspace || workspace_bytes < kPartialBytes)) return NVFP4_ERR_WORKSPACE;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 3u)) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timed t(s, NVFP4_OP_QUANTIZE_A2A);
+    const uint16_t *xb = static_cast<const uint16_t *>(x_bf16);
+    uint32_t *partial = static_cast<uint32_t *>(workspace);
+    int n_partial = 0;
+    if (!global_scale_in)
+        if (launch_amax(xb, T * H, d, d, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
+    hipError_t e = launch_quantize_rows_slabs(xb, T, H, d, (int)(H / P), global_scale_in, partial, n_partial,
+                                              out->codes, out->scales, out->global_scale, s);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
 int nvfp4_quantize_rht(const void *x_bf16, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
                        const float *global_scale_in, nvfp4_tensor *out, void *workspace,
                        size_t workspace_bytes, void *stream)
@@ -347,6 +371,7 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
     case NVFP4_OP_KV_QUANT_K:
     case NVFP4_OP_QUANTIZE_2D:
     case NVFP4_OP_QUANTIZE_RHT:
+    case NVFP4_OP_QUANTIZE_A2A:
         return kPartialBytes;
     case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c: bit 0 = caller supplies H, bit 1 = caller supplies the scale
         if (a <= 0 || b <= 0) return 0;

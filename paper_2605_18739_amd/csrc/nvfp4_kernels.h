@@ -20,6 +20,11 @@ hipError_t launch_quantize_cols(const uint16_t *x, int64_t R, int64_t C, int64_t
 hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, const float *gs, int64_t rows,
                                int64_t K, uint16_t *out, hipStream_t s);
 
+// [T, H, d] quantized along d with the rows regrouped into H / slab_heads per-destination slabs
+hipError_t launch_quantize_rows_slabs(const uint16_t *x, int64_t T, int64_t H, int64_t d, int slab_heads,
+                                      const float *gs_in, const uint32_t *partial, int n_partial,
+                                      uint8_t *codes, uint8_t *scales, float *gs_out, hipStream_t s);
+
 // Weight-gradient operands with the random Hadamard transform along the contraction axis (rows of x,
 // groups of 16) before the transposed quantizer; sign_mask bit j = 1: s_j = -1.
 hipError_t launch_amax_rht(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,

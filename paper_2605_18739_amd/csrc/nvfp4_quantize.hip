@@ -135,6 +135,9 @@ __device__ __forceinline__ float resolve_global_scale(const float *gs_in, const 
 // (two 128-bit loads, one 64-bit code store, one scale byte).
 // SEARCH: the Four-over-Six scale search of Eq. 12-13 instead of the plain max -> 6 rule.
 // SMOOTH: the row means of Eq. 6 (row_mean, one bf16 per row) are removed first.
+// slab_heads > 0: the rows are (token, head) pairs of a [T, H, d] tensor and the output is
+// regrouped into H / slab_heads slabs of slab_heads heads each, [slab][token][head in slab]
+// (what the pre-attention all-to-all of sequence-parallel inference sends to each peer).
 // --------------------------------------------------------------------------
 template <bool CONTIG, bool SEARCH = false, bool SMOOTH = false>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
@@ -144,7 +147,8 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
                                                             int n_partial, uint8_t *__restrict__ codes,
                                                             uint8_t *__restrict__ scales,
                                                             float *__restrict__ gs_out,
-                                                            const uint16_t *__restrict__ row_mean = nullptr)
+                                                            const uint16_t *__restrict__ row_mean = nullptr,
+                                                            int heads = 0, int slab_heads = 0)
 {
     __shared__ uint32_t lds4[4];
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
@@ -189,12 +193,19 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
                     encode_block16(w, e4m3_to_f32(sbyte), sg, c0, c1);
                 }
                 uint2v cc = {c0, c1};
+                int64_t go = g;                       // output block index
+                if (slab_heads > 0) {
+                    const int64_t row = g / nb_row, b = g - row * nb_row;
+                    const int64_t t = row / heads, h = row - t * heads;
+                    const int64_t slab = h / slab_heads, hl = h - slab * slab_heads;
+                    go = ((slab * (R / heads) + t) * slab_heads + hl) * nb_row + b;
+                }
 #if NVFP4_Q_PLAIN_STORE
-                *(uint2v *)(codes + (g << 3)) = cc;
+                *(uint2v *)(codes + (go << 3)) = cc;
 #else
-                __builtin_nontemporal_store(cc, (uint2v *)(codes + (g << 3)));
+                __builtin_nontemporal_store(cc, (uint2v *)(codes + (go << 3)));
 #endif
-                scales[g] = (uint8_t)sbyte;
+                scales[go] = (uint8_t)sbyte;
             }
         }
     }
@@ -628,6 +639,16 @@ hipError_t launch_quantize_tiles(const uint16_t *x, int64_t R, int64_t C, int64_
     dim3 grid((unsigned)((C + 255) / 256), (unsigned)((R + 255) / 256));
     quantize_tiles_kernel<<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes, scales, codes_t,
                                                scales_t, gs_out, gs_out_t);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_rows_slabs(const uint16_t *x, int64_t T, int64_t H, int64_t d, int slab_heads,
+                                      const float *gs_in, const uint32_t *partial, int n_partial,
+                                      uint8_t *codes, uint8_t *scales, float *gs_out, hipStream_t s)
+{
+    int grid = grid_for(T * H * (d >> 4), NVFP4_Q_GRID);
+    quantize_rows_kernel<true, false, false><<<grid, 256, 0, s>>>(x, T * H, d, d, gs_in, partial, n_partial, codes,
+                                                                  scales, gs_out, nullptr, (int)H, slab_heads);
     return hipGetLastError();
 }
 

@@ -24,7 +24,8 @@ def test_library_exports_every_declared_symbol():
     assert {"nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_act_quant", "nvfp4_kv_quant",
             "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string",
             "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6", "nvfp4_kv_quant_k",
-            "nvfp4_kv_dequant_gather", "nvfp4_quantize_2d", "nvfp4_quantize_rht"} <= set(names)
+            "nvfp4_kv_dequant_gather", "nvfp4_quantize_2d", "nvfp4_quantize_rht",
+            "nvfp4_quantize_for_all_to_all"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -92,6 +93,11 @@ def test_gemm_and_kv_reject_bad_arguments_on_the_host():
     assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w16), 1, None, ctypes.byref(out), None, ws, 16, None) == -4
     kv = ctypes.c_void_p(0x60000)
     t = _t(rows=6, K=32)
+    # all-to-all packer: the heads must divide over the peers
+    a2a = lambda T_, H_, d_, P_, o: L.nvfp4_quantize_for_all_to_all(kv, T_, H_, d_, P_, None, ctypes.byref(o), ws, 4096, None)
+    assert a2a(2, 3, 32, 2, t) == -2
+    assert a2a(2, 3, 32, 0, t) == -2
+    assert a2a(2, 4, 32, 2, t) == -2                                                  # rows != T*H
     # Hadamard-transformed weight-gradient operand: out is [C, R]; the sign mask has 16 bits
     rt = _t(rows=48, K=32)
     qr = lambda R, C, mask, o, wsp, wb: L.nvfp4_quantize_rht(kv, R, C, C, mask, None, ctypes.byref(o), wsp, wb, None)

@@ -294,6 +294,29 @@ def test_kv_quant_four_over_six(oracle):
     assert e46 <= e6
 
 
+# ------------------------------------------------------- all-to-all send buffers
+
+@pytest.mark.parametrize("T,H,d,P", [(5, 4, 16, 1), (33, 24, 128, 4), (220, 24, 128, 8), (7, 6, 64, 3)])
+def test_quantize_for_all_to_all(oracle, T, H, d, P):
+    """Appendix "Sequence Parallelism Inference", Eq. 11: NVFP4 along d, rows regrouped into one
+    contiguous slab per destination.  The bytes are the oracle's, permuted by plain indexing."""
+    say(f"[a2a] {T}x{H}x{d} over {P} peers")
+    xb = wl.kv_tensor(T, H, d, 27, T)
+    want = oracle.quantize(xb.reshape(T * H, d))
+    got = nv.nvfp4_quantize_for_all_to_all(dev_bf16(xb.reshape(T * H, d)).reshape(T, H, d), P)
+    codes, scales, gs = host_q(got)
+    Hp = H // P
+    perm = lambda a: a.reshape(T, P, Hp, -1).transpose(1, 0, 2, 3).reshape(T * H, -1)
+    assert gs.view(np.uint32) == np.float32(want.global_scale).view(np.uint32)
+    assert (codes == perm(want.codes)).all() and (scales == perm(want.scales)).all()
+    # slab p is what device p receives: heads p*Hp.. of every local token, ready for the plain dequantizer
+    p = P - 1
+    slab = nv.NVFP4Tensor(T * Hp, d, "cuda", got.codes[p * T * Hp:(p + 1) * T * Hp], got.scales[p * T * Hp:(p + 1) * T * Hp], got.global_scale)
+    back = nv.bits_from_bf16(nv.nvfp4_kv_dequant(slab, T, Hp, d)).reshape(T, Hp, d)
+    ref = oracle.dequant_bf16(want).reshape(T, H, d)[:, p * Hp:(p + 1) * Hp]
+    assert (back == ref).all()
+
+
 # ----------------------------------------------------- random Hadamard transform
 
 @pytest.mark.parametrize("R,C,mask", [(16, 8, 0), (48, 24, 0xFFFF), (128, 256, 0x9A3C), (400, 520, 0x0F5A), (1024, 3072, 0x6D21)])
