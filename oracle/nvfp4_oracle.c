@@ -455,6 +455,49 @@ void nvfp4o_gemm(const uint8_t *codesA, const uint8_t *scalesA, float gsA,
 
 /* ------------------------------------------------------------ activation */
 
+/* ----------------------------------------------------- LoRA side branch */
+
+/* Low-rank adapter beside the quantized weight (Sec. 2.2 "Few-step Distillation in NVFP4":
+ * W ~ Dequant(Q(W0)) + (alpha_LoRA / r) B A, adapter weights in bf16; Sec. 3.1: deployed as a
+ * separate branch or fused).  Down projection: T[m, j] = RN_bf16(sum_k X[m,k] A[j,k]), the sum
+ * in fp64 over the UNQUANTIZED bf16 activations (the adapter branch runs in bf16). */
+void nvfp4o_lora_down(const uint16_t *x, const uint16_t *a, int64_t M, int64_t K, int64_t r,
+                      uint16_t *t_out)
+{
+    int64_t m;
+#pragma omp parallel for schedule(static)
+    for (m = 0; m < M; ++m) {
+        int64_t j, k;
+        for (j = 0; j < r; ++j) {
+            double acc = 0.0;
+            for (k = 0; k < K; ++k) acc += nvfp4o_bf16_decode(x[m * K + k]) * nvfp4o_bf16_decode(a[j * K + k]);
+            t_out[m * r + j] = nvfp4o_bf16_rne(acc);
+        }
+    }
+}
+
+/* Low-rank update added to a GEMM result: Y[i, n] += scale * sum_j T[m_i, j] B[n, j] and
+ * S[i, n] += |scale| * sum_j |T B| (T [M, r], B [N, r] bf16; rows as in nvfp4o_gemm). */
+void nvfp4o_lora_up_add(const uint16_t *t, const uint16_t *b, int64_t N, int64_t r, double scale,
+                        const int64_t *rows, int64_t nrows, double *Y, double *S)
+{
+    int64_t i;
+#pragma omp parallel for schedule(static)
+    for (i = 0; i < nrows; ++i) {
+        int64_t m = rows ? rows[i] : i, n, j;
+        for (n = 0; n < N; ++n) {
+            double y = 0.0, sabs = 0.0;
+            for (j = 0; j < r; ++j) {
+                double p = nvfp4o_bf16_decode(t[m * r + j]) * nvfp4o_bf16_decode(b[n * r + j]);
+                y += p;
+                sabs += fabs(p);
+            }
+            Y[i * N + n] += scale * y;
+            if (S) S[i * N + n] += fabs(scale) * sabs;
+        }
+    }
+}
+
 /* GELU, tanh form: 0.5 y (1 + tanh( sqrt(2/pi) (y + 0.044715 y^3) )). */
 double nvfp4o_gelu_tanh(double y)
 {

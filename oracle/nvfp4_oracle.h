@@ -56,6 +56,13 @@ void nvfp4o_dequant_bf16(const uint8_t *codes, const uint8_t *scales, float glob
 void nvfp4o_rht_rows(const uint16_t *x, int64_t R, int64_t C, int64_t ld, unsigned sign_mask,
                      uint16_t *out);
 
+/* LoRA side branch (Sec. 2.2 / 3.1): T = RN_bf16(X A^T) on bf16 activations, and the update
+ * Y += scale * T B^T added to a GEMM result (S += the matching sum of absolute terms). */
+void nvfp4o_lora_down(const uint16_t *x, const uint16_t *a, int64_t M, int64_t K, int64_t r,
+                      uint16_t *t_out);
+void nvfp4o_lora_up_add(const uint16_t *t, const uint16_t *b, int64_t N, int64_t r, double scale,
+                        const int64_t *rows, int64_t nrows, double *Y, double *S);
+
 /* K-smoothing of the key cache (Sec. 3.2, Eq. 6): x bf16 [rows, d] -> per-row mean (bf16) and
  * the smoothed rows RN_bf16(x - mean) (bf16), which are then quantized like any tensor;
  * reconstruction RN_bf16(x^ + mean). */

@@ -57,6 +57,11 @@ def lib():
         L.nvfp4o_dequant_f64.argtypes = [u8p, u8p, c.c_float, i64, i64, f64p]
         L.nvfp4o_dequant_bf16.restype = None
         L.nvfp4o_dequant_bf16.argtypes = [u8p, u8p, c.c_float, i64, i64, u16p]
+        L.nvfp4o_lora_down.restype = None
+        L.nvfp4o_lora_down.argtypes = [u16p, u16p, i64, i64, i64, u16p]
+        L.nvfp4o_lora_up_add.restype = None
+        L.nvfp4o_lora_up_add.argtypes = [u16p, u16p, i64, i64, c.c_double, c.POINTER(c.c_int64), i64,
+                                         c.POINTER(c.c_double), c.POINTER(c.c_double)]
         L.nvfp4o_rht_rows.restype = None
         L.nvfp4o_rht_rows.argtypes = [u16p, i64, i64, i64, c.c_uint, u16p]
         L.nvfp4o_kv_smooth.restype = None
@@ -205,6 +210,30 @@ def gemm(qa, qw, rows=None, want_abs=True):
                       ctypes.c_float(float(qw.global_scale)),
                       M, N, K, rp, nr, _p(Y, ctypes.c_double),
                       _p(S, ctypes.c_double) if want_abs else None)
+    return Y, S
+
+
+def lora_down(x_bits, a_bits):
+    """T = RN_bf16(X A^T): x_bits [M, K], a_bits [r, K] bf16 bit patterns -> [M, r]."""
+    x, a = _u16(x_bits), _u16(a_bits)
+    (M, K), (r, K2) = x.shape, a.shape
+    assert K == K2
+    t = np.empty((M, r), np.uint16)
+    lib().nvfp4o_lora_down(_p(x, ctypes.c_uint16), _p(a, ctypes.c_uint16), M, K, r, _p(t, ctypes.c_uint16))
+    return t
+
+
+def gemm_lora(qa, qw, t_bits, b_bits, scale, rows=None):
+    """GEMM of the quantized operands plus scale * T B^T (T [M, r], B [N, r] bf16 bits). Returns (Y, S)."""
+    Y, S = gemm(qa, qw, rows=rows)
+    t, b = _u16(t_bits), _u16(b_bits)
+    assert t.shape[0] == qa.rows and b.shape[0] == qw.rows and t.shape[1] == b.shape[1]
+    rp, nr = None, qa.rows
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        rp, nr = _p(rows, ctypes.c_int64), len(rows)
+    lib().nvfp4o_lora_up_add(_p(t, ctypes.c_uint16), _p(b, ctypes.c_uint16), qw.rows, t.shape[1], float(scale),
+                             rp, nr, _p(Y, ctypes.c_double), _p(S, ctypes.c_double))
     return Y, S
 
 

@@ -633,3 +633,34 @@ def test_rht_rounds_once_to_bf16(oracle):
                 ef = float(exact)
                 assert Fraction(ef) == exact                   # fits fp32 here: torch's cast is then the single rounding
                 assert y[16 * grp + i, c] == _bf16_of_exact(ef)
+
+
+# ----------------------------------------------------------- LoRA side branch
+
+def test_lora_branch_against_numpy(oracle):
+    """Sec. 2.2: W ~ Dequant(Q(W0)) + (alpha/r) B A.  The oracle's loops against numpy's matmul on
+    independently decoded operands; zero adapters leave the GEMM alone; the update is linear in its scale."""
+    M, N, K, r = 6, 7, 32, 16
+    xb = wl.normal((M, K), 1.0, 41, 0)
+    wb = wl.normal((N, K), 0.02, 41, 1)
+    ab = wl.normal((r, K), 0.05, 41, 2)
+    bb = wl.normal((N, r), 0.05, 41, 3)
+    x, a, b = (wl.bf16_bits_to_f32(v).astype(np.float64) for v in (xb, ab, bb))
+    t = oracle.lora_down(xb, ab)
+    assert (t == oracle.bf16_rne(x @ a.T)).all()
+    # the rounding of T is torch's bf16 cast where fp32 holds the sum exactly enough: compare values
+    tt = torch.tensor(x @ a.T).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert (np.abs(wl.bf16_bits_to_f32(t) - tt) <= np.abs(tt) * 2.0 ** -8).all()
+    qa, qw = oracle.quantize(xb), oracle.quantize(wb)
+    Y0, S0 = oracle.gemm(qa, qw)
+    tv = wl.bf16_bits_to_f32(t).astype(np.float64)
+    Y, S = oracle.gemm_lora(qa, qw, t, bb, 0.5)
+    assert np.allclose(Y, Y0 + 0.5 * (tv @ b.T), rtol=1e-13, atol=1e-300)
+    assert np.allclose(S, S0 + 0.5 * (np.abs(tv) @ np.abs(b).T), rtol=1e-13)
+    Yz, _ = oracle.gemm_lora(qa, qw, t, wl.to_bf16_bits(np.zeros((N, r), np.float32)), 0.5)
+    assert (Yz == Y0).all()
+    Y2, _ = oracle.gemm_lora(qa, qw, t, bb, 1.0)
+    assert np.allclose(Y2 - Y0, 2 * (Y - Y0), rtol=1e-12, atol=1e-300)
+    rows = np.array([4, 1], np.int64)
+    Yr, Sr = oracle.gemm_lora(qa, qw, t, bb, 0.5, rows=rows)
+    assert (Yr == Y[rows]).all() and (Sr == S[rows]).all()
