@@ -196,6 +196,26 @@ def measure_rows(nv, wl, torch, np):
     res["kv_dequant_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
                                       "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
     del kv, back, q
+    # --- LoRA side branch on the DiT projection (rank 128, alpha 128): bf16 down projection, then the
+    # quantized GEMM with the low-rank update fused in, against the plain quantized GEMM ------------
+    c2 = wl.config2()
+    Mi, Dm = wl.TOKENS_INFER, wl.D_MODEL
+    Xi = nv.bf16_from_bits(c2["A"], dev)
+    qXi, qWi = nv.nvfp4_quantize(Xi), nv.nvfp4_quantize(nv.bf16_from_bits(c2["W"], dev))
+    La = nv.bf16_from_bits(wl.normal((nv.LORA_RANK, Dm), 0.02, 1, 7), dev)
+    Lb = nv.bf16_from_bits(wl.normal((Dm, nv.LORA_RANK), 0.02, 1, 8), dev)
+    Tl = torch.empty((Mi, nv.LORA_RANK), dtype=torch.bfloat16, device=dev)
+    Yl = torch.empty((Mi, Dm), dtype=torch.bfloat16, device=dev)
+    fl = 2.0 * Mi * Dm * Dm
+    wsl = torch.empty(nv.nvfp4_workspace_bytes(nv.OP_LORA_DOWN, Mi, Dm), dtype=torch.uint8, device=dev)
+    ms = _time_op(nv, torch, nv.OP_LORA_DOWN, lambda: nv.nvfp4_lora_down(Xi, La, out=Tl, workspace=wsl), 20)
+    res["lora_down_3520x3072_r128"] = {"ms": round(ms, 4), "tflops": round(2.0 * Mi * Dm * nv.LORA_RANK / ms / 1e9, 1)}
+    ms = _time_op(nv, torch, nv.OP_GEMM_LORA, lambda: nv.nvfp4_gemm_lora(qXi, qWi, Tl, Lb, 1.0, nv.OUT_BF16, Y=Yl), 20)
+    res["gemm_lora_fused_3520x3072x3072"] = {"ms": round(ms, 4), "tflops": round((fl + 2.0 * Mi * Dm * nv.LORA_RANK) / ms / 1e9, 1)}
+    ms = _time_op(nv, torch, nv.OP_GEMM, lambda: nv.nvfp4_gemm(qXi, qWi, nv.OUT_BF16, Y=Yl), 20)
+    res["gemm_plain_3520x3072x3072"] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 1),
+                                        "frac_mfma": round(fl / ms / 1e9 / PEAK_MFMA_F16_TFLOPS, 4)}
+    del c2, Xi, qXi, qWi, La, Lb, Tl, Yl
     # --- training triplet: X[17600,3072], W[14336,3072], dY[17600,14336] ---------------------
     c5 = wl.config5()
     Mt, D, F = wl.TOKENS_TRAIN, wl.D_MODEL, wl.D_FFN

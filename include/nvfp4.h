@@ -68,7 +68,8 @@ enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2
        NVFP4_OP_GEMM_ACT_QUANT_GEMM = 5 /* timing only: the GEMM kernel inside nvfp4_gemm_act_quant */,
        NVFP4_OP_QUANTIZE_4OVER6 = 6, NVFP4_OP_KV_QUANT_4OVER6 = 7, NVFP4_OP_KV_QUANT_K = 8,
        NVFP4_OP_KV_DEQUANT_GATHER = 9, NVFP4_OP_QUANTIZE_2D = 10,
-       NVFP4_OP_QUANTIZE_RHT = 11, NVFP4_OP_QUANTIZE_A2A = 12 };
+       NVFP4_OP_QUANTIZE_RHT = 11, NVFP4_OP_QUANTIZE_A2A = 12,
+       NVFP4_OP_LORA_DOWN = 13, NVFP4_OP_GEMM_LORA = 14 };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
@@ -151,6 +152,30 @@ int nvfp4_quantize_2d(const void *w_bf16, int64_t R, int64_t C, int64_t ld,
  */
 int nvfp4_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y, int64_t ldy,
                int out_dtype, void *stream);
+
+/*
+ * LoRA side branch next to the quantized weight (Sec. 2.2 "Few-step Distillation
+ * in NVFP4": W ~ Dequant(Q(W0)) + (alpha_LoRA / r) B A with bf16 adapters of rank
+ * r = 128; Sec. 3.1: run as a separate branch or with fused low-rank kernels).
+ *
+ * nvfp4_lora_down: T = RN_bf16(X A^T), fp32 accumulation.  x_bf16 [M, K] bf16 (row
+ *   stride ldx, the UNQUANTIZED activations), a_bf16 [NVFP4_LORA_RANK, K] bf16,
+ *   t_bf16 [M, NVFP4_LORA_RANK] bf16 out.  K % 16 == 0, ldx % 8 == 0.  The K
+ *   range is cut across workgroups; workspace (16-byte aligned,
+ *   nvfp4_workspace_bytes(NVFP4_OP_LORA_DOWN, M, K, 0) bytes) holds their fp32
+ *   partial sums, which are added in a fixed order: results are deterministic.
+ * nvfp4_gemm_lora: Y = nvfp4_gemm(A, W) + lora_scale * T B^T in one kernel: the
+ *   low-rank product (b_bf16 [N, NVFP4_LORA_RANK] bf16) is accumulated on the
+ *   matrix cores into the accumulators of the FP4 product, in fp32.  Y, ldy,
+ *   out_dtype as nvfp4_gemm; lora_scale = alpha_LoRA / r.  Needs K % 64 == 0
+ *   and N % 8 == 0 (NVFP4_ERR_SHAPE otherwise).
+ */
+#define NVFP4_LORA_RANK 128
+int nvfp4_lora_down(const void *x_bf16, int64_t M, int64_t K, int64_t ldx, const void *a_bf16,
+                    void *t_bf16, void *workspace, size_t workspace_bytes, void *stream);
+int nvfp4_gemm_lora(const nvfp4_tensor *A, const nvfp4_tensor *W, const void *t_bf16,
+                    const void *b_bf16, float lora_scale, void *Y, int64_t ldy, int out_dtype,
+                    void *stream);
 
 /*
  * GEMM with fused activation and re-quantization of the result along N

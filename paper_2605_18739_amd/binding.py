@@ -19,7 +19,8 @@ ACT_NONE, ACT_GELU_TANH = 0, 1
 OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT, OP_GEMM_ACT_QUANT_GEMM = 0, 1, 2, 3, 4, 5
 OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6, OP_KV_QUANT_K, OP_KV_DEQUANT_GATHER = 6, 7, 8, 9
 KV_MAX_CHUNKS = 64
-OP_QUANTIZE_2D, OP_QUANTIZE_RHT, OP_QUANTIZE_A2A = 10, 11, 12
+OP_QUANTIZE_2D, OP_QUANTIZE_RHT, OP_QUANTIZE_A2A, OP_LORA_DOWN, OP_GEMM_LORA = 10, 11, 12, 13, 14
+LORA_RANK = 128
 
 
 class _CTensor(ctypes.Structure):
@@ -50,6 +51,10 @@ def lib():
         L.nvfp4_quantize.argtypes = [vp, i64, i64, i64, c.c_int, vp, tp, vp, sz, vp]
         L.nvfp4_gemm.restype = c.c_int
         L.nvfp4_gemm.argtypes = [tp, tp, vp, i64, c.c_int, vp]
+        L.nvfp4_lora_down.restype = c.c_int
+        L.nvfp4_lora_down.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
+        L.nvfp4_gemm_lora.restype = c.c_int
+        L.nvfp4_gemm_lora.argtypes = [tp, tp, vp, vp, c.c_float, vp, i64, c.c_int, vp]
         L.nvfp4_gemm_act_quant.restype = c.c_int
         L.nvfp4_gemm_act_quant.argtypes = [tp, tp, c.c_int, vp, tp, vp, vp, sz, vp]
         L.nvfp4_kv_quant.restype = c.c_int
@@ -150,6 +155,33 @@ def nvfp4_gemm(A, W, out_dtype=OUT_F32, Y=None, stream=None):
     ca, cw = A.c(), W.c()
     _check(lib().nvfp4_gemm(ctypes.byref(ca), ctypes.byref(cw), _ptr(Y), Y.stride(0), out_dtype,
                             _stream(stream)))
+    return Y
+
+
+def nvfp4_lora_down(x, a, out=None, workspace=None, stream=None):
+    """T = bf16(x a^T): x bf16 [M, K] (unit stride along K), a bf16 [128, K] contiguous."""
+    assert x.dtype == torch.bfloat16 and a.dtype == torch.bfloat16 and x.stride(1) == 1 and a.is_contiguous()
+    M, K = x.shape
+    assert a.shape == (LORA_RANK, K)
+    if out is None:
+        out = torch.empty((M, LORA_RANK), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_LORA_DOWN, M, K), x.device)
+    _check(lib().nvfp4_lora_down(_ptr(x), M, K, x.stride(0), _ptr(a), _ptr(out), _ptr(workspace), workspace.numel(),
+                                 _stream(stream)))
+    return out
+
+
+def nvfp4_gemm_lora(A, W, t, b, lora_scale, out_dtype=OUT_F32, Y=None, stream=None):
+    """nvfp4_gemm(A, W) + lora_scale * t b^T, fused; t bf16 [M, 128], b bf16 [N, 128], both contiguous."""
+    M, N = A.rows, W.rows
+    assert t.is_contiguous() and b.is_contiguous() and t.shape == (M, LORA_RANK) and b.shape == (N, LORA_RANK)
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.float32 if out_dtype == OUT_F32 else torch.bfloat16,
+                        device=A.codes.device)
+    ca, cw = A.c(), W.c()
+    _check(lib().nvfp4_gemm_lora(ctypes.byref(ca), ctypes.byref(cw), _ptr(t), _ptr(b), float(lora_scale), _ptr(Y),
+                                 Y.stride(0), out_dtype, _stream(stream)))
     return Y
 
 

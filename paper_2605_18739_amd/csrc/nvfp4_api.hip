@@ -299,6 +299,48 @@ int nvfp4_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y, int64_t ld
     return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
 }
 
+int nvfp4_lora_down(const void *x_bf16, int64_t M, int64_t K, int64_t ldx, const void *a_bf16,
+                    void *t_bf16, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!x_bf16 || !a_bf16 || !t_bf16) return NVFP4_ERR_NULL;
+    if (M <= 0 || K <= 0 || (K & 15) != 0 || ldx < K) return NVFP4_ERR_SHAPE;
+    if (!aligned16(x_bf16) || !aligned16(a_bf16) || !aligned16(t_bf16) || (ldx & 7) != 0) return NVFP4_ERR_ALIGN;
+    if (!workspace || workspace_bytes < lora_down_workspace_bytes(M, K)) return NVFP4_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timed t(s, NVFP4_OP_LORA_DOWN);
+    hipError_t e = launch_lora_down(static_cast<const uint16_t *>(x_bf16), M, K, ldx,
+                                    static_cast<const uint16_t *>(a_bf16), static_cast<uint16_t *>(t_bf16),
+                                    static_cast<float *>(workspace), s);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
+int nvfp4_gemm_lora(const nvfp4_tensor *A, const nvfp4_tensor *W, const void *t_bf16, const void *b_bf16,
+                    float lora_scale, void *Y, int64_t ldy, int out_dtype, void *stream)
+{
+    if (!Y || !t_bf16 || !b_bf16) return NVFP4_ERR_NULL;
+    if (int rc = check_gemm(A, W)) return rc;
+    if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16) return NVFP4_ERR_SHAPE;
+    if (ldy < W->rows) return NVFP4_ERR_SHAPE;
+    if (!gemm_is_tiled(A->rows, W->rows, A->K)) return NVFP4_ERR_SHAPE;   // K % 64 == 0 and N % 8 == 0 for the fused branch
+    if (!aligned16(Y) || (ldy & 3) != 0 || !aligned16(t_bf16) || !aligned16(b_bf16)) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_GEMM_LORA);
+    GemmEpilogue ep{};
+    ep.out_dtype = out_dtype;
+    ep.act = NVFP4_ACT_NONE;
+    ep.Y = Y;
+    ep.ldy = ldy;
+    LoraBranch lora;
+    lora.t = static_cast<const uint16_t *>(t_bf16);
+    lora.b = static_cast<const uint16_t *>(b_bf16);
+    lora.scale = lora_scale;
+    hipError_t e = launch_gemm(A->codes, A->scales, A->global_scale, W->codes, W->scales, W->global_scale,
+                               A->rows, W->rows, A->K, ep, nullptr, static_cast<hipStream_t>(stream), lora);
+    return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
 int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
                          const float *global_scale_in, nvfp4_tensor *out, void *h_bf16_opt,
                          void *workspace, size_t workspace_bytes, void *stream)
@@ -373,6 +415,9 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
     case NVFP4_OP_QUANTIZE_RHT:
     case NVFP4_OP_QUANTIZE_A2A:
         return kPartialBytes;
+    case NVFP4_OP_LORA_DOWN:          // a = M, b = K
+        if (a <= 0 || b <= 0) return 0;
+        return lora_down_workspace_bytes(a, b);
     case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c: bit 0 = caller supplies H, bit 1 = caller supplies the scale
         if (a <= 0 || b <= 0) return 0;
         // the GEMM tile (hence the number of per-workgroup maxima) depends on K, which this query

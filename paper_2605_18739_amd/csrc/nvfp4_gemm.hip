@@ -44,7 +44,9 @@ constexpr int ROW_BYTES = BK * 2;      // one staged f16 row
 // Epilogue variants (kernel template parameter): the kind of output, plus kEpiGelu when the
 // tanh-form GELU is applied (a compile-time choice: as a run-time one the compiler evaluates
 // the activation for every output and selects afterwards).
-enum { kEpiF32 = 0, kEpiBF16 = 1, kEpiQuant = 2, kEpiGelu = 4 };   // fp32 out, bf16 out, bf16 + fused re-quantization
+// kEpiLora: before the quantized operands are multiplied, the accumulators receive the low-rank
+// update of a LoRA adapter (a kernel variant of its own, so that the plain kernels stay as they are).
+enum { kEpiF32 = 0, kEpiBF16 = 1, kEpiQuant = 2, kEpiGelu = 4, kEpiLora = 8 };   // fp32 out, bf16 out, bf16 + fused re-quantization
 
 struct GemmArgs {
     const uint8_t *codesA, *scalesA;
@@ -55,6 +57,9 @@ struct GemmArgs {
     int n_tiles_n;             // tiles along N: workgroup t works on tile (t / n_tiles_n, t % n_tiles_n)
     int64_t q_pitch;           // row pitch in ELEMENTS of the fused quantizer's output (N of the whole problem)
     int partial_base;          // first slot of this launch in ep.amax_partial
+    // LoRA side branch (kEpiLora kernels): Y += lora_scale * T B^T, T [M, 128], B [N, 128] bf16
+    const uint16_t *lora_t, *lora_b;
+    float lora_scale;
 };
 
 // tanh-form GELU in fp32: 0.5 y (1 + tanh(u)), u = sqrt(2/pi) (y + 0.044715 y^3), with
@@ -584,6 +589,63 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+    if constexpr ((EPI & kEpiLora) != 0) {
+        // ---- LoRA phase (Sec. 2.2 / 3.1: low-rank adapter beside the quantized weight).  The
+        // tile's 256 + BN rows of T and B (128 bf16 = 256 B each) are copied into LDS, multiplied
+        // with v_mfma_f32_32x32x16_bf16 in eight 16-wide sub-steps, and the accumulators are
+        // rescaled by lora_scale / (gsA gsW) so that the quantized product can be added on top
+        // and the epilogue's single multiplication by gsA gsW leaves lora_scale * T B^T.
+        // LDS: row r at 256 r, its sixteen 16-byte chunks XOR-swizzled with r & 15 (sixteen rows
+        // of one chunk, what a fragment read touches per LDS cycle, fall on distinct banks).
+        typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
+        const __amdgpu_buffer_rsrc_t rT = __builtin_amdgcn_make_buffer_rsrc((void *)g.lora_t, 0, (int)(g.M * 256), 0x00020000);
+        const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc((void *)g.lora_b, 0, (int)(g.N * 256), 0x00020000);
+        constexpr int LUNITS = ROWS / 4;               // 1 KB copies: four rows each
+#pragma unroll
+        for (int x = 0; x < LUNITS / 4; ++x) {
+            const int u = wave + 4 * x;
+            const int srow = 4 * u + (lane >> 4);
+            const int chunk = (lane & 15) ^ (srow & 15);
+            uint8_t *dst = lds + u * 1024;
+            if (4 * u < BM) {
+                const int64_t gr = m0 + srow;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rT, (lds_ptr_t)dst, 16, gr < g.M ? (int)(gr * 256) + chunk * 16 : 0x7FF00000, 0, 0, 0);
+            } else {
+                const int64_t gr = n0 + (srow - BM);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rB, (lds_ptr_t)dst, 16, gr < g.N ? (int)(gr * 256) + chunk * 16 : 0x7FF00000, 0, 0, 0);
+            }
+        }
+        wait_vmcnt_le<0>();
+        NVFP4_COMPILER_FENCE();
+        __builtin_amdgcn_s_barrier();
+        NVFP4_COMPILER_FENCE();
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            uint4v lf[NF];
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                const int row = frag_row0(f) + lrow;
+                lf[f] = *(const uint4v *)(lds + row * 256 + (((2 * kk + lhalf) ^ (row & 15)) << 4));
+            }
+#pragma unroll
+            for (int t = 0; t < NMF; ++t) {
+                const int i = t / TM, jj = t % TM;
+                acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8v, lf[TM + i]),
+                                                                      __builtin_bit_cast(bf16x8v, lf[jj]), acc[i][jj], 0, 0, 0);
+            }
+        }
+        const float rescale = g.lora_scale / ((*g.gsA) * (*g.gsW));
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] *= rescale;
+        NVFP4_COMPILER_FENCE();
+        __builtin_amdgcn_s_barrier();                   // every wave has read its rows: the stages may be filled
+        NVFP4_COMPILER_FENCE();
+    }
+
     // fragments of MFMA sub-step j live in frag[j & 1]; order: A tiles then W tiles
     uint4v frag[2][NF];
     // piece pc (0 .. 2 NF - 1) of sub-step j of register set `set`: half a fragment
@@ -699,6 +761,116 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
 #endif
 }
 
+// ============================================================================
+// Down projection of the LoRA side branch: T [M, 128] = bf16(X A^T), X [M, K] and A [128, K]
+// bf16, fp32 accumulation on v_mfma_f32_32x32x16_bf16.  A skinny GEMM: with whole-K tiles
+// either few workgroups run or every one of them pulls all of A through its compute unit, and
+// a compute unit pulls only ~30-60 GB/s at the latency of one step in flight.  So K is cut:
+// workgroup (i, s) multiplies rows 128 i .. 128 i + 127 with K range s of `splits` (64-k steps
+// staged in LDS with full-line coalesced loads, one step ahead; 2 x 2 waves of 64 x 64), writes
+// an fp32 partial tile to the workspace, and a second small kernel adds the partial tiles in
+// split order and rounds to bf16.
+// ============================================================================
+constexpr int kLdRows = 128;                                      // rows of X per workgroup
+__global__ __launch_bounds__(256) void lora_down_partial_kernel(const uint16_t *__restrict__ x, int64_t M,
+                                                                int64_t K, int64_t ldx,
+                                                                const uint16_t *__restrict__ a, int steps_per_split,
+                                                                float *__restrict__ partial, int64_t m_pad)
+{
+    typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
+    constexpr int ROWS = kLdRows + kLoraRank;                     // staged rows: X rows first, then A rows
+    constexpr int STAGE = ROWS * ROW_BYTES;                       // 32 KB
+    constexpr int CHUNKS = ROWS * 8 / 256;                        // 16-byte chunks per thread and step
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int64_t m0 = (int64_t)blockIdx.x * kLdRows;
+    const int step0 = blockIdx.y * steps_per_split;
+    const int ksteps_all = (int)((K + 63) >> 6);                  // the last step may be partly past K (K % 16 == 0)
+    const int nsteps = min(steps_per_split, ksteps_all - step0);
+    // this thread's chunks: q = tid + 256 i -> staged row q / 8, chunk q % 8
+    const uint16_t *src[CHUNKS];
+    int dst[CHUNKS], kc[CHUNKS];
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+        const int q = tid + 256 * i, row = q >> 3, c = q & 7;
+        src[i] = row < kLdRows ? x + min(m0 + row, M - 1) * ldx + 8 * c     // rows past the end repeat the last one (never used)
+                               : a + (int64_t)(row - kLdRows) * K + 8 * c;
+        dst[i] = lds_chunk_off(row, c);
+        kc[i] = 8 * c;
+    }
+    uint4v regs[CHUNKS];
+    auto fetch = [&](int step) {
+#pragma unroll
+        for (int i = 0; i < CHUNKS; ++i) {
+            const int64_t k = (int64_t)step * 64 + kc[i];
+            regs[i] = k < K ? *(const uint4v *)(src[i] + (int64_t)step * 64) : uint4v{0u, 0u, 0u, 0u};
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CHUNKS; ++i) *(uint4v *)(lds + buf * STAGE + dst[i]) = regs[i];
+    };
+    float16v acc[2][2];                                           // [column tile][row tile] of this wave's 64 x 64
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[c][j][r] = 0.0f;
+    if (nsteps > 0) {
+        fetch(step0);
+        stage(0);
+    }
+    __syncthreads();
+    for (int st = 0; st < nsteps; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < nsteps) fetch(step0 + st + 1);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            uint4v fx[2], fa[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                fx[j] = *(const uint4v *)(lds + buf * STAGE + lds_chunk_off(64 * wm + 32 * j + lrow, 2 * kk + lhalf));
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                fa[c] = *(const uint4v *)(lds + buf * STAGE + lds_chunk_off(kLdRows + 64 * wn + 32 * c + lrow, 2 * kk + lhalf));
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[c][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8v, fa[c]),
+                                                                        __builtin_bit_cast(bf16x8v, fx[j]), acc[c][j], 0, 0, 0);
+        }
+        if (st + 1 < nsteps) stage(buf ^ 1);         // the other stage was last read before the previous barrier
+        __syncthreads();
+    }
+    // lane = output row, register r = column 8 (r / 4) + 4 lhalf + r % 4 of the 32-column tile
+    float *pp = partial + ((int64_t)blockIdx.y * m_pad + m0) * kLoraRank;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int row = 64 * wm + 32 * j + lrow;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(float4v *)(pp + (int64_t)row * kLoraRank + 64 * wn + 32 * c + 8 * q + 4 * lhalf) =
+                    float4v{acc[c][j][4 * q], acc[c][j][4 * q + 1], acc[c][j][4 * q + 2], acc[c][j][4 * q + 3]};
+    }
+}
+
+// T = bf16(sum over the splits, in split order)
+__global__ __launch_bounds__(256) void lora_down_reduce_kernel(const float *__restrict__ partial, int splits,
+                                                               int64_t m_pad, int64_t M, uint16_t *__restrict__ t)
+{
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;           // four consecutive columns of one row
+    if (i >= M * kLoraRank) return;
+    float4v sum = *(const float4v *)(partial + i);
+    for (int s = 1; s < splits; ++s) sum += *(const float4v *)(partial + (int64_t)s * m_pad * kLoraRank + i);
+    *(uint2v *)(t + i) = uint2v{pack_bf16x2(sum.x, sum.y), pack_bf16x2(sum.z, sum.w)};
+}
+
 // Any K % 16 == 0, any M, N: one output per thread, plain loop.  Only used for
 // shapes the tiled kernel does not take (K not a multiple of 64, N not a
 // multiple of 8); not a performance path.
@@ -779,7 +951,8 @@ static double tile_cost(int64_t M, int64_t N, int64_t K, const TileShape &t)
     return waves * ((double)(K / BK) * t.step_cost + 8.0) + 4.0;
 }
 
-static TileKind choose_tile(int64_t M, int64_t N, int64_t K, double *cost = nullptr)
+// big_only: only the 256-row tile shapes (the kernels that can carry the LoRA phase)
+static TileKind choose_tile(int64_t M, int64_t N, int64_t K, double *cost = nullptr, bool big_only = false)
 {
     int best = 0;
     double c[3];
@@ -787,6 +960,7 @@ static TileKind choose_tile(int64_t M, int64_t N, int64_t K, double *cost = null
         c[i] = tile_cost(M, N, K, kShapes[i]);
         // prefer the larger tile on ties (order: 256x256, 256x192, 128x128)
     }
+    if (big_only) c[0] = 1e300;
     best = (c[1] <= c[0] && c[1] <= c[2]) ? 1 : (c[2] <= c[0] ? 2 : 0);
     if (cost) *cost = c[best];
     return (TileKind)best;
@@ -800,11 +974,11 @@ static TileKind choose_tile(int64_t M, int64_t N, int64_t K, double *cost = null
 struct SubLaunch { int64_t m_lo, m_hi, n_lo, n_hi; TileKind kind; int64_t tiles; };   // tiles: how many of its grid to run (prefix)
 struct LaunchPlan { int n; SubLaunch part[3]; };
 
-static LaunchPlan plan_gemm(int64_t M, int64_t N, int64_t K)
+static LaunchPlan plan_gemm(int64_t M, int64_t N, int64_t K, bool big_only = false)
 {
     LaunchPlan p{};
     double whole;
-    const TileKind kind = choose_tile(M, N, K, &whole);
+    const TileKind kind = choose_tile(M, N, K, &whole, big_only);
     const TileShape &t = kShapes[kind];
     const int64_t tm = (M + t.bm - 1) / t.bm, tn = (N + t.bn - 1) / t.bn, tiles = tm * tn;
     p.n = 1;
@@ -824,7 +998,7 @@ static LaunchPlan plan_gemm(int64_t M, int64_t N, int64_t K)
     if (full_from < tm) extra[ne++] = {full_from * t.bm, M, 0, N, kTile128, 0};
     for (int i = 0; i < ne; ++i) {
         double ci;
-        extra[i].kind = choose_tile(extra[i].m_hi - extra[i].m_lo, extra[i].n_hi - extra[i].n_lo, K, &ci);
+        extra[i].kind = choose_tile(extra[i].m_hi - extra[i].m_lo, extra[i].n_hi - extra[i].n_lo, K, &ci, big_only);
         const TileShape &ts = kShapes[extra[i].kind];
         extra[i].tiles = ((extra[i].m_hi - extra[i].m_lo + ts.bm - 1) / ts.bm) * ((extra[i].n_hi - extra[i].n_lo + ts.bn - 1) / ts.bn);
         split += ci;
@@ -858,22 +1032,27 @@ static hipError_t launch_kind(TileKind kind, const GemmArgs &g, int64_t tiles, h
     switch (kind) {
     case kTile256x256: return launch_regdq<256, 256, EPI>(g, tiles, s);
     case kTile256x192: return launch_regdq<256, 192, EPI>(g, tiles, s);
-    default: return launch_tiled<128, 128, EPI>(g, tiles, s);
+    default:
+        if constexpr ((EPI & kEpiLora) != 0) return hipErrorInvalidValue;   // planned with the 256-row tiles only
+        else return launch_tiled<128, 128, EPI>(g, tiles, s);
     }
 }
 
 hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const float *gsA,
                        const uint8_t *codesW, const uint8_t *scalesW, const float *gsW, int64_t M,
-                       int64_t N, int64_t K, const GemmEpilogue &ep, int *n_wg, hipStream_t s)
+                       int64_t N, int64_t K, const GemmEpilogue &ep, int *n_wg, hipStream_t s,
+                       const LoraBranch &lora)
 {
-    GemmArgs g{codesA, scalesA, codesW, scalesW, gsA, gsW, M, N, K, ep, 0, N, 0};
+    GemmArgs g{codesA, scalesA, codesW, scalesW, gsA, gsW, M, N, K, ep, 0, N, 0, lora.t, lora.b, lora.scale};
+    const bool with_lora = lora.t != nullptr;
     if (!tiled_ok(M, N, K)) {
+        if (with_lora) return hipErrorInvalidValue;      // the untiled fallback has no LoRA phase (callers check gemm_is_tiled)
         if (n_wg) *n_wg = 0;
         int64_t total = M * N;
         gemm_generic_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(g);
         return hipGetLastError();
     }
-    const LaunchPlan plan = plan_gemm(M, N, K);
+    const LaunchPlan plan = plan_gemm(M, N, K, with_lora);
     // (the tiled fp32 output never carries an activation: nvfp4_gemm has none and the fused call emits bf16)
     const int out_kind = ep.q_scale ? kEpiQuant : (ep.out_dtype != 0 ? kEpiBF16 : kEpiF32);
     const int epi = out_kind | ((ep.act == 1 && out_kind != kEpiF32) ? kEpiGelu : 0);
@@ -896,8 +1075,14 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
         }
         a.q_pitch = N;
         a.partial_base = wg_total;
+        if (with_lora) {
+            a.lora_t = lora.t + p.m_lo * kLoraRank;
+            a.lora_b = lora.b + p.n_lo * kLoraRank;
+        }
         hipError_t e;
-        switch (epi) {
+        switch (epi | (with_lora ? kEpiLora : 0)) {
+        case kEpiF32 | kEpiLora: e = launch_kind<kEpiF32 | kEpiLora>(p.kind, a, p.tiles, s); break;
+        case kEpiBF16 | kEpiLora: e = launch_kind<kEpiBF16 | kEpiLora>(p.kind, a, p.tiles, s); break;
         case kEpiF32: e = launch_kind<kEpiF32>(p.kind, a, p.tiles, s); break;
         case kEpiBF16: e = launch_kind<kEpiBF16>(p.kind, a, p.tiles, s); break;
         case kEpiBF16 | kEpiGelu: e = launch_kind<kEpiBF16 | kEpiGelu>(p.kind, a, p.tiles, s); break;
@@ -909,6 +1094,39 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
     }
     if (n_wg) *n_wg = wg_total;
     return hipSuccess;
+}
+
+// K is cut into `splits` ranges of whole 64-k steps so that about one workgroup per compute unit runs
+static void lora_down_plan(int64_t M, int64_t K, int *splits, int *steps_per_split, int64_t *m_pad)
+{
+    const int64_t row_tiles = (M + kLdRows - 1) / kLdRows;
+    const int ksteps = (int)((K + 63) >> 6);
+    int want = (int)std::max<int64_t>(1, std::min<int64_t>(16, kCUs / row_tiles));
+    *steps_per_split = (ksteps + want - 1) / want;
+    *splits = (ksteps + *steps_per_split - 1) / *steps_per_split;
+    *m_pad = row_tiles * kLdRows;
+}
+
+size_t lora_down_workspace_bytes(int64_t M, int64_t K)
+{
+    int splits, sps;
+    int64_t m_pad;
+    lora_down_plan(M, K, &splits, &sps, &m_pad);
+    return (size_t)splits * (size_t)m_pad * kLoraRank * sizeof(float);
+}
+
+hipError_t launch_lora_down(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const uint16_t *a,
+                            uint16_t *t, float *workspace, hipStream_t s)
+{
+    int splits, sps;
+    int64_t m_pad;
+    lora_down_plan(M, K, &splits, &sps, &m_pad);
+    dim3 grid((unsigned)(m_pad / kLdRows), (unsigned)splits);
+    lora_down_partial_kernel<<<grid, 256, 2 * (kLdRows + kLoraRank) * ROW_BYTES, s>>>(x, M, K, ldx, a, sps, workspace, m_pad);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    lora_down_reduce_kernel<<<(unsigned)((M * kLoraRank / 4 + 255) / 256), 256, 0, s>>>(workspace, splits, m_pad, M, t);
+    return hipGetLastError();
 }
 
 }  // namespace nvfp4

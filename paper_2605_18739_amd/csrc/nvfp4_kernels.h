@@ -67,9 +67,20 @@ struct GemmEpilogue {
     uint8_t *q_scales;        // [M, N/16]
 };
 
+// LoRA side branch fused into the GEMM: Y += scale * T B^T with T [M, kLoraRank], B [N, kLoraRank] bf16
+// (t == nullptr: none).  Only for shapes the tiled kernels take, plain fp32 / bf16 output.
+constexpr int kLoraRank = 128;
+struct LoraBranch { const uint16_t *t = nullptr, *b = nullptr; float scale = 0.0f; };
+
 hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const float *gsA,
                        const uint8_t *codesW, const uint8_t *scalesW, const float *gsW, int64_t M,
-                       int64_t N, int64_t K, const GemmEpilogue &ep, int *n_wg, hipStream_t s);
+                       int64_t N, int64_t K, const GemmEpilogue &ep, int *n_wg, hipStream_t s,
+                       const LoraBranch &lora = LoraBranch());
+// T = bf16(X A^T): X [M, K] bf16 (row stride ldx), A [kLoraRank, K] bf16, K % 16 == 0; the workspace
+// (lora_down_workspace_bytes, 16-byte aligned) holds the fp32 partial tiles of the K ranges
+size_t lora_down_workspace_bytes(int64_t M, int64_t K);
+hipError_t launch_lora_down(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const uint16_t *a,
+                            uint16_t *t, float *workspace, hipStream_t s);
 int gemm_workgroups(int64_t M, int64_t N, int64_t K);
 bool gemm_is_tiled(int64_t M, int64_t N, int64_t K);   // false: the untiled fallback kernel (no fused epilogues)
 

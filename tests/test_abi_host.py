@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
             "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string",
             "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6", "nvfp4_kv_quant_k",
             "nvfp4_kv_dequant_gather", "nvfp4_quantize_2d", "nvfp4_quantize_rht",
-            "nvfp4_quantize_for_all_to_all"} <= set(names)
+            "nvfp4_quantize_for_all_to_all", "nvfp4_lora_down", "nvfp4_gemm_lora"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -82,6 +82,19 @@ def test_gemm_and_kv_reject_bad_arguments_on_the_host():
     assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 4, 0, None) == -2                  # ldy < N
     assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 8, 7, None) == -2                  # bad dtype
     assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 10, 0, None) == -3                 # ldy % 4
+    # LoRA branch: rank-128 operands are required; the fused call only takes tiled shapes
+    tb = ctypes.c_void_p(0x80000)
+    lw = ctypes.c_void_p(0x90000)
+    assert nv.nvfp4_workspace_bytes(nv.OP_LORA_DOWN, 3520, 3072) == 8 * 3584 * 128 * 4          # 28 row tiles x 8 K ranges
+    assert L.nvfp4_lora_down(None, 4, 32, 32, tb, tb, lw, 1 << 20, None) == -1
+    assert L.nvfp4_lora_down(y, 4, 24, 24, tb, tb, lw, 1 << 20, None) == -2                      # K % 16
+    assert L.nvfp4_lora_down(y, 4, 32, 36, tb, tb, lw, 1 << 20, None) == -3                      # ldx % 8
+    assert L.nvfp4_lora_down(y, 4, 32, 32, tb, tb, lw, 100, None) == -4
+    assert L.nvfp4_gemm_lora(ctypes.byref(a), ctypes.byref(w), None, tb, 1.0, y, 8, 0, None) == -1
+    assert L.nvfp4_gemm_lora(ctypes.byref(a), ctypes.byref(w), tb, tb, 1.0, y, 8, 0, None) == -2  # K = 32 is not a multiple of 64
+    a64, w64 = _t(rows=4, K=64), _t(rows=8, K=64)
+    assert L.nvfp4_gemm_lora(ctypes.byref(a64), ctypes.byref(w64), tb, tb, 1.0, y, 4, 0, None) == -2   # ldy < N
+    assert L.nvfp4_gemm_lora(ctypes.byref(a64), ctypes.byref(w64), tb, tb, 1.0, y, 8, 3, None) == -2   # bad dtype
     out = _t(rows=4, K=16)
     ws = ctypes.c_void_p(0x50000)
     assert L.nvfp4_gemm_act_quant(ctypes.byref(a), ctypes.byref(w), 1, None, ctypes.byref(out), None, ws, 1 << 20, None) == -2

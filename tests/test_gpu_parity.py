@@ -294,6 +294,56 @@ def test_kv_quant_four_over_six(oracle):
     assert e46 <= e6
 
 
+# ----------------------------------------------------------- LoRA side branch
+
+def _lora_case(oracle, M, N, K, scale, what, rows=None):
+    say(f"[lora] {what} {M}x{N}x{K}")
+    r = nv.LORA_RANK
+    xb = wl.activation_with_outliers(M, K, 28, 0)
+    wb = wl.normal((N, K), 0.02, 28, 1)
+    ab = wl.normal((r, K), 0.02, 28, 2)
+    bb = wl.normal((N, r), 0.05, 28, 3)
+    # down projection on the unquantized activations: bf16 result, equal to the fp64 chain's
+    # rounding almost everywhere and never more than one bf16 ulp (plus fp32 accumulation) away
+    t = nv.nvfp4_lora_down(dev_bf16(xb), dev_bf16(ab))
+    torch.cuda.synchronize()
+    tb = nv.bits_from_bf16(t)
+    want_t = oracle.lora_down(xb, ab)
+    tv, wv = wl.bf16_bits_to_f32(tb).astype(np.float64), wl.bf16_bits_to_f32(want_t).astype(np.float64)
+    bound = (np.abs(wl.bf16_bits_to_f32(xb)).astype(np.float64) @ np.abs(wl.bf16_bits_to_f32(ab)).astype(np.float64).T)
+    assert (np.abs(tv - wv) <= 2.0 ** -7 * np.abs(wv) + 2.0 ** -15 * bound).all()
+    assert (tb != want_t).mean() < 0.02
+    # fused GEMM: quantized product + scale * T B^T, against the oracle fed the T the GPU produced
+    oa, ow = oracle.quantize(xb), oracle.quantize(wb)
+    ga, gw = nv.nvfp4_quantize(dev_bf16(xb)), nv.nvfp4_quantize(dev_bf16(wb))
+    Y, S = oracle.gemm_lora(oa, ow, tb, bb, scale, rows=rows)
+    y32 = nv.nvfp4_gemm_lora(ga, gw, t, dev_bf16(bb), scale, nv.OUT_F32)
+    torch.cuda.synchronize()
+    got = y32.cpu().numpy()
+    fro, worst = assert_gemm_close(got if rows is None else got[rows], Y, S, what)
+    say(f"        rel fro {fro:.2e}  worst err/S {worst:.2e}")
+    y16 = nv.nvfp4_gemm_lora(ga, gw, t, dev_bf16(bb), scale, nv.OUT_BF16)
+    assert (nv.bits_from_bf16(y16) == nv.bits_from_bf16(y32.to(torch.bfloat16))).all()
+    # the branch really contributes, and a zero adapter gives the plain GEMM bit for bit
+    plain = nv.nvfp4_gemm(ga, gw, nv.OUT_F32)
+    assert not torch.equal(plain, y32)
+    zero = nv.nvfp4_gemm_lora(ga, gw, t, torch.zeros_like(dev_bf16(bb)), scale, nv.OUT_F32)
+    assert torch.equal(zero, plain)
+
+
+def test_gemm_lora_small_and_ragged(oracle):
+    _lora_case(oracle, 100, 136, 192, 1.0, "one ragged tile")
+    _lora_case(oracle, 300, 520, 64, 0.5, "several tiles, one k step")
+    _lora_case(oracle, 520, 400, 320, 2.0, "256x192 tiles")
+
+
+def test_gemm_lora_projection_shape(oracle):
+    """The DiT projection with its adapter (rank 128, alpha 128): sampled rows against the oracle."""
+    M = wl.TOKENS_INFER
+    rows = _sample_rows(M, 16, 5)
+    _lora_case(oracle, M, wl.D_MODEL, wl.D_MODEL, 1.0, "projection 3520x3072x3072", rows=rows)
+
+
 # ------------------------------------------------------- all-to-all send buffers
 
 @pytest.mark.parametrize("T,H,d,P", [(5, 4, 16, 1), (33, 24, 128, 4), (220, 24, 128, 8), (7, 6, 64, 3)])
