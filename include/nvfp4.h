@@ -280,8 +280,12 @@ const char *nvfp4_status_string(int status);
  * (enabling also discards earlier records; at most 8192 calls are recorded).
  * nvfp4_timing_read() waits for the recorded events of entry point `op`
  * (NVFP4_OP_*) and returns how many calls were recorded and the sum of their
- * durations in milliseconds.  Host pointers. */
+ * durations in milliseconds.  Host pointers.  An event pair costs a few
+ * microseconds of idle stream per call; nvfp4_set_timing_ops() restricts the
+ * recording to the entry points whose bit (1u << NVFP4_OP_*) is set in op_mask
+ * (nvfp4_set_timing(1) = all, 0 = none). */
 void nvfp4_set_timing(int enabled);
+void nvfp4_set_timing_ops(uint32_t op_mask);
 int  nvfp4_timing_read(int op, int *calls, float *total_ms);
 
 #ifdef __cplusplus

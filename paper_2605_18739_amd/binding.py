@@ -81,6 +81,8 @@ def lib():
         L.nvfp4_status_string.argtypes = [c.c_int]
         L.nvfp4_set_timing.restype = None
         L.nvfp4_set_timing.argtypes = [c.c_int]
+        L.nvfp4_set_timing_ops.restype = None
+        L.nvfp4_set_timing_ops.argtypes = [c.c_uint32]
         L.nvfp4_timing_read.restype = c.c_int
         L.nvfp4_timing_read.argtypes = [c.c_int, c.POINTER(c.c_int), c.POINTER(c.c_float)]
         _lib = L
@@ -331,6 +333,14 @@ def nvfp4_kv_dequant(q, T, H, d, out=None, stream=None):
 
 def nvfp4_set_timing(enabled):
     lib().nvfp4_set_timing(1 if enabled else 0)
+
+
+def nvfp4_set_timing_ops(ops):
+    """Record events only around the entry points listed in `ops` (OP_* ids); an empty list: none."""
+    mask = 0
+    for op in ops:
+        mask |= 1 << op
+    lib().nvfp4_set_timing_ops(mask)
 
 
 def nvfp4_timing_read(op):

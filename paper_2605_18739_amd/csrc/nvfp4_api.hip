@@ -27,7 +27,7 @@ int check_tensor(const nvfp4_tensor *t)
 // kernels on the caller's stream, tagged with its NVFP4_OP_* id.  Nothing is
 // synchronised until nvfp4_timing_read() is called.
 std::mutex g_mu;
-bool g_timing = false;
+uint32_t g_timing = 0;          // bit i: entry point i records events
 constexpr int kMaxRecords = 8192;
 struct Record { hipEvent_t e0, e1; int op; };
 std::vector<Record> g_pool;     // events are created once and reused
@@ -38,7 +38,7 @@ struct Timed {
     int slot;
     Timed(hipStream_t st, int op) : s(st), slot(-1)
     {
-        if (!g_timing || g_used >= kMaxRecords) return;
+        if (((g_timing >> op) & 1u) == 0 || g_used >= kMaxRecords) return;
         if (g_used == (int)g_pool.size()) {
             Record r{nullptr, nullptr, op};
             if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
@@ -449,8 +449,13 @@ const char *nvfp4_status_string(int status)
 
 void nvfp4_set_timing(int enabled)
 {
+    nvfp4_set_timing_ops(enabled != 0 ? 0xffffffffu : 0u);
+}
+
+void nvfp4_set_timing_ops(uint32_t op_mask)
+{
     std::lock_guard<std::mutex> lk(g_mu);
-    g_timing = enabled != 0;
+    g_timing = op_mask;
     g_used = 0;
 }
 

@@ -160,26 +160,24 @@ __device__ __forceinline__ void encode_block16(const uint32_t (&w)[8], float sb,
 }
 
 // ---- Four-over-Six scale search (Appendix "Scale Search NVFP4 Quantization", Eq. 12-13) ----
-// Squared reconstruction error of a 16-element block under one candidate encoding, in fp32,
-// plus the sum of |x - x^| that the error bound below needs.  den = s_b * s_g rounded to fp32;
-// the codes carry the sign of x, so the decoded values are subtracted as they are.
-__device__ __forceinline__ void block_error_f32(const uint32_t (&w)[8], uint32_t c0, uint32_t c1, float den,
-                                                float &err, float &sabs)
+// Squared reconstruction error of a 16-element block under one candidate encoding, in fp32.
+// den = s_b * s_g rounded to fp32; the codes carry the sign of x, so the decoded values are
+// subtracted as they are.
+__device__ __forceinline__ float block_error_f32(const uint32_t (&w)[8], uint32_t c0, uint32_t c1, float den)
 {
     typedef float float2v __attribute__((ext_vector_type(2)));
-    err = 0.0f;
-    sabs = 0.0f;
+    float err = 0.0f;
 #define NVFP4_ERR(W, C, SEL)                                                                  \
     {                                                                                         \
         float2v q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(C, 1.0f, SEL);                   \
         float d0 = __builtin_fmaf(-q.x, den, bf16lo_to_f32(W)), d1 = __builtin_fmaf(-q.y, den, bf16hi_to_f32(W)); \
         err = __builtin_fmaf(d0, d0, err);                                                    \
         err = __builtin_fmaf(d1, d1, err);                                                    \
-        sabs += fabsf(d0) + fabsf(d1);                                                        \
     }
     NVFP4_ERR(w[0], c0, 0) NVFP4_ERR(w[1], c0, 1) NVFP4_ERR(w[2], c0, 2) NVFP4_ERR(w[3], c0, 3)
     NVFP4_ERR(w[4], c1, 0) NVFP4_ERR(w[5], c1, 1) NVFP4_ERR(w[6], c1, 2) NVFP4_ERR(w[7], c1, 3)
 #undef NVFP4_ERR
+    return err;
 }
 
 // The same error as the fp64 definition evaluates it: every difference |x| - m s_b s_g taken
@@ -219,17 +217,19 @@ __device__ __forceinline__ void encode_block16_4over6(const uint32_t (&w)[8], fl
     uint32_t b0, b1;
     encode_block16(w, sb4, sg, b0, b1);
     const float den6 = sb6 * sg, den4 = sb4 * sg;
-    float e6, t6, e4, t4;
-    block_error_f32(w, a0, a1, den6, e6, t6);
-    block_error_f32(w, b0, b1, den4, e4, t4);
-    // |d~ - d| <= 2^-24 (|x| + |x^| + 6 den) < u; |d~^2 - d^2| <= u (2 |d~| + u); sixteen fused
-    // accumulations add at most 2^-19 of the sum
+    const float e6 = block_error_f32(w, a0, a1, den6), e4 = block_error_f32(w, b0, b1, den4);
+    // |d~ - d| <= 2^-24 (|x| + |x^| + 6 den) < u; |d~^2 - d^2| <= u (2 |d~| + u), and the sixteen
+    // |d~| add up to at most 4 sqrt(sum d~^2) (Cauchy-Schwarz; 4.01 covers the approximate square
+    // root and the rounding of the sum); sixteen fused accumulations add at most 2^-19 of the sum
     const float u6 = 0x1p-22f * (bmax + 6.0f * den6), u4 = 0x1p-22f * (bmax + 6.0f * den4);
-    const float r6 = u6 * (2.0f * t6 + 16.0f * u6) + 0x1p-19f * e6;
-    const float r4 = u4 * (2.0f * t4 + 16.0f * u4) + 0x1p-19f * e4;
+    const float r6 = u6 * (8.02f * __builtin_amdgcn_sqrtf(e6) + 16.0f * u6) + 0x1p-19f * e6;
+    const float r4 = u4 * (8.02f * __builtin_amdgcn_sqrtf(e4) + 16.0f * u4) + 0x1p-19f * e4;
+    // the relative bounds above need normal fp32 numbers: errors near the underflow range
+    // (and exact zeros) go to fp64 as well
+    const bool tiny = fminf(e4, e6) < 0x1p-100f;
     bool pick4;
-    if (e4 + r4 < e6 - r6) pick4 = true;
-    else if (e4 - r4 > e6 + r6) pick4 = false;
+    if (!tiny && e4 + r4 < e6 - r6) pick4 = true;
+    else if (!tiny && e4 - r4 > e6 + r6) pick4 = false;
     else pick4 = block_error_f64(w, b0, b1, sb4, sg) < block_error_f64(w, a0, a1, sb6, sg);
     if (pick4) {
         sbyte = s4;
@@ -258,16 +258,26 @@ __device__ __forceinline__ uint32_t bf16_rne_signed_from_f64(double v)
     return sign | bf16_rne_from_f64(fabs(v));
 }
 
-// K-smoothing (Sec. 3.2, Eq. 6) of one 16-element block given its row mean (a bf16 value held
-// in a double): x_j -> RN_bf16(x_j - mean), the difference taken in fp64.
-__device__ __forceinline__ void smooth_block16(uint32_t (&w)[8], double mu)
+// two fp32 -> packed bf16 (round to nearest even), one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+    float2v v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
+}
+
+// K-smoothing (Sec. 3.2, Eq. 6) of one 16-element block given its row mean (a bf16 value):
+// x_j -> RN_bf16(x_j - mean), one rounding of the exact difference.  An fp32 subtraction
+// followed by the rounding to bf16 gives exactly that for every pair of finite bf16 numbers:
+// when the exponents are at most 15 apart the fp32 difference is exact (8 + 15 + 1 bits), and
+// when they are further apart the smaller operand is below 2^-15 of the larger, which is a
+// bf16 number at least 2^-10 of its magnitude away from the nearest rounding boundary, so both
+// the exact difference and its fp32 rounding round to that operand.
+__device__ __forceinline__ void smooth_block16(uint32_t (&w)[8], float mu)
 {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const uint32_t lo = bf16_rne_signed_from_f64((double)bf16lo_to_f32(w[i]) - mu);
-        const uint32_t hi = bf16_rne_signed_from_f64((double)bf16hi_to_f32(w[i]) - mu);
-        w[i] = lo | (hi << 16);
-    }
+    for (int i = 0; i < 8; ++i) w[i] = pack_bf16x2(bf16lo_to_f32(w[i]) - mu, bf16hi_to_f32(w[i]) - mu);
 }
 
 // Random Hadamard transform (Sec. 2.2, weight-gradient operands) of one group of 16 values

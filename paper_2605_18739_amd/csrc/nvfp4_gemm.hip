@@ -80,15 +80,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-// two fp32 -> packed bf16 (round to nearest even), one v_cvt_pk_bf16_f32
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
-{
-    typedef float float2v __attribute__((ext_vector_type(2)));
-    typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-    float2v v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
-}
-
 // Eight codes (one dword, all inside one 16-element block) times the block
 // scale -> eight f16: four conversions (two codes each) and four packed multiplies.
 __device__ __forceinline__ half8v expand_dword(uint32_t w, half2v p)
@@ -114,7 +105,7 @@ __device__ __forceinline__ int lds_chunk_off(int row, int c) { return row * ROW_
 // through a private 16 KB slab of LDS, 32 output rows at a time: a lane owns (row
 // m, four consecutive n) after the MFMA, and (row m, 16 consecutive bytes) when
 // it stores, so whole rows of the wave tile leave as contiguous runs.
-template <int TM, int TN, int EPI_ACT>
+template <int TM, int TN, int EPI_ACT, int NW = 4>
 __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const GemmArgs &g, uint8_t *lds,
                                               int64_t wave_m0, int64_t wave_n0)
 {
@@ -248,8 +239,12 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
         uint32_t *wmax = (uint32_t *)lds;
         if (lane == 0) wmax[wave] = mx;
         __syncthreads();
-        if (tid == 0)
-            ep.amax_partial[g.partial_base + blockIdx.x] = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+        if (tid == 0) {
+            uint32_t all = wmax[0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) all = max(all, wmax[w]);
+            ep.amax_partial[g.partial_base + blockIdx.x] = all;
+        }
     }
 }
 
@@ -473,6 +468,10 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
 // one chunk -- what a fragment read touches per LDS cycle -- fall on distinct
 // banks.
 // ============================================================================
+#ifndef NVFP4_REGDQ_WAVES
+#define NVFP4_REGDQ_WAVES 4
+#endif
+constexpr int kRegdqWaves = NVFP4_REGDQ_WAVES;   // waves per workgroup of the register-dequantizing kernel (4 or 8)
 constexpr int kCodeStages = 4;         // LDS ring of 128-k code stages: copies run three copy steps ahead, one barrier per two
 constexpr int kScaleSteps = 2;         // copy steps covered by one 16-byte run of scales
 
@@ -485,27 +484,30 @@ __device__ __forceinline__ void wait_vmcnt_le()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
 }
 
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
+template <int BM, int BN, int EPI, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
-    constexpr int WM = BM / 2, WN = BN / 2;        // per-wave tile (2 x 2 waves)
+    // wave grid: 2 x 2 (one wave per SIMD), or eight waves (two per SIMD) as 2 x 4 / 4 x 2
+    constexpr int WGN = NW == 4 ? 2 : (BN % 128 == 0 ? 4 : 2), WGM = NW / WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN;    // per-wave tile
     constexpr int TM = WM / 32, TN = WN / 32;      // 32x32 MFMA tiles per wave
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
     constexpr int NF = TM + TN;                    // operand fragments per MFMA sub-step
     constexpr int NMF = TM * TN;                   // MFMAs per sub-step
     constexpr int ROWS = BM + BN;                  // staged rows: A rows first, then W rows
     constexpr int CODE_STAGE = ROWS * 64;          // 128 k of codes per row
     constexpr int SCALE_STAGE = ROWS * 16;         // 256 k of scales per row
     constexpr int SCALE_BASE = kCodeStages * CODE_STAGE;
-    constexpr int UNITS = ROWS / 16, UPW = (UNITS + 3) / 4;     // 1 KB code copies per stage / per wave (at most)
-    constexpr int SUNITS = ROWS / 64, SUPW = (SUNITS + 3) / 4;  // 1 KB scale copies
-    static_assert(UNITS % 4 == 0 && BM % 64 == 0 && BN % 64 == 0, "tile shape");
+    constexpr int UNITS = ROWS / 16, UPW = (UNITS + NW - 1) / NW;     // 1 KB code copies per stage / per wave (at most)
+    constexpr int SUNITS = ROWS / 64, SUPW = (SUNITS + NW - 1) / NW;  // 1 KB scale copies
+    static_assert(BM % 64 == 0 && BN % 64 == 0, "tile shape");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: it selects LDS targets of the copies
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int64_t m0 = (int64_t)(blockIdx.x / g.n_tiles_n) * BM, n0 = (int64_t)(blockIdx.x % g.n_tiles_n) * BN;
     const int kbytes = (int)(g.K >> 1), kblocks = (int)(g.K >> 4);
@@ -521,11 +523,16 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesW, 0, (int)(g.N * kblocks), 0x00020000);
 
     // ---- copy units.  Code unit u (0 .. UNITS-1) is 16 consecutive staged rows, 64 B
-    // each; wave w issues units w, w+4, w+8, ...  Scale unit: 64 rows, 16 B each.
+    // each; wave w issues units w, w + NW, w + 2 NW, ...  Scale unit: 64 rows, 16 B each.
+    // Every wave issues the same number of copies per step (the prologue's wait counts them):
+    // where the units do not divide evenly a wave repeats the last unit, which writes the
+    // same bytes to the same place.
+    auto code_unit = [&](int x) { return min(wave + NW * x, UNITS - 1); };
+    auto scale_unit = [&](int x) { return min(wave + NW * x, SUNITS - 1); };
     int cvoff[UPW], svoff[SUPW];
 #pragma unroll
     for (int x = 0; x < UPW; ++x) {
-        const int srow = (wave + 4 * x) * 16 + (lane >> 2);
+        const int srow = code_unit(x) * 16 + (lane >> 2);
         const int chunk = (lane & 3) ^ ((srow >> 2) & 3);
         const bool isA = srow < BM;
         const int64_t gr = isA ? m0 + srow : n0 + (srow - BM);
@@ -533,15 +540,15 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     }
 #pragma unroll
     for (int x = 0; x < SUPW; ++x) {
-        const int srow = (wave + 4 * x) * 64 + lane;
+        const int srow = scale_unit(x) * 64 + lane;
         const bool isA = srow < BM;
         const int64_t gr = isA ? m0 + srow : n0 + (srow - BM);
-        svoff[x] = (srow < ROWS && gr < (isA ? g.M : g.N)) ? (int)(gr * kblocks) : 0x7FF00000;
+        svoff[x] = gr < (isA ? g.M : g.N) ? (int)(gr * kblocks) : 0x7FF00000;
     }
     auto copy_codes = [&](int gs) {                 // copy step gs -> code stage gs % kCodeStages
 #pragma unroll
         for (int x = 0; x < UPW; ++x) {
-            const int u = wave + 4 * x;
+            const int u = code_unit(x);
             uint8_t *dst = lds + (gs & (kCodeStages - 1)) * CODE_STAGE + u * 1024;
             if (u * 16 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rcA, (lds_ptr_t)dst, 16, cvoff[x] + gs * 64, 0, 0, 0);
             else __builtin_amdgcn_raw_ptr_buffer_load_lds(rcW, (lds_ptr_t)dst, 16, cvoff[x] + gs * 64, 0, 0, 0);
@@ -550,12 +557,10 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     auto copy_scales = [&](int grp) {               // scale group grp (copy steps 2 grp, 2 grp + 1) -> scale stage grp & 1
 #pragma unroll
         for (int x = 0; x < SUPW; ++x) {
-            const int u = wave + 4 * x;
-            if (u < SUNITS) {                        // wave-uniform
-                uint8_t *dst = lds + SCALE_BASE + (grp & 1) * SCALE_STAGE + u * 1024;
-                if (u * 64 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)dst, 16, svoff[x] + grp * 16, 0, 0, 0);
-                else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsW, (lds_ptr_t)dst, 16, svoff[x] + grp * 16, 0, 0, 0);
-            }
+            const int u = scale_unit(x);
+            uint8_t *dst = lds + SCALE_BASE + (grp & 1) * SCALE_STAGE + u * 1024;
+            if (u * 64 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)dst, 16, svoff[x] + grp * 16, 0, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsW, (lds_ptr_t)dst, 16, svoff[x] + grp * 16, 0, 0, 0);
         }
     };
 
@@ -602,8 +607,8 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
         const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc((void *)g.lora_b, 0, (int)(g.N * 256), 0x00020000);
         constexpr int LUNITS = ROWS / 4;               // 1 KB copies: four rows each
 #pragma unroll
-        for (int x = 0; x < LUNITS / 4; ++x) {
-            const int u = wave + 4 * x;
+        for (int x = 0; x < LUNITS / NW; ++x) {
+            const int u = wave + NW * x;
             const int srow = 4 * u + (lane >> 4);
             const int chunk = (lane & 15) ^ (srow & 15);
             uint8_t *dst = lds + u * 1024;
@@ -755,7 +760,7 @@ __global__ __launch_bounds__(256) void gemm_regdq_kernel(GemmArgs g)
     }
     wait_vmcnt_le<0>();                            // no copy may still be writing LDS when the epilogue reuses it
     __syncthreads();
-    gemm_epilogue<TM, TN, EPI>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
+    gemm_epilogue<TM, TN, EPI, NW>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
 #else
     (void)g;
 #endif
@@ -920,11 +925,12 @@ static hipError_t launch_tiled(const GemmArgs &g, int64_t tiles, hipStream_t s)
 template <int BM, int BN, int EPI>
 static hipError_t launch_regdq(const GemmArgs &g, int64_t tiles, hipStream_t s)
 {
-    constexpr int smem_main = kCodeStages * (BM + BN) * 64 + 2 * (BM + BN) * 16, smem_epi = 4 * 16384;
+    constexpr int NW = kRegdqWaves;
+    constexpr int smem_main = kCodeStages * (BM + BN) * 64 + 2 * (BM + BN) * 16, smem_epi = NW * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_regdq_kernel<BM, BN, EPI>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_regdq_kernel<BM, BN, EPI, NW>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -932,7 +938,7 @@ static hipError_t launch_regdq(const GemmArgs &g, int64_t tiles, hipStream_t s)
     GemmArgs a = g;
     a.n_tiles_n = (int)((g.N + BN - 1) / BN);
     const unsigned grid = (unsigned)tiles;          // a prefix of the row-major tile grid
-    gemm_regdq_kernel<BM, BN, EPI><<<grid, 256, smem, s>>>(a);
+    gemm_regdq_kernel<BM, BN, EPI, NW><<<grid, NW * 64, smem, s>>>(a);
     return hipGetLastError();
 }
 

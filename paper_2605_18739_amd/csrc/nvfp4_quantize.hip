@@ -65,12 +65,13 @@ __global__ __launch_bounds__(256) void amax_partial_kernel(const uint16_t *__res
 // are neighbours (d/16 a power of two up to 64) and add their fp64 partial sums by shuffles.
 // --------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void amax_smooth_kernel(const uint16_t *__restrict__ x, int64_t rows,
-                                                          int d, uint16_t *__restrict__ mean_out,
+                                                          int log2_nb_row, uint16_t *__restrict__ mean_out,
                                                           uint32_t *__restrict__ partial)
 {
     __shared__ uint32_t wave_max[4];
-    const int nb_row = d >> 4;
-    const int64_t nblk = rows * nb_row;
+    const int nb_row = 1 << log2_nb_row;                        // blocks per row, d = 16 nb_row
+    const double inv_d = 1.0 / (double)(16 << log2_nb_row);    // a power of two: the quotient below is exact
+    const int64_t nblk = rows << log2_nb_row;
     const int64_t stride = (int64_t)gridDim.x * 256;           // a multiple of nb_row
     uint32_t acc = 0;
     // the trip count is the same for all lanes of a wave up to the tail, where lanes past the end
@@ -92,11 +93,10 @@ __global__ __launch_bounds__(256) void amax_smooth_kernel(const uint16_t *__rest
             sum += (double)bf16hi_to_f32(w[i]);
         }
         for (int m = 1; m < nb_row; m <<= 1) sum += __shfl_xor(sum, m, 64);
-        const uint32_t mean_bits = bf16_rne_signed_from_f64(sum / (double)d);
-        const double mu = (double)__uint_as_float(mean_bits << 16);
+        const uint32_t mean_bits = bf16_rne_signed_from_f64(sum * inv_d);
         if (live) {
-            if ((g % nb_row) == 0) mean_out[g / nb_row] = (uint16_t)mean_bits;
-            smooth_block16(w, mu);
+            if ((g & (nb_row - 1)) == 0) mean_out[g >> log2_nb_row] = (uint16_t)mean_bits;
+            smooth_block16(w, __uint_as_float(mean_bits << 16));
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
         }
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
                                                             uint8_t *__restrict__ scales,
                                                             float *__restrict__ gs_out,
                                                             const uint16_t *__restrict__ row_mean = nullptr,
-                                                            int heads = 0, int slab_heads = 0)
+                                                            int heads = 0, int slab_heads = 0, int row_shift = 0)
 {
     __shared__ uint32_t lds4[4];
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
@@ -180,7 +180,8 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
             const int64_t g = g0 + u * stride;
             if (g < nblk) {
                 uint32_t w[8] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w, v1[u].x, v1[u].y, v1[u].z, v1[u].w};
-                if constexpr (SMOOTH) smooth_block16(w, (double)__uint_as_float((uint32_t)row_mean[g / nb_row] << 16));
+                // SMOOTH: C / 16 = 1 << row_shift blocks per row
+                if constexpr (SMOOTH) smooth_block16(w, __uint_as_float((uint32_t)row_mean[g >> row_shift] << 16));
                 uint32_t acc = 0;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
@@ -657,7 +658,7 @@ hipError_t launch_amax_smooth(const uint16_t *x, int64_t rows, int d, uint16_t *
 {
     int grid = grid_for(rows * (d >> 4), kMaxPartials);
     *n_partial = grid;
-    amax_smooth_kernel<<<grid, 256, 0, s>>>(x, rows, d, mean_out, partial);
+    amax_smooth_kernel<<<grid, 256, 0, s>>>(x, rows, __builtin_ctz((unsigned)(d >> 4)), mean_out, partial);
     return hipGetLastError();
 }
 
@@ -667,7 +668,8 @@ hipError_t launch_quantize_rows_smooth(const uint16_t *x, int64_t rows, int d, c
 {
     int grid = grid_for(rows * (d >> 4), NVFP4_Q_GRID);
     quantize_rows_kernel<true, true, true><<<grid, 256, 0, s>>>(x, rows, d, d, nullptr, partial, n_partial, codes,
-                                                                scales, gs_out, row_mean);
+                                                                scales, gs_out, row_mean, 0, 0,
+                                                                __builtin_ctz((unsigned)(d >> 4)));
     return hipGetLastError();
 }
 
