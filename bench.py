@@ -87,11 +87,11 @@ def main():
     value = 2 * flops_gemm / (ms_step * 1e-3) / 1e12
     # dominant kernel: the up-projection GEMM (GELU + bf16 H + amax in its epilogue), timed by HIP
     # events on the stream it runs on.  The library launches it as whole waves of 256x256 tiles
-    # (768 of the 784) plus a second, small launch for the last 16 tile positions; the events
+    # (768 of the 784) plus a second, small launch (64x64 tiles) for the last 16 tile positions; the events
     # bracket both, and the flops are those of the whole projection.
     up_ms = ms_up / max(n_up, 1)
     achieved = flops_gemm / (up_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "up projection 3520x14336x3072, f16 MFMA: gemm_regdq_kernel<256,256,bf16+gelu> (768 tiles) + gemm_ldsf16_kernel<128,128,bf16+gelu> (rest)",
+    roofline = {"bound": "mfma", "kernel": "up projection 3520x14336x3072, f16 MFMA: gemm_regdq_kernel<256,256,bf16+gelu> (768 tiles) + gemm_ldsf16_kernel<64,64,bf16+gelu> (rest)",
                 "achieved": round(achieved, 1), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4), "traffic": profile_traffic(),
                 "avg_launch_ms": round(up_ms, 4), "launches": n_up}

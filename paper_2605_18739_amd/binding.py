@@ -79,6 +79,8 @@ def lib():
         L.nvfp4_workspace_bytes.argtypes = [c.c_int, i64, i64, i64]
         L.nvfp4_status_string.restype = c.c_char_p
         L.nvfp4_status_string.argtypes = [c.c_int]
+        L.nvfp4_gemm_plan.restype = c.c_int
+        L.nvfp4_gemm_plan.argtypes = [i64, i64, i64, c.c_char_p, sz]
         L.nvfp4_set_timing.restype = None
         L.nvfp4_set_timing.argtypes = [c.c_int]
         L.nvfp4_set_timing_ops.restype = None
@@ -329,6 +331,14 @@ def nvfp4_kv_dequant(q, T, H, d, out=None, stream=None):
     ct = q.c()
     _check(lib().nvfp4_kv_dequant(ctypes.byref(ct), _ptr(out), T, H, d, _stream(stream)))
     return out
+
+
+def nvfp4_gemm_plan(M, N, K):
+    """-> list of (tile, workgroups) per launch, e.g. [("256x256", 768), ("64x64", 192)]; host only."""
+    buf = ctypes.create_string_buffer(256)
+    _check(min(lib().nvfp4_gemm_plan(M, N, K, buf, len(buf)), 0))
+    return [(item.split(":")[0], int(item.split(":")[1])) if ":" in item else (item, 0)
+            for item in buf.value.decode().split()]
 
 
 def nvfp4_set_timing(enabled):

@@ -447,6 +447,14 @@ const char *nvfp4_status_string(int status)
     }
 }
 
+int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, char *text, size_t text_bytes)
+{
+    if (!text) return NVFP4_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || (K & 15) != 0 || text_bytes == 0) return NVFP4_ERR_SHAPE;
+    const int n = gemm_plan_text(M, N, K, text, text_bytes);
+    return n < 0 ? NVFP4_ERR_WORKSPACE : n;
+}
+
 void nvfp4_set_timing(int enabled)
 {
     nvfp4_set_timing_ops(enabled != 0 ? 0xffffffffu : 0u);

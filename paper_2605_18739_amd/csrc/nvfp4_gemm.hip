@@ -19,6 +19,7 @@
 #include "nvfp4_device.h"
 #include "nvfp4_kernels.h"
 
+#include <cstdio>
 #include <type_traits>
 
 #ifndef NVFP4_SCHED
@@ -276,13 +277,19 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
 {
     constexpr int WM = BM / 2, WN = BN / 2;        // per-wave tile (2 x 2 waves)
     constexpr int TM = WM / 32, TN = WN / 32;      // 32x32 MFMA tiles per wave
-    constexpr int CA = BM / 128, CW = BN / 128;    // staging units (16 B of codes) per thread and step
-    constexpr int NU = CA + CW;
+    // Staging units: 128 staged rows, 16 B of codes per thread and step.  Tiles of 128-row
+    // multiples have whole units of A and of W; the 64 x 64 tile has one unit whose rows
+    // 0..63 are A and 64..127 are W (waves 0-1 stage A, waves 2-3 stage W).
+    constexpr bool MIXED = BM < 128;
+    static_assert(MIXED ? (BM == 64 && BN == 64) : (BM % 128 == 0 && BN % 128 == 0), "tile shape");
+    constexpr int CA = MIXED ? 0 : BM / 128, CW = MIXED ? 0 : BN / 128;
+    constexpr int NU = MIXED ? 1 : CA + CW;
     constexpr int A_BYTES = BM * ROW_BYTES, W_BYTES = BN * ROW_BYTES;
     constexpr int W_BASE = 2 * A_BYTES;            // LDS: [A buf0][A buf1][W buf0][W buf1]
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: it selects the operand a unit belongs to
     const int wm = wave >> 1, wn = wave & 1;
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int64_t m0 = (int64_t)(blockIdx.x / g.n_tiles_n) * BM, n0 = (int64_t)(blockIdx.x % g.n_tiles_n) * BN;
@@ -295,14 +302,17 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
     const __amdgpu_buffer_rsrc_t rcW = __builtin_amdgcn_make_buffer_rsrc((void *)g.codesW, 0, (int)(g.N * kbytes), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesW, 0, (int)(g.N * kblocks), 0x00020000);
 
-    // staging: unit u of this thread covers row (tid >> 1) + 128 u', half-row (tid & 1);
+    // staging: unit u of this thread covers staged row (tid >> 1) + 128 u', half-row (tid & 1);
     // units 0..CA-1 belong to A, CA..NU-1 to W
     const int srow = tid >> 1, hsel = tid & 1;
+    auto unit_is_a = [&](int u) { return MIXED ? wave < 2 : u < CA; };
     int vc[NU], vs[NU];
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-        const int64_t gr = (u < CA ? m0 : n0) + srow + 128 * (u < CA ? u : u - CA);
-        const int64_t lim = u < CA ? g.M : g.N;
+        const bool isA = unit_is_a(u);
+        const int64_t gr = MIXED ? (isA ? m0 + srow : n0 + (srow - 64))
+                                 : (u < CA ? m0 : n0) + srow + 128 * (u < CA ? u : u - CA);
+        const int64_t lim = isA ? g.M : g.N;
         // an out-of-range row gets an offset past the end of the buffer (reads zero)
         vc[u] = gr < lim ? (int)(gr * kbytes) + hsel * 16 : 0x7FFFFFF0;
         vs[u] = gr < lim ? (int)(gr * kblocks) + hsel * 2 : 0x7FFFFFF0;
@@ -310,7 +320,7 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
     int st_a[4], st_w[4];          // LDS byte offsets of this thread's four chunks of a staged row
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        st_a[i] = lds_chunk_off(srow, 4 * hsel + i);
+        st_a[i] = lds_chunk_off(MIXED ? (srow & 63) : srow, 4 * hsel + i);
         st_w[i] = st_a[i] + W_BASE;
     }
     int fr_a[4], fr_w[4];          // LDS byte offsets of this lane's fragment in phase kk
@@ -324,17 +334,24 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
     uint32_t rs[NU];
     auto load_unit = [&](int u, int kt) {
         kt = min(kt, KT - 1);                      // never read past the last K step of a row
-        rc[u] = __builtin_amdgcn_raw_buffer_load_b128(u < CA ? rcA : rcW, vc[u], kt * 32, 0);
-        rs[u] = __builtin_amdgcn_raw_buffer_load_b16(u < CA ? rsA : rsW, vs[u], kt * 4, 0);
+        if (unit_is_a(u)) {
+            rc[u] = __builtin_amdgcn_raw_buffer_load_b128(rcA, vc[u], kt * 32, 0);
+            rs[u] = __builtin_amdgcn_raw_buffer_load_b16(rsA, vs[u], kt * 4, 0);
+        } else {
+            rc[u] = __builtin_amdgcn_raw_buffer_load_b128(rcW, vc[u], kt * 32, 0);
+            rs[u] = __builtin_amdgcn_raw_buffer_load_b16(rsW, vs[u], kt * 4, 0);
+        }
     };
     // half h of unit u: 16 codes = one block -> two 16-byte f16 chunks
     auto stage_half = [&](int u, int h, int buf) {
-        const int imm = u < CA ? buf * A_BYTES + u * 128 * ROW_BYTES : buf * W_BYTES + (u - CA) * 128 * ROW_BYTES;
-        const int *st = u < CA ? st_a : st_w;
+        const bool isA = unit_is_a(u);
+        const int imm = MIXED ? buf * A_BYTES
+                              : (u < CA ? buf * A_BYTES + u * 128 * ROW_BYTES : buf * W_BYTES + (u - CA) * 128 * ROW_BYTES);
+        const int o0 = isA ? st_a[2 * h] : st_w[2 * h], o1 = isA ? st_a[2 * h + 1] : st_w[2 * h + 1];
         half2v sc = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rs[u], 1.0f, false);   // both E4M3 scales -> f16
         half2v p = h ? half2v{sc.y, sc.y} : half2v{sc.x, sc.x};
-        *(half8v *)(lds + st[2 * h] + imm) = expand_dword(rc[u][2 * h], p);
-        *(half8v *)(lds + st[2 * h + 1] + imm) = expand_dword(rc[u][2 * h + 1], p);
+        *(half8v *)(lds + o0 + imm) = expand_dword(rc[u][2 * h], p);
+        *(half8v *)(lds + o1 + imm) = expand_dword(rc[u][2 * h + 1], p);
     };
 
     float16v acc[TN][TM];
@@ -945,9 +962,9 @@ static hipError_t launch_regdq(const GemmArgs &g, int64_t tiles, hipStream_t s)
 // Tile choice.  Cost of a launch in units of "one 64-k step of a 256x256 tile":
 // waves of workgroups over the 256 CUs times (steps per tile * relative step cost +
 // a fixed per-tile overhead worth about 8 steps), plus about 4 for the launch itself.
-enum TileKind { kTile128 = 0, kTile256x256 = 1, kTile256x192 = 2 };
+enum TileKind { kTile128 = 0, kTile256x256 = 1, kTile256x192 = 2, kTile64 = 3 };
 struct TileShape { int bm, bn; double step_cost; };
-static const TileShape kShapes[3] = {{128, 128, 0.45}, {256, 256, 1.0}, {256, 192, 0.80}};
+static const TileShape kShapes[4] = {{128, 128, 0.45}, {256, 256, 1.0}, {256, 192, 0.80}, {64, 64, 0.22}};
 constexpr int kCUs = 256;
 
 static double tile_cost(int64_t M, int64_t N, int64_t K, const TileShape &t)
@@ -960,16 +977,19 @@ static double tile_cost(int64_t M, int64_t N, int64_t K, const TileShape &t)
 // big_only: only the 256-row tile shapes (the kernels that can carry the LoRA phase)
 static TileKind choose_tile(int64_t M, int64_t N, int64_t K, double *cost = nullptr, bool big_only = false)
 {
-    int best = 0;
-    double c[3];
-    for (int i = 0; i < 3; ++i) {
-        c[i] = tile_cost(M, N, K, kShapes[i]);
-        // prefer the larger tile on ties (order: 256x256, 256x192, 128x128)
+    // order of preference on ties: the larger tile
+    static const TileKind order[4] = {kTile256x256, kTile256x192, kTile128, kTile64};
+    TileKind best = kTile256x256;
+    double cbest = 1e300;
+    for (int i = 0; i < (big_only ? 2 : 4); ++i) {
+        const double c = tile_cost(M, N, K, kShapes[order[i]]);
+        if (c < cbest) {
+            cbest = c;
+            best = order[i];
+        }
     }
-    if (big_only) c[0] = 1e300;
-    best = (c[1] <= c[0] && c[1] <= c[2]) ? 1 : (c[2] <= c[0] ? 2 : 0);
-    if (cost) *cost = c[best];
-    return (TileKind)best;
+    if (cost) *cost = cbest;
+    return best;
 }
 
 // A launch plan: the main launch runs whole waves of tiles (in row-major tile
@@ -1024,6 +1044,25 @@ static bool tiled_ok(int64_t M, int64_t N, int64_t K)
 
 bool gemm_is_tiled(int64_t M, int64_t N, int64_t K) { return tiled_ok(M, N, K); }
 
+// "BMxBN:workgroups" per launch, separated by spaces ("generic" for the untiled fallback)
+int gemm_plan_text(int64_t M, int64_t N, int64_t K, char *text, size_t text_bytes)
+{
+    if (!tiled_ok(M, N, K)) {
+        snprintf(text, text_bytes, "generic");
+        return 1;
+    }
+    const LaunchPlan p = plan_gemm(M, N, K);
+    size_t used = 0;
+    for (int i = 0; i < p.n; ++i) {
+        const TileShape &t = kShapes[p.part[i].kind];
+        const int w = snprintf(text + used, used < text_bytes ? text_bytes - used : 0, "%s%dx%d:%lld", i ? " " : "", t.bm,
+                               t.bn, (long long)p.part[i].tiles);
+        if (w < 0 || used + (size_t)w >= text_bytes) return -1;
+        used += (size_t)w;
+    }
+    return p.n;
+}
+
 int gemm_workgroups(int64_t M, int64_t N, int64_t K)
 {
     const LaunchPlan p = plan_gemm(M, N, K);
@@ -1040,6 +1079,7 @@ static hipError_t launch_kind(TileKind kind, const GemmArgs &g, int64_t tiles, h
     case kTile256x192: return launch_regdq<256, 192, EPI>(g, tiles, s);
     default:
         if constexpr ((EPI & kEpiLora) != 0) return hipErrorInvalidValue;   // planned with the 256-row tiles only
+        else if (kind == kTile64) return launch_tiled<64, 64, EPI>(g, tiles, s);
         else return launch_tiled<128, 128, EPI>(g, tiles, s);
     }
 }

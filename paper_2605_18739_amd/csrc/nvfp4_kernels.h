@@ -82,6 +82,8 @@ size_t lora_down_workspace_bytes(int64_t M, int64_t K);
 hipError_t launch_lora_down(const uint16_t *x, int64_t M, int64_t K, int64_t ldx, const uint16_t *a,
                             uint16_t *t, float *workspace, hipStream_t s);
 int gemm_workgroups(int64_t M, int64_t N, int64_t K);
+// the launches of a GEMM of this shape as text ("256x256:768 64x64:192"); returns their number, -1 if the text does not fit
+int gemm_plan_text(int64_t M, int64_t N, int64_t K, char *text, size_t text_bytes);
 bool gemm_is_tiled(int64_t M, int64_t N, int64_t K);   // false: the untiled fallback kernel (no fused epilogues)
 
 }  // namespace nvfp4

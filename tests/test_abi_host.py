@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2605_18739_amd as nv
@@ -154,6 +155,50 @@ def test_gemm_and_kv_reject_bad_arguments_on_the_host():
     assert L.nvfp4_kv_quant(kv, 2, 3, 24, ctypes.byref(_t(rows=6, K=24)), ws, 4096, None) == -2
     assert L.nvfp4_kv_dequant(ctypes.byref(t), None, 2, 3, 32, None) == -1
     assert L.nvfp4_kv_dequant(ctypes.byref(t), kv, 2, 4, 32, None) == -2
+
+
+def test_gemm_launch_plan():
+    """Host logic of the GEMM tiling: whole waves of large tiles on the 256 compute units, the
+    leftover rectangle on smaller tiles, every output covered exactly once."""
+    # the DiT FFN pair of the benchmark: 784 tiles of 256x256 = 3 waves + 16; the last 16 tile
+    # positions (192 valid rows x 4096 columns) run as 3 x 64 tiles of 64x64
+    assert nv.nvfp4_gemm_plan(3520, 14336, 3072) == [("256x256", 768), ("64x64", 192)]
+    assert nv.nvfp4_gemm_plan(3520, 3072, 14336) == [("256x192", 224)]
+    assert nv.nvfp4_gemm_plan(64, 64, 48) == [("generic", 0)]          # K % 64 != 0
+    assert nv.nvfp4_gemm_plan(130, 260, 128) == [("generic", 0)]       # N % 8 != 0
+    rng = np.random.default_rng(5)
+    seen = set()
+    for _ in range(300):
+        M, N = int(rng.integers(1, 20000)), int(rng.integers(1, 2500)) * 8
+        K = int(rng.integers(1, 64)) * 64
+        plan = nv.nvfp4_gemm_plan(M, N, K)
+        bm, bn = (int(v) for v in plan[0][0].split("x"))
+        tiles_n = -(-N // bn)
+        main = plan[0][1]
+        assert main <= -(-M // bm) * tiles_n
+        if len(plan) == 1:
+            assert main == -(-M // bm) * tiles_n
+        else:
+            # the main launch is a whole number of waves and stops inside tile row q at column c;
+            # the other launches tile [row q, from column c] and [rows below q] completely
+            assert main % 256 == 0
+            q, c = divmod(main, tiles_n)
+            rects = []
+            if c:
+                rects.append((min(M, (q + 1) * bm) - q * bm, N - c * bn))
+            below = M - (q + (1 if c else 0)) * bm
+            if below > 0:
+                rects.append((below, N))
+            assert len(rects) == len(plan) - 1
+            for (rm, rn), (tile, wgs) in zip(rects, plan[1:]):
+                tm, tn = (int(v) for v in tile.split("x"))
+                assert wgs == -(-rm // tm) * -(-rn // tn)
+        seen.update(t for t, _ in plan)
+    assert seen == {"256x256", "256x192", "128x128", "64x64"}
+    text = ctypes.create_string_buffer(4)
+    assert nv.lib().nvfp4_gemm_plan(3520, 14336, 3072, text, 4) == -4    # text does not fit
+    assert nv.lib().nvfp4_gemm_plan(3520, 14336, 3072, None, 64) == -1
+    assert nv.lib().nvfp4_gemm_plan(3520, 14336, 3070, text, 4) == -2
 
 
 def test_binding_fails_loudly_without_the_library(monkeypatch):

@@ -162,8 +162,10 @@ def test_gemm_config1(oracle):
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 4, 64), (100, 136, 192), (130, 260, 128), (300, 520, 64),
-                                   (513, 1028, 320)])
+                                   (513, 1028, 320),
+                                   (1100, 2048, 320)])     # 128x128 tiles, odd number of 64-k steps
 def test_gemm_ragged_tiles(oracle, M, N, K):
+    say(f"[gemm] ragged {M}x{N}x{K}: {nv.nvfp4_gemm_plan(M, N, K)}")
     g = np.random.default_rng(M + N + K)
     ab = wl.to_bf16_bits(g.standard_normal((M, K)).astype(np.float32))
     wb = wl.to_bf16_bits((g.standard_normal((N, K)) * 0.02).astype(np.float32))
@@ -496,6 +498,22 @@ def test_kv_quant_k_degenerate_rows(oracle):
     assert (nv.bits_from_bf16(zm) == 0).all()
 
 
+def test_kv_quant_k_wide_exponent_range(oracle):
+    """Elements up to 2^36 apart in one row: the difference to the row mean is far from exact in
+    fp32 for many of them, the rounded result must still be the single rounding of the exact one."""
+    T, H, d = 16, 8, 128
+    g = np.random.default_rng(77)
+    e = g.integers(-18, 19, size=(T * H, d))
+    x = (np.ldexp(1.0 + g.integers(0, 128, size=e.shape) / 128.0, e) * g.choice([-1.0, 1.0], size=e.shape)).astype(np.float32)
+    x[::3] = np.abs(x[::3])                         # rows with a mean of the size of their largest element
+    kb = wl.to_bf16_bits(x)
+    want_mean, want_q = _oracle_k_path(oracle, kb)
+    say(f"[kv-k] wide exponent range {T}x{H}x{d}")
+    got_q, got_mean = nv.nvfp4_kv_quant_k(dev_bf16(kb).reshape(T, H, d))
+    assert (nv.bits_from_bf16(got_mean) == want_mean).all()
+    assert_q_equal(got_q, want_q, "wide exponent range")
+
+
 def test_kv_dequant_gather_window(oracle):
     """A sink chunk plus a sliding window of chunks of different lengths, keys smoothed and values
     plain, reconstructed by one launch each: every byte equals the per-chunk oracle output."""
@@ -559,6 +577,7 @@ def _act_quant_case(oracle, M, N, K, given_scale, what):
 def test_gemm_act_quant(oracle, given_scale):
     _act_quant_case(oracle, 200, 272, 256, given_scale, "small")
     _act_quant_case(oracle, 520, 1040, 128, given_scale, "multi-tile")
+    _act_quant_case(oracle, 1100, 2048, 192, given_scale, "128x128 tiles")
     _act_quant_case(oracle, 2100, 2064, 256, given_scale, "256x192 tiles")
     _act_quant_case(oracle, 4200, 3072, 128, given_scale, "256x256 tiles")
     _act_quant_case(oracle, 40, 48, 48, given_scale, "untiled K")
