@@ -474,10 +474,11 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
 //
 // K order: a "register step" is 64 k = four MFMA sub-steps.  In register step
 // (g, half) -- g counts 128-k copy steps -- lane half h (lanes 32h .. 32h+31) of
-// an MFMA operand owns chunk 2 half + h of its row, i.e. k = 128 g + 32 (2 half
-// + h) + 0..31, and MFMA sub-step j multiplies the eight codes of dword j of that
-// chunk, which share block scale 4 half + 2 h + j/2 of the copy step.  This is a
-// permutation of k applied to both operands alike.
+// an MFMA operand owns chunk 2 h + half of its row, i.e. k = 128 g + 32 (2 h +
+// half) + 0..31, and MFMA sub-step j multiplies the eight codes of dword j of that
+// chunk, which share block scale 4 h + 2 half + j/2 of the copy step: the four
+// scale bytes a lane needs for one copy step are one aligned dword, read once.
+// This is a permutation of k applied to both operands alike.
 //
 // LDS: chunk c of staged row r sits in 16-byte slot 4 r + (c ^ ((r >> 2) & 3)) of
 // its stage; the copy instructions fill slots in lane order (lane l of unit u
@@ -528,8 +529,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int64_t m0 = (int64_t)(blockIdx.x / g.n_tiles_n) * BM, n0 = (int64_t)(blockIdx.x % g.n_tiles_n) * BN;
     const int kbytes = (int)(g.K >> 1), kblocks = (int)(g.K >> 4);
-    const int KT = (int)(g.K / BK);                // register steps
-    const int GT = (KT + 1) / 2;                   // copy steps
+    const int GT = (int)((g.K + 2 * BK - 1) / (2 * BK));   // copy steps
+    const int KT = 2 * GT;                         // register steps (K = 64 mod 128: the upper half of the last copy step is zeros)
+    const bool k_tail = (g.K & (2 * BK - 1)) != 0;
 
     // Copies are range checked against the operand size: a row past the end of the
     // operand, and the part of the last copy step past the end of the last row, read
@@ -562,13 +564,18 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
         const int64_t gr = isA ? m0 + srow : n0 + (srow - BM);
         svoff[x] = gr < (isA ? g.M : g.N) ? (int)(gr * kblocks) : 0x7FF00000;
     }
+    // A lane fetches chunk (lane & 3) ^ ((lane >> 4) & 3) of its row in every unit.  When K ends in
+    // the middle of the last copy step, chunks 2 and 3 of that step lie past the end of the row:
+    // their lanes get an offset past the end of the operand, which reads as zeros.
+    const bool hi_chunk = (((lane & 3) ^ ((lane >> 4) & 3)) & 2) != 0;
     auto copy_codes = [&](int gs) {                 // copy step gs -> code stage gs % kCodeStages
+        const int past = (k_tail && gs == GT - 1 && hi_chunk) ? 0x7FF00000 : 0;
 #pragma unroll
         for (int x = 0; x < UPW; ++x) {
             const int u = code_unit(x);
             uint8_t *dst = lds + (gs & (kCodeStages - 1)) * CODE_STAGE + u * 1024;
-            if (u * 16 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rcA, (lds_ptr_t)dst, 16, cvoff[x] + gs * 64, 0, 0, 0);
-            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rcW, (lds_ptr_t)dst, 16, cvoff[x] + gs * 64, 0, 0, 0);
+            if (u * 16 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rcA, (lds_ptr_t)dst, 16, (cvoff[x] + gs * 64) | past, 0, 0, 0);
+            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rcW, (lds_ptr_t)dst, 16, (cvoff[x] + gs * 64) | past, 0, 0, 0);
         }
     };
     auto copy_scales = [&](int grp) {               // scale group grp (copy steps 2 grp, 2 grp + 1) -> scale stage grp & 1
@@ -586,20 +593,21 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
     const int key = (lrow >> 2) & 3;
     int code_lane[2];                               // byte offset inside a stage for half 0 / 1, tile 0 of A
 #pragma unroll
-    for (int half = 0; half < 2; ++half) code_lane[half] = lrow * 64 + (((2 * half + lhalf) ^ key) << 4);
-    const int scale_lane = lrow * 16 + 2 * lhalf;
+    for (int half = 0; half < 2; ++half) code_lane[half] = lrow * 64 + (((2 * lhalf + half) ^ key) << 4);
+    const int scale_lane = lrow * 16 + 4 * lhalf;
     auto frag_row0 = [&](int f) { return f < TM ? wm * WM + f * 32 : BM + wn * WN + (f - TM) * 32; };
     uint4v codes[2][NF];          // packed codes of the register step being multiplied / the next one
-    uint16_t scl[2][NF];          // their two block scales (E4M3 bytes) ...
-    uint32_t scf[2][NF];          // ... and the same as a pair of f16
-    auto read_step = [&](int rs, int set) {         // register step rs = 2 gs + half
+    uint32_t scl[NF];             // the four block scales (E4M3 bytes) of a lane's two register steps of one copy step ...
+    uint32_t scf[2][NF];          // ... and those of one register step as a pair of f16
+    // register step rs = 2 gs + half; with_scales: rs is even, the copy step's scales are read too
+    auto read_step = [&](int rs, int set, bool with_scales) {
         const int gs = rs >> 1, half = rs & 1;
         const uint8_t *cbase = lds + (gs & (kCodeStages - 1)) * CODE_STAGE + code_lane[half];
-        const uint8_t *sbase = lds + SCALE_BASE + ((gs >> 1) & 1) * SCALE_STAGE + (gs & 1) * 8 + half * 4 + scale_lane;
+        const uint8_t *sbase = lds + SCALE_BASE + ((gs >> 1) & 1) * SCALE_STAGE + (gs & 1) * 8 + scale_lane;
 #pragma unroll
         for (int f = 0; f < NF; ++f) {
             codes[set][f] = *(const uint4v *)(cbase + frag_row0(f) * 64);
-            scl[set][f] = *(const uint16_t *)(sbase + frag_row0(f) * 16);
+            if (with_scales) scl[f] = *(const uint32_t *)(sbase + frag_row0(f) * 16);
         }
     };
 
@@ -686,12 +694,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
         frag[j & 1][f][d0] = x0;
         frag[j & 1][f][d1] = x1;
     };
-    auto convert_scales = [&](int set, int f) {     // E4M3 pair -> f16 pair, pinned where it is written
-        uint16_t raw16 = scl[set][f];
-        NVFP4_PIN1(raw16);                          // do not touch it before this point (the LDS read may still be in flight)
-        uint32_t raw = raw16;
-        uint32_t x = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(raw, 1.0f, false));
+    // E4M3 pair of register step parity `odd` (low / high half of the dword) -> f16 pair, pinned where it is written
+    auto convert_scales = [&](int set, int f, bool odd) {
+        uint32_t raw = scl[f];
+        NVFP4_PIN1(raw);                            // do not touch it before this point (the LDS read may still be in flight)
+        uint32_t x = odd ? __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(raw, 1.0f, true))
+                         : __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(raw, 1.0f, false));
         NVFP4_PIN1(x);
+        scl[f] = raw;
         scf[set][f] = x;
     };
 
@@ -706,9 +716,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
     NVFP4_COMPILER_FENCE();
     __builtin_amdgcn_s_barrier();
     NVFP4_COMPILER_FENCE();
-    read_step(0, 0);
+    read_step(0, 0, true);
 #pragma unroll
-    for (int f = 0; f < NF; ++f) convert_scales(0, f);
+    for (int f = 0; f < NF; ++f) convert_scales(0, f, false);
 #pragma unroll
     for (int pc = 0; pc < 2 * NF; ++pc) expand_piece(0, 0, pc);
 
@@ -730,7 +740,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
             __builtin_amdgcn_s_barrier();
             NVFP4_COMPILER_FENCE();
         }
-        read_step(rs + 1, set ^ 1);
+        read_step(rs + 1, set ^ 1, half == 1);
         if constexpr (half == 1) {
             const int ng = (rs >> 1) + 3;                   // copy step to start (clamped at the end of K)
             if constexpr (quarter == 3) copy_scales(min(ng, GT - 1) >> 1);   // ng is even here: a new scale group
@@ -752,7 +762,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
                         else expand_piece(set ^ 1, 0, pc);
                     }
                 // the next step's scales (read at the top of this iteration) become f16 during sub-step 2
-                if (j == 2 && t < NF) convert_scales(set ^ 1, t);
+                if (j == 2 && t < NF) convert_scales(set ^ 1, t, half == 0);
 #if NVFP4_SCHED
                 __builtin_amdgcn_sched_barrier(0);
 #endif
@@ -771,9 +781,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
             iteration(rs + 2, Q2{});
             iteration(rs + 3, Q3{});
         }
-        if (rs < KT) iteration(rs, Q0{});
-        if (rs + 1 < KT) iteration(rs + 1, Q1{});
-        if (rs + 2 < KT) iteration(rs + 2, Q2{});
+        if (rs < KT) {                              // KT is even: two steps are left, or none
+            iteration(rs, Q0{});
+            iteration(rs + 1, Q1{});
+        }
     }
     wait_vmcnt_le<0>();                            // no copy may still be writing LDS when the epilogue reuses it
     __syncthreads();
