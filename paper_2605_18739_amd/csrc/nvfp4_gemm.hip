@@ -379,6 +379,79 @@ __global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
         }
     };
 
+    if constexpr (MIXED) {
+        // One MFMA tile per wave: the phase-by-phase pipeline below would expose an LDS round
+        // trip per MFMA and one global-load latency per step.  Instead the codes of the next
+        // four steps are kept in flight in registers, all four phases' fragments of a step are
+        // read at once right after the barrier that completes the step's buffer, and the four
+        // MFMAs follow back to back while the next step is expanded into the other buffer.
+        constexpr int D = 4;                        // steps in flight
+        uint4v qc[D];
+        uint32_t qs[D];
+        const bool isA = wave < 2;
+        auto fetch = [&](int slot, int kt) {
+            kt = min(kt, KT - 1);                   // never read past the last K step of a row
+            if (isA) {
+                qc[slot] = __builtin_amdgcn_raw_buffer_load_b128(rcA, vc[0], kt * 32, 0);
+                qs[slot] = __builtin_amdgcn_raw_buffer_load_b16(rsA, vs[0], kt * 4, 0);
+            } else {
+                qc[slot] = __builtin_amdgcn_raw_buffer_load_b128(rcW, vc[0], kt * 32, 0);
+                qs[slot] = __builtin_amdgcn_raw_buffer_load_b16(rsW, vs[0], kt * 4, 0);
+            }
+        };
+        auto stage = [&](int slot, int buf) {       // 32 codes = two blocks -> four 16-byte f16 chunks
+            half2v sc = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(qs[slot], 1.0f, false);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                half2v p = h ? half2v{sc.y, sc.y} : half2v{sc.x, sc.x};
+                const int o0 = (isA ? st_a[2 * h] : st_w[2 * h]) + buf * A_BYTES;
+                const int o1 = (isA ? st_a[2 * h + 1] : st_w[2 * h + 1]) + buf * A_BYTES;
+                *(half8v *)(lds + o0) = expand_dword(qc[slot][2 * h], p);
+                *(half8v *)(lds + o1) = expand_dword(qc[slot][2 * h + 1], p);
+            }
+        };
+        half8v a4[4], w4[4];
+        auto read_all = [&](int buf) {
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                a4[kk] = *(const half8v *)(lds + fr_a[kk] + buf * A_BYTES);
+                w4[kk] = *(const half8v *)(lds + fr_w[kk] + buf * W_BYTES);
+            }
+        };
+        // slot of step t: t mod D.  Prologue: steps 0 .. D in flight / staged.
+#pragma unroll
+        for (int t = 0; t < D; ++t) fetch(t, t);
+        stage(0, 0);
+        fetch(0, D);
+        __syncthreads();
+        read_all(0);
+        // iteration kt multiplies step kt out of buffer kt & 1, stages step kt + 1 (slot (kt + 1) mod D)
+        // into the other buffer, which was last read before the previous barrier, and refills the slot
+        auto iteration = [&](int kt, auto slot_c) {
+            constexpr int slot = decltype(slot_c)::value;       // (kt + 1) mod D
+            const int buf = kt & 1;
+            stage(slot, buf ^ 1);
+            fetch(slot, kt + 1 + D);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w4[kk], a4[kk], acc[0][0], 0, 0, 0);
+            __syncthreads();
+            read_all(buf ^ 1);
+        };
+        int kt = 0;
+        for (; kt + 3 < KT; kt += 4) {
+            iteration(kt, std::integral_constant<int, 1>{});
+            iteration(kt + 1, std::integral_constant<int, 2>{});
+            iteration(kt + 2, std::integral_constant<int, 3>{});
+            iteration(kt + 3, std::integral_constant<int, 0>{});
+        }
+        if (kt < KT) iteration(kt, std::integral_constant<int, 1>{});
+        if (kt + 1 < KT) iteration(kt + 1, std::integral_constant<int, 2>{});
+        if (kt + 2 < KT) iteration(kt + 2, std::integral_constant<int, 3>{});
+        gemm_epilogue<TM, TN, EPI>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
+        return;
+    }
+
     // prologue: step 0 staged, step 1 in registers, fragments of (step 0, phase 0) in flight
 #pragma unroll
     for (int u = 0; u < NU; ++u) load_unit(u, 0);
