@@ -172,6 +172,27 @@ def test_gemm_ragged_tiles(oracle, M, N, K):
     _gemm_case(oracle, ab, wb, f"ragged {M}x{N}x{K}")
 
 
+def test_gemm_random_shapes(oracle):
+    """Seeded sweep over shapes that land on every tile kind of the launch plan, with ragged M and
+    N tails, odd numbers of 64-k steps and multi-launch plans."""
+    g = np.random.default_rng(20260518)
+    kinds = set()
+    shapes = [(int(g.integers(1, 900)), 8 * int(g.integers(1, 260)), 64 * int(g.integers(1, 9))) for _ in range(10)]
+    shapes += [(1290, 2056, 192), (2400, 2304, 64), (4600, 1800, 320), (9000, 4104, 64), (17000, 3080, 64)]
+    # whole waves of 256x256 tiles plus one or two more launches: rows below the last full wave, the tail
+    # of a tile row, and both
+    shapes += [(5489, 2928, 768), (6418, 7544, 512), (7226, 7000, 1856)]
+    for M, N, K in shapes:
+        plan = nv.nvfp4_gemm_plan(M, N, K)
+        kinds.update(t for t, _ in plan)
+        ab = wl.to_bf16_bits(g.standard_normal((M, K)).astype(np.float32))
+        wb = wl.to_bf16_bits((g.standard_normal((N, K)) * 0.02).astype(np.float32))
+        rows = None if M * N * K < 3e9 else np.unique(np.concatenate([g.integers(0, M, 200), [0, M - 1]]))
+        _gemm_case(oracle, ab, wb, f"sweep {M}x{N}x{K} {plan}", rows=rows, check_bf16=False)
+    assert kinds >= {"64x64", "128x128", "256x192", "256x256"}, kinds
+    assert [len(nv.nvfp4_gemm_plan(*shp)) for shp in shapes[-3:]] == [2, 2, 3]
+
+
 @pytest.mark.parametrize("M,N,K", [(5, 8, 16), (7, 12, 48), (9, 4, 80)])
 def test_gemm_small_k_untiled(oracle, M, N, K):
     g = np.random.default_rng(M * N * K)
