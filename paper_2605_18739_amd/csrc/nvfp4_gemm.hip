@@ -258,6 +258,17 @@ __host__ __device__ constexpr int half_units_in_phase(int NH, int kk)
     return n;
 }
 
+// f(integral_constant<int, I>) for I = First .. Last - 1: a loop whose index is a compile-time
+// constant in the body (array indices stay constants, guards can be `if constexpr`)
+template <int First, int Last, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (First < Last) {
+        f(std::integral_constant<int, First>{});
+        static_for<First + 1, Last>(f);
+    }
+}
+
 // Scheduling request for one phase: NM MFMAs, each followed by its share of NV VALU
 // and ND LDS instructions.
 template <int NV, int ND, int NM, int T = 0>
@@ -641,15 +652,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
     // the middle of the last copy step, chunks 2 and 3 of that step lie past the end of the row:
     // their lanes get an offset past the end of the operand, which reads as zeros.
     const bool hi_chunk = (((lane & 3) ^ ((lane >> 4) & 3)) & 2) != 0;
-    auto copy_codes = [&](int gs) {                 // copy step gs -> code stage gs % kCodeStages
+    auto copy_code_unit = [&](int gs, int x) {      // this wave's x-th unit of copy step gs -> code stage gs % kCodeStages
         const int past = (k_tail && gs == GT - 1 && hi_chunk) ? 0x7FF00000 : 0;
+        const int u = code_unit(x);
+        uint8_t *dst = lds + (gs & (kCodeStages - 1)) * CODE_STAGE + u * 1024;
+        if (u * 16 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rcA, (lds_ptr_t)dst, 16, (cvoff[x] + gs * 64) | past, 0, 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(rcW, (lds_ptr_t)dst, 16, (cvoff[x] + gs * 64) | past, 0, 0, 0);
+    };
+    auto copy_codes = [&](int gs) {
 #pragma unroll
-        for (int x = 0; x < UPW; ++x) {
-            const int u = code_unit(x);
-            uint8_t *dst = lds + (gs & (kCodeStages - 1)) * CODE_STAGE + u * 1024;
-            if (u * 16 < BM) __builtin_amdgcn_raw_ptr_buffer_load_lds(rcA, (lds_ptr_t)dst, 16, (cvoff[x] + gs * 64) | past, 0, 0, 0);
-            else __builtin_amdgcn_raw_ptr_buffer_load_lds(rcW, (lds_ptr_t)dst, 16, (cvoff[x] + gs * 64) | past, 0, 0, 0);
-        }
+        for (int x = 0; x < UPW; ++x) copy_code_unit(gs, x);
     };
     auto copy_scales = [&](int grp) {               // scale group grp (copy steps 2 grp, 2 grp + 1) -> scale stage grp & 1
 #pragma unroll
@@ -673,15 +685,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
     uint32_t scl[NF];             // the four block scales (E4M3 bytes) of a lane's two register steps of one copy step ...
     uint32_t scf[2][NF];          // ... and those of one register step as a pair of f16
     // register step rs = 2 gs + half; with_scales: rs is even, the copy step's scales are read too
-    auto read_step = [&](int rs, int set, bool with_scales) {
+    auto read_frag = [&](int rs, int set, int f, bool with_scales) {
         const int gs = rs >> 1, half = rs & 1;
         const uint8_t *cbase = lds + (gs & (kCodeStages - 1)) * CODE_STAGE + code_lane[half];
         const uint8_t *sbase = lds + SCALE_BASE + ((gs >> 1) & 1) * SCALE_STAGE + (gs & 1) * 8 + scale_lane;
+        codes[set][f] = *(const uint4v *)(cbase + frag_row0(f) * 64);
+        if (with_scales) scl[f] = *(const uint32_t *)(sbase + frag_row0(f) * 16);
+    };
+    auto read_step = [&](int rs, int set, bool with_scales) {
 #pragma unroll
-        for (int f = 0; f < NF; ++f) {
-            codes[set][f] = *(const uint4v *)(cbase + frag_row0(f) * 64);
-            if (with_scales) scl[f] = *(const uint32_t *)(sbase + frag_row0(f) * 16);
-        }
+        for (int f = 0; f < NF; ++f) read_frag(rs, set, f, with_scales);
     };
 
     float16v acc[TN][TM];
@@ -813,34 +826,41 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
             __builtin_amdgcn_s_barrier();
             NVFP4_COMPILER_FENCE();
         }
-        read_step(rs + 1, set ^ 1, half == 1);
-        if constexpr (half == 1) {
-            const int ng = (rs >> 1) + 3;                   // copy step to start (clamped at the end of K)
-            if constexpr (quarter == 3) copy_scales(min(ng, GT - 1) >> 1);   // ng is even here: a new scale group
-            copy_codes(min(ng, GT - 1));
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int t = 0; t < NMF; ++t) {
-                const int i = t / TM, jj = t % TM;
+        // The LDS reads of the next register step and (odd iterations) the copies of copy step
+        // rs/2 + 3 are dealt out behind the MFMAs of sub-steps 0 and 1, one per MFMA, so that
+        // their issue overlaps a running MFMA instead of leaving the matrix pipe idle.
+        const int ng = min((rs >> 1) + 3, GT - 1);          // copy step to start (clamped at the end of K)
+        static_for<0, 4>([&](auto j_c) {
+            constexpr int j = decltype(j_c)::value;
+            static_for<0, NMF>([&](auto t_c) {
+                constexpr int t = decltype(t_c)::value;
+                constexpr int i = t / TM, jj = t % TM;
                 acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, frag[j & 1][TM + i]),
                                                                      __builtin_bit_cast(half8v, frag[j & 1][jj]),
                                                                      acc[i][jj], 0, 0, 0);
                 // next sub-step's fragments: 2 NF pieces dealt over the NMF MFMAs
-#pragma unroll
-                for (int pc = 0; pc < 2 * NF; ++pc)
-                    if (pc * NMF / (2 * NF) == t) {
-                        if (j < 3) expand_piece(set, j + 1, pc);
+                static_for<0, 2 * NF>([&](auto pc_c) {
+                    constexpr int pc = decltype(pc_c)::value;
+                    if constexpr (pc * NMF / (2 * NF) == t) {
+                        if constexpr (j < 3) expand_piece(set, j + 1, pc);
                         else expand_piece(set ^ 1, 0, pc);
                     }
-                // the next step's scales (read at the top of this iteration) become f16 during sub-step 2
-                if (j == 2 && t < NF) convert_scales(set ^ 1, t, half == 0);
+                });
+                if constexpr (j == 0 && t < NF) read_frag(rs + 1, set ^ 1, t, half == 1);
+                if constexpr (half == 1 && j == 1) {
+                    static_for<0, UPW>([&](auto x_c) {
+                        constexpr int x = decltype(x_c)::value;
+                        if constexpr (x * NMF / UPW == t) copy_code_unit(ng, x);
+                    });
+                    if constexpr (quarter == 3 && t == NMF - 1) copy_scales(ng >> 1);   // ng is even here: a new scale group
+                }
+                // the next step's scales (read during sub-step 0) become f16 during sub-step 2
+                if constexpr (j == 2 && t < NF) convert_scales(set ^ 1, t, half == 0);
 #if NVFP4_SCHED
                 __builtin_amdgcn_sched_barrier(0);
 #endif
-            }
-        }
+            });
+        });
     };
     {
         using Q0 = std::integral_constant<int, 0>;
