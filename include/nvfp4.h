@@ -20,6 +20,12 @@
  *     validated on the host before anything is launched; a call that returns
  *     an error has launched nothing.  Non-finite inputs are outside the
  *     contract.
+ *   - Stream capture: an entry point only enqueues kernels (no memset or copy
+ *     nodes, no synchronisation), so it may be called while `stream` is being
+ *     captured into a HIP graph, provided the same entry point has run once
+ *     before on this device with arguments of the same kind (the first launch
+ *     of a kernel variant raises its dynamic LDS limit, which is not a stream
+ *     operation), and launch timing is off.
  *
  * NVFP4 tensor format (Eq. 2):  x^ = code * block_scale * global_scale
  *   codes   [rows, K/2]  two E2M1 codes per byte; element 2j in bits 3:0 and

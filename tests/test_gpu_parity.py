@@ -671,6 +671,48 @@ def _sample_rows(M, n, seed):
     return np.unique(np.concatenate([edge, np.random.default_rng(seed).integers(0, M, n)])).astype(np.int64)
 
 
+def test_ffn_step_replays_from_a_hip_graph():
+    """The entry points allocate nothing, synchronise nothing and clear no memory with memset
+    nodes, so a caller may capture them: one FFN step (quantize, up projection with GELU and
+    re-quantization, down projection) captured once and replayed several times, with eager
+    work and synchronisations in between, gives the eager result bit for bit every time."""
+    M, D, F = 520, 1024, 2048
+    g = np.random.default_rng(11)
+    A = dev_bf16(wl.to_bf16_bits(g.standard_normal((M, D)).astype(np.float32)))
+    W1 = nv.nvfp4_quantize(dev_bf16(wl.to_bf16_bits((g.standard_normal((F, D)) * 0.02).astype(np.float32))))
+    W2 = nv.nvfp4_quantize(dev_bf16(wl.to_bf16_bits((g.standard_normal((D, F)) * 0.02).astype(np.float32))))
+    qA, qH = nv.NVFP4Tensor(M, D, "cuda"), nv.NVFP4Tensor(M, F, "cuda")
+    Y = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+    ws_q = torch.empty(nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE, M, D), dtype=torch.uint8, device="cuda")
+    ws_g = torch.empty(nv.nvfp4_workspace_bytes(nv.OP_GEMM_ACT_QUANT, M, F, 0), dtype=torch.uint8, device="cuda")
+
+    def step():
+        nv.nvfp4_quantize(A, out=qA, workspace=ws_q)
+        nv.nvfp4_gemm_act_quant(qA, W1, nv.ACT_GELU_TANH, out=qH, workspace=ws_g)
+        nv.nvfp4_gemm(qH, W2, nv.OUT_BF16, Y=Y)
+
+    step()                                          # eager: also the first use of every kernel variant
+    torch.cuda.synchronize()
+    want, want_codes = Y.clone(), qH.codes.clone()
+    say("[graph] capture")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        Y.zero_()
+        qH.codes.zero_()
+        A2 = (A.float() * 0.5).to(torch.bfloat16)   # unrelated eager work between the replays
+        torch.cuda.synchronize()
+        say(f"[graph] replay {rep}")
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, want) and torch.equal(qH.codes, want_codes), f"replay {rep}"
+        del A2
+
+
 def test_full_size_ffn_pair_config3(oracle):
     cfg = wl.config3()
     M, D, F = wl.TOKENS_INFER, wl.D_MODEL, wl.D_FFN
