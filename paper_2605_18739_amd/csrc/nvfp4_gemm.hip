@@ -4,13 +4,20 @@
 // Route: every code*block_scale product (<= 6 significant bits, magnitude in
 // [2^-10, 2688]) is an exact f16 number, and f16*f16 products are exact in the
 // FP32 accumulator of v_mfma_f32_32x32x16_f16, so the only rounding left is the
-// FP32 accumulation.  Packed codes travel HBM -> registers (128-bit buffer
-// loads, out-of-range rows read as zero), are expanded once per workgroup with
-// v_cvt_scalef32_pk_f16_fp4 (two codes per instruction) and one packed f16
-// multiply by the block scale (v_cvt_scalef32_pk_f16_fp8 turns the E4M3 byte
-// into f16), and are staged in LDS as f16 in an XOR-swizzled layout that both
-// the 128-bit writes and the 128-bit MFMA fragment reads hit without bank
-// conflicts.
+// FP32 accumulation.  Codes become f16 with v_cvt_scalef32_pk_f16_fp4 (two codes
+// per instruction) and one packed f16 multiply by the block scale
+// (v_cvt_scalef32_pk_f16_fp8 turns the E4M3 byte into f16).
+//
+// Two kernels share the epilogue:
+//  - gemm_regdq_kernel (256x256 and 256x192 tiles): the operands stay 4-bit through
+//    LDS (filled by buffer loads that write LDS directly) and are expanded in
+//    registers in the shadow of the MFMAs that precede their use;
+//  - gemm_ldsf16_kernel (128x128 and 64x64 tiles, small problems and the leftover
+//    rectangle of a launch plan): codes are expanded once per workgroup and staged
+//    in LDS as f16 in an XOR-swizzled layout that both the 128-bit writes and the
+//    128-bit MFMA fragment reads hit without bank conflicts.
+// plan_gemm picks tile shapes and splits a problem into whole waves of large tiles
+// plus the leftover on small ones.
 //
 // Orientation: the MFMA's row operand is the W fragment and its column operand
 // the A fragment, so a lane ends up with ONE output row m and runs of four
