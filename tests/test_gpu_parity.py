@@ -95,6 +95,48 @@ def test_quantize_transposed(oracle, R, C):
     assert_q_equal(gq, oq, f"transposed {R}x{C}")
 
 
+def test_quantize_more_than_2_to_31_elements(oracle):
+    """A tensor past 2^31 elements (4.3 GB of bf16): every index in the kernels is 64-bit.  The tensor
+    is drawn on the device; rows around the 2^31-element mark, the first and last rows and seeded
+    ones are checked against the oracle, which gets the tensor scale the way the kernel finds it
+    (from the one largest element, planted in the last row)."""
+    R, C = 66000, 32768
+    assert R * C > 2 ** 31
+    say(f"[quantize] {R}x{C} = {R * C / 2 ** 30:.2f} Gi elements")
+    x = torch.empty((R, C), dtype=torch.bfloat16, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(31)
+    for r0 in range(0, R, 4000):
+        r1 = min(R, r0 + 4000)
+        x[r0:r1] = torch.randn((r1 - r0, C), generator=gen, device="cuda").to(torch.bfloat16)
+    x[R - 1, C - 1] = 77.0                          # larger than any N(0,1) draw
+    for axis in (0, 1):
+        say(f"[quantize] {R}x{C} block_axis={axis}")
+        q = nv.nvfp4_quantize(x, block_axis=axis)
+        torch.cuda.synchronize()
+        gs = oracle.global_scale(wl.to_bf16_bits(np.array([[77.0]], np.float32)))
+        assert np.float32(q.global_scale.cpu().numpy()[0]).view(np.uint32) == np.float32(gs).view(np.uint32)
+        g = np.random.default_rng(axis)
+        if axis == 0:
+            rows = np.unique(np.concatenate([[0, 1, 65535, 65536, 65537, R - 2, R - 1], g.integers(0, R, 8)]))
+            xb = nv.bits_from_bf16(x[torch.as_tensor(rows, device="cuda")])
+            want = oracle.quantize(xb, global_scale_in=gs)
+            sel = torch.as_tensor(rows, device="cuda")
+            assert (q.codes[sel].cpu().numpy() == want.codes).all()
+            assert (q.scales[sel].cpu().numpy() == want.scales).all()
+        else:
+            # blocks run along the rows: output row = input column; check whole output rows
+            cols = np.unique(np.concatenate([[0, 1, C - 1], g.integers(0, C, 5)]))
+            sel = torch.as_tensor(cols, device="cuda")
+            xb = nv.bits_from_bf16(x[:R - R % 16][:, sel].t().contiguous())
+            want = oracle.quantize(xb, global_scale_in=gs)
+            assert (q.codes[sel].cpu().numpy() == want.codes).all()
+            assert (q.scales[sel].cpu().numpy() == want.scales).all()
+        del q
+    del x
+    torch.cuda.empty_cache()
+
+
 def test_quantize_is_deterministic():
     xb = wl.activation_with_outliers(512, 3072, 1, 0)
     x = dev_bf16(xb)
