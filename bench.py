@@ -261,16 +261,19 @@ def measure_rows(nv, wl, torch, np):
                                       "frac_hbm": round(B_PER_ELEM * Mt * F / ms / 1e6 / PEAK_HBM_GBS, 4)}
     del out, X, dY, W
 
-    def gtime(a, w, name):
-        y = torch.empty((a.rows, w.rows), dtype=torch.float32, device=dev)
-        ms = _time_op(nv, torch, nv.OP_GEMM, lambda: nv.nvfp4_gemm(a, w, nv.OUT_F32, Y=y), 5, warm=1)
+    def gtime(a, w, name, out_dtype=nv.OUT_F32):
+        y = torch.empty((a.rows, w.rows), dtype=torch.float32 if out_dtype == nv.OUT_F32 else torch.bfloat16, device=dev)
+        ms = _time_op(nv, torch, nv.OP_GEMM, lambda: nv.nvfp4_gemm(a, w, out_dtype, Y=y), 10, warm=3)
         fl = 2.0 * a.rows * w.rows * a.K
         res[name] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 1),
                      "frac_mfma": round(fl / ms / 1e9 / PEAK_MFMA_F16_TFLOPS, 4)}
 
+    # fp32 outputs (the accumulator as it is); activations and their gradients also as bf16
     gtime(qX, qW, "fprop_17600x14336x3072")
     gtime(qdY, qWt, "dgrad_17600x3072x14336")
     gtime(qdYt, qXt, "wgrad_14336x3072x17600")
+    gtime(qX, qW, "fprop_17600x14336x3072_bf16_out", nv.OUT_BF16)
+    gtime(qdY, qWt, "dgrad_17600x3072x14336_bf16_out", nv.OUT_BF16)
     return res
 
 
