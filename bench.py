@@ -30,6 +30,9 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-rows", action="store_true", help="skip the per-row extras (KV, training triplet)")
+    ap.add_argument("--rows-only", default=None, metavar="SECTIONS",
+                    help="run only the per-row measurements of the given sections (comma list of kv, lora, train) "
+                         "and print them as one JSON line: for per-kernel profiles of the streaming rows")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling FETCH_SIZE / WRITE_SIZE counters)")
@@ -44,6 +47,10 @@ def main():
 
     torch.cuda.set_device(0)
     dev = "cuda"
+    if args.rows_only:
+        rows = measure_rows(nv, wl, torch, np, tuple(args.rows_only.split(",")))
+        print(json.dumps({"rows_only": args.rows_only, "data": "synthetic", "rows": rows}))
+        return
     M, D, F = wl.TOKENS_INFER, wl.D_MODEL, wl.D_FFN
     cfg = wl.config3()
     A = nv.bf16_from_bits(cfg["A"], dev)
@@ -160,15 +167,26 @@ def _time_op(nv, torch, op_id, fn, iters, warm=2):
     return ms / max(n, 1)
 
 
-def measure_rows(nv, wl, torch, np):
+def measure_rows(nv, wl, torch, np, sections=("kv", "lora", "train")):
     """One measurement per remaining row of the path, at the sizes of the KV and training configs."""
     dev = "cuda"
     res = {}
+    ws = torch.empty(4096, dtype=torch.uint8, device=dev)
+    if "kv" in sections:
+        _rows_kv(nv, wl, torch, res, ws)
+    if "lora" in sections:
+        _rows_lora(nv, wl, torch, res)
+    if "train" in sections:
+        _rows_train(nv, wl, torch, res, ws)
+    return res
+
+
+def _rows_kv(nv, wl, torch, res, ws):
+    dev = "cuda"
     # --- KV cache: K [18480, 24, 128] -------------------------------------------------------
     T, H, d = wl.KV_TOKENS, wl.KV_HEADS, wl.KV_DIM
     kv = nv.bf16_from_bits(wl.kv_tensor(T, H, d, 3, 0), dev)
     q = nv.NVFP4Tensor(T * H, d, dev)
-    ws = torch.empty(4096, dtype=torch.uint8, device=dev)
     back = torch.empty_like(kv)
     n = T * H * d
     ms = _time_op(nv, torch, nv.OP_KV_QUANT, lambda: nv.nvfp4_kv_quant(kv, out=q, workspace=ws), 20)
@@ -203,6 +221,10 @@ def measure_rows(nv, wl, torch, np):
     res["kv_dequant_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
                                       "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
     del kv, back, q
+
+
+def _rows_lora(nv, wl, torch, res):
+    dev = "cuda"
     # --- LoRA side branch on the DiT projection (rank 128, alpha 128): bf16 down projection, then the
     # quantized GEMM with the low-rank update fused in, against the plain quantized GEMM ------------
     c2 = wl.config2()
@@ -223,6 +245,10 @@ def measure_rows(nv, wl, torch, np):
     res["gemm_plain_3520x3072x3072"] = {"ms": round(ms, 4), "tflops": round(fl / ms / 1e9, 1),
                                         "frac_mfma": round(fl / ms / 1e9 / PEAK_MFMA_F16_TFLOPS, 4)}
     del c2, Xi, qXi, qWi, La, Lb, Tl, Yl
+
+
+def _rows_train(nv, wl, torch, res, ws):
+    dev = "cuda"
     # --- training triplet: X[17600,3072], W[14336,3072], dY[17600,14336] ---------------------
     c5 = wl.config5()
     Mt, D, F = wl.TOKENS_TRAIN, wl.D_MODEL, wl.D_FFN
@@ -274,7 +300,6 @@ def measure_rows(nv, wl, torch, np):
     gtime(qdYt, qXt, "wgrad_14336x3072x17600")
     gtime(qX, qW, "fprop_17600x14336x3072_bf16_out", nv.OUT_BF16)
     gtime(qdY, qWt, "dgrad_17600x3072x14336_bf16_out", nv.OUT_BF16)
-    return res
 
 
 def cpu_baseline(cfg, wl, np):
