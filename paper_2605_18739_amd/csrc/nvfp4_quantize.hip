@@ -3,6 +3,8 @@
 // streaming kernels bound by HBM: 2 B read + 0.5625 B written per element
 // (quantize), 0.5625 B read + 2 B written (KV reconstruction).
 #include "nvfp4_device.h"
+
+#include <algorithm>
 #include "nvfp4_kernels.h"
 
 #ifndef NVFP4_Q_PLAIN_STORE
@@ -28,17 +30,20 @@ namespace nvfp4 {
 // x is [R, C] with row stride ld; C % 8 == 0.  partial[blockIdx.x] is written
 // by every workgroup (no atomics, nothing to clear).
 // --------------------------------------------------------------------------
+// 1024 threads per workgroup: one workgroup per compute unit keeps sixteen waves of loads in
+// flight and leaves at most 256 partial maxima for every pass-2 workgroup to reduce again.
+constexpr int kAmaxThreads = 1024, kAmaxGrid = 256;
 template <bool CONTIG>
-__global__ __launch_bounds__(256) void amax_partial_kernel(const uint16_t *__restrict__ x, int64_t R,
-                                                           int64_t C, int64_t ld,
-                                                           uint32_t *__restrict__ partial)
+__global__ __launch_bounds__(kAmaxThreads) void amax_partial_kernel(const uint16_t *__restrict__ x, int64_t R,
+                                                                    int64_t C, int64_t ld,
+                                                                    uint32_t *__restrict__ partial)
 {
-    __shared__ uint32_t wave_max[4];
+    __shared__ uint32_t wave_max[kAmaxThreads / 64];
     const int64_t vec_per_row = C >> 3;
     const int64_t nvec = R * vec_per_row;
-    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int64_t stride = (int64_t)gridDim.x * kAmaxThreads;
     uint32_t acc = 0;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += stride) {
+    for (int64_t i = (int64_t)blockIdx.x * kAmaxThreads + threadIdx.x; i < nvec; i += stride) {
         int64_t off;
         if (CONTIG) off = i << 3;
         else {
@@ -54,8 +59,11 @@ __global__ __launch_bounds__(256) void amax_partial_kernel(const uint16_t *__res
     uint32_t m = wave_max_u32(pk_hmax_u16(acc));
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
     __syncthreads();
-    if (threadIdx.x == 0)
-        partial[blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    if (threadIdx.x == 0) {
+        uint32_t all = 0;
+        for (int w = 0; w < kAmaxThreads / 64; ++w) all = max(all, wave_max[w]);
+        partial[blockIdx.x] = all;
+    }
 }
 
 // --------------------------------------------------------------------------
@@ -566,10 +574,11 @@ static int grid_for(int64_t work_items, int max_grid)
 hipError_t launch_amax(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t *partial,
                        int *n_partial, hipStream_t s)
 {
-    int grid = grid_for(R * (C >> 3), kMaxPartials);
+    const int64_t want = (R * (C >> 3) + kAmaxThreads - 1) / kAmaxThreads;
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(want, kAmaxGrid));
     *n_partial = grid;
-    if (ld == C) amax_partial_kernel<true><<<grid, 256, 0, s>>>(x, R, C, ld, partial);
-    else amax_partial_kernel<false><<<grid, 256, 0, s>>>(x, R, C, ld, partial);
+    if (ld == C) amax_partial_kernel<true><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
+    else amax_partial_kernel<false><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
     return hipGetLastError();
 }
 
