@@ -72,19 +72,19 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_partial_kernel(const uint16
 // smoothed values RN_bf16(x - mean).  One lane per 16-element block; the d/16 lanes of a row
 // are neighbours (d/16 a power of two up to 64) and add their fp64 partial sums by shuffles.
 // --------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void amax_smooth_kernel(const uint16_t *__restrict__ x, int64_t rows,
+__global__ __launch_bounds__(kAmaxThreads) void amax_smooth_kernel(const uint16_t *__restrict__ x, int64_t rows,
                                                           int log2_nb_row, uint16_t *__restrict__ mean_out,
                                                           uint32_t *__restrict__ partial)
 {
-    __shared__ uint32_t wave_max[4];
+    __shared__ uint32_t wave_max[kAmaxThreads / 64];
     const int nb_row = 1 << log2_nb_row;                        // blocks per row, d = 16 nb_row
     const double inv_d = 1.0 / (double)(16 << log2_nb_row);    // a power of two: the quotient below is exact
     const int64_t nblk = rows << log2_nb_row;
-    const int64_t stride = (int64_t)gridDim.x * 256;           // a multiple of nb_row
+    const int64_t stride = (int64_t)gridDim.x * kAmaxThreads;  // a multiple of nb_row
     uint32_t acc = 0;
     // the trip count is the same for all lanes of a wave up to the tail, where lanes past the end
     // contribute zeros to the shuffles (their rows do not exist)
-    for (int64_t g0 = (int64_t)blockIdx.x * 256; g0 < nblk; g0 += stride) {
+    for (int64_t g0 = (int64_t)blockIdx.x * kAmaxThreads; g0 < nblk; g0 += stride) {
         const int64_t g = g0 + threadIdx.x;
         const bool live = g < nblk;
         uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -112,8 +112,11 @@ __global__ __launch_bounds__(256) void amax_smooth_kernel(const uint16_t *__rest
     uint32_t m = wave_max_u32(pk_hmax_u16(acc));
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
     __syncthreads();
-    if (threadIdx.x == 0)
-        partial[blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    if (threadIdx.x == 0) {
+        uint32_t all = 0;
+        for (int w = 0; w < kAmaxThreads / 64; ++w) all = max(all, wave_max[w]);
+        partial[blockIdx.x] = all;
+    }
 }
 
 // Every workgroup of a pass-2 kernel reduces the partials again (a few KB out
@@ -665,9 +668,10 @@ hipError_t launch_quantize_rows_slabs(const uint16_t *x, int64_t T, int64_t H, i
 hipError_t launch_amax_smooth(const uint16_t *x, int64_t rows, int d, uint16_t *mean_out, uint32_t *partial,
                               int *n_partial, hipStream_t s)
 {
-    int grid = grid_for(rows * (d >> 4), kMaxPartials);
+    const int64_t want = (rows * (d >> 4) + kAmaxThreads - 1) / kAmaxThreads;
+    const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(want, kAmaxGrid));
     *n_partial = grid;
-    amax_smooth_kernel<<<grid, 256, 0, s>>>(x, rows, __builtin_ctz((unsigned)(d >> 4)), mean_out, partial);
+    amax_smooth_kernel<<<grid, kAmaxThreads, 0, s>>>(x, rows, __builtin_ctz((unsigned)(d >> 4)), mean_out, partial);
     return hipGetLastError();
 }
 
