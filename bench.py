@@ -135,7 +135,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": "dit_ffn_pair: A[3520,3072] -> W1[14336,3072] -> gelu_tanh -> requantize -> "
-                               "W2[3072,14336], W4A4 NVFP4, bf16 out (BASELINE configs[2])",
+                               "W2[3072,14336], W4A4 NVFP4, bf16 out (the DiT FFN pair configuration)",
                    "global_batch": M, "parallelism": "single-gpu"},
         "roofline": roofline, "kernels": kernels, "rows": rows, "cpu_baseline": cpu,
     }
