@@ -155,6 +155,9 @@ int nvfp4_quantize_2d(const void *w_bf16, int64_t R, int64_t C, int64_t ld,
  * stride ldy elements, fp32 (NVFP4_OUT_F32) or bf16 (NVFP4_OUT_BF16, the fp32
  * result rounded to nearest even).  dgrad and wgrad are this same call on
  * operands produced by nvfp4_quantize with the matching block_axis.
+ * K % 64 == 0 and N % 8 == 0 run on the tiled MFMA kernels at any M and N
+ * (operands of 2 GiB and more are cut into row chunks, one set of launches per
+ * chunk); other shapes (K % 16 == 0) run on a plain, much slower kernel.
  */
 int nvfp4_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y, int64_t ldy,
                int out_dtype, void *stream);

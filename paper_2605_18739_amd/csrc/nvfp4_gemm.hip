@@ -1147,13 +1147,30 @@ static LaunchPlan plan_gemm(int64_t M, int64_t N, int64_t K, bool big_only = fal
     return p;
 }
 
+// The tiled kernels address an operand through a 32-bit buffer offset and rely on the range
+// check to zero-fill rows past its end, so one launch sees at most max_operand_rows(K) rows of
+// A and of W; larger problems are cut into chunks of that many rows (pointer offsets only).
+static int64_t max_operand_rows(int64_t K) { return ((0x7FF00000LL - 1) / (K >> 1)) / 256 * 256; }
+
 static bool tiled_ok(int64_t M, int64_t N, int64_t K)
 {
-    // 32-bit buffer offsets and zero-fill of out-of-range rows need operands below 2 GiB
-    return K % BK == 0 && N % 8 == 0 && M * (K >> 1) < 0x7FF00000LL && N * (K >> 1) < 0x7FF00000LL;
+    (void)M;
+    return K % BK == 0 && N % 8 == 0 && max_operand_rows(K) >= 256;
 }
 
 bool gemm_is_tiled(int64_t M, int64_t N, int64_t K) { return tiled_ok(M, N, K); }
+
+// f(m_lo, m_hi, n_lo, n_hi, plan) for every chunk of the problem, in launch order
+template <class F>
+static void for_each_chunk(int64_t M, int64_t N, int64_t K, bool big_only, F &&f)
+{
+    const int64_t step = max_operand_rows(K);
+    for (int64_t m_lo = 0; m_lo < M; m_lo += step)
+        for (int64_t n_lo = 0; n_lo < N; n_lo += step) {
+            const int64_t m_hi = std::min(M, m_lo + step), n_hi = std::min(N, n_lo + step);
+            f(m_lo, m_hi, n_lo, n_hi, plan_gemm(m_hi - m_lo, n_hi - n_lo, K, big_only));
+        }
+}
 
 // "BMxBN:workgroups" per launch, separated by spaces ("generic" for the untiled fallback)
 int gemm_plan_text(int64_t M, int64_t N, int64_t K, char *text, size_t text_bytes)
@@ -1162,23 +1179,30 @@ int gemm_plan_text(int64_t M, int64_t N, int64_t K, char *text, size_t text_byte
         snprintf(text, text_bytes, "generic");
         return 1;
     }
-    const LaunchPlan p = plan_gemm(M, N, K);
     size_t used = 0;
-    for (int i = 0; i < p.n; ++i) {
-        const TileShape &t = kShapes[p.part[i].kind];
-        const int w = snprintf(text + used, used < text_bytes ? text_bytes - used : 0, "%s%dx%d:%lld", i ? " " : "", t.bm,
-                               t.bn, (long long)p.part[i].tiles);
-        if (w < 0 || used + (size_t)w >= text_bytes) return -1;
-        used += (size_t)w;
-    }
-    return p.n;
+    int launches = 0;
+    bool fits = true;
+    for_each_chunk(M, N, K, false, [&](int64_t, int64_t, int64_t, int64_t, const LaunchPlan &p) {
+        for (int i = 0; i < p.n && fits; ++i) {
+            const TileShape &t = kShapes[p.part[i].kind];
+            const int w = snprintf(text + used, used < text_bytes ? text_bytes - used : 0, "%s%dx%d:%lld",
+                                   launches ? " " : "", t.bm, t.bn, (long long)p.part[i].tiles);
+            if (w < 0 || used + (size_t)w >= text_bytes) fits = false;
+            else {
+                used += (size_t)w;
+                ++launches;
+            }
+        }
+    });
+    return fits ? launches : -1;
 }
 
 int gemm_workgroups(int64_t M, int64_t N, int64_t K)
 {
-    const LaunchPlan p = plan_gemm(M, N, K);
     int64_t n = 0;
-    for (int i = 0; i < p.n; ++i) n += p.part[i].tiles;
+    for_each_chunk(M, N, K, false, [&](int64_t, int64_t, int64_t, int64_t, const LaunchPlan &p) {
+        for (int i = 0; i < p.n; ++i) n += p.part[i].tiles;
+    });
     return (int)n;
 }
 
@@ -1209,46 +1233,50 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
         gemm_generic_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(g);
         return hipGetLastError();
     }
-    const LaunchPlan plan = plan_gemm(M, N, K, with_lora);
     // (the tiled fp32 output never carries an activation: nvfp4_gemm has none and the fused call emits bf16)
     const int out_kind = ep.q_scale ? kEpiQuant : (ep.out_dtype != 0 ? kEpiBF16 : kEpiF32);
     const int epi = out_kind | ((ep.act == 1 && out_kind != kEpiF32) ? kEpiGelu : 0);
     const int64_t kbytes = K >> 1, kblocks = K >> 4;
     const int64_t ysize = ep.out_dtype == 0 ? 4 : 2;
     int wg_total = 0;
-    for (int i = 0; i < plan.n; ++i) {
-        const SubLaunch &p = plan.part[i];
-        GemmArgs a = g;                              // the sub-rectangle [m_lo, m_hi) x [n_lo, n_hi) as a problem of its own
-        a.codesA = codesA + p.m_lo * kbytes;
-        a.scalesA = scalesA + p.m_lo * kblocks;
-        a.codesW = codesW + p.n_lo * kbytes;
-        a.scalesW = scalesW + p.n_lo * kblocks;
-        a.M = p.m_hi - p.m_lo;
-        a.N = p.n_hi - p.n_lo;
-        if (ep.Y) a.ep.Y = (uint8_t *)ep.Y + (p.m_lo * ep.ldy + p.n_lo) * ysize;
-        if (ep.q_codes) {
-            a.ep.q_codes = ep.q_codes + p.m_lo * (N >> 1) + (p.n_lo >> 1);
-            a.ep.q_scales = ep.q_scales + p.m_lo * (N >> 4) + (p.n_lo >> 4);
+    hipError_t err = hipSuccess;
+    for_each_chunk(M, N, K, with_lora, [&](int64_t cm, int64_t, int64_t cn, int64_t, const LaunchPlan &plan) {
+        for (int i = 0; i < plan.n && err == hipSuccess; ++i) {
+            const SubLaunch &p = plan.part[i];
+            const int64_t m_lo = cm + p.m_lo, n_lo = cn + p.n_lo;     // the sub-rectangle [m_lo, ..) x [n_lo, ..) as a problem of its own
+            GemmArgs a = g;
+            a.codesA = codesA + m_lo * kbytes;
+            a.scalesA = scalesA + m_lo * kblocks;
+            a.codesW = codesW + n_lo * kbytes;
+            a.scalesW = scalesW + n_lo * kblocks;
+            a.M = p.m_hi - p.m_lo;
+            a.N = p.n_hi - p.n_lo;
+            if (ep.Y) a.ep.Y = (uint8_t *)ep.Y + (m_lo * ep.ldy + n_lo) * ysize;
+            if (ep.q_codes) {
+                a.ep.q_codes = ep.q_codes + m_lo * (N >> 1) + (n_lo >> 1);
+                a.ep.q_scales = ep.q_scales + m_lo * (N >> 4) + (n_lo >> 4);
+            }
+            a.q_pitch = N;
+            a.partial_base = wg_total;
+            if (with_lora) {
+                a.lora_t = lora.t + m_lo * kLoraRank;
+                a.lora_b = lora.b + n_lo * kLoraRank;
+            }
+            hipError_t e;
+            switch (epi | (with_lora ? kEpiLora : 0)) {
+            case kEpiF32 | kEpiLora: e = launch_kind<kEpiF32 | kEpiLora>(p.kind, a, p.tiles, s); break;
+            case kEpiBF16 | kEpiLora: e = launch_kind<kEpiBF16 | kEpiLora>(p.kind, a, p.tiles, s); break;
+            case kEpiF32: e = launch_kind<kEpiF32>(p.kind, a, p.tiles, s); break;
+            case kEpiBF16: e = launch_kind<kEpiBF16>(p.kind, a, p.tiles, s); break;
+            case kEpiBF16 | kEpiGelu: e = launch_kind<kEpiBF16 | kEpiGelu>(p.kind, a, p.tiles, s); break;
+            case kEpiQuant: e = launch_kind<kEpiQuant>(p.kind, a, p.tiles, s); break;
+            default: e = launch_kind<kEpiQuant | kEpiGelu>(p.kind, a, p.tiles, s); break;
+            }
+            err = e;
+            wg_total += (int)p.tiles;
         }
-        a.q_pitch = N;
-        a.partial_base = wg_total;
-        if (with_lora) {
-            a.lora_t = lora.t + p.m_lo * kLoraRank;
-            a.lora_b = lora.b + p.n_lo * kLoraRank;
-        }
-        hipError_t e;
-        switch (epi | (with_lora ? kEpiLora : 0)) {
-        case kEpiF32 | kEpiLora: e = launch_kind<kEpiF32 | kEpiLora>(p.kind, a, p.tiles, s); break;
-        case kEpiBF16 | kEpiLora: e = launch_kind<kEpiBF16 | kEpiLora>(p.kind, a, p.tiles, s); break;
-        case kEpiF32: e = launch_kind<kEpiF32>(p.kind, a, p.tiles, s); break;
-        case kEpiBF16: e = launch_kind<kEpiBF16>(p.kind, a, p.tiles, s); break;
-        case kEpiBF16 | kEpiGelu: e = launch_kind<kEpiBF16 | kEpiGelu>(p.kind, a, p.tiles, s); break;
-        case kEpiQuant: e = launch_kind<kEpiQuant>(p.kind, a, p.tiles, s); break;
-        default: e = launch_kind<kEpiQuant | kEpiGelu>(p.kind, a, p.tiles, s); break;
-        }
-        if (e != hipSuccess) return e;
-        wg_total += (int)p.tiles;
-    }
+    });
+    if (err != hipSuccess) return err;
     if (n_wg) *n_wg = wg_total;
     return hipSuccess;
 }

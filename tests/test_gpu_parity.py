@@ -235,6 +235,49 @@ def test_gemm_random_shapes(oracle):
     assert [len(nv.nvfp4_gemm_plan(*shp)) for shp in shapes[-3:]] == [2, 2, 3]
 
 
+@pytest.mark.parametrize("M,N", [(300100, 264), (72, 300104)])
+def test_gemm_operand_of_2_gib(oracle, M, N):
+    """An operand of more than 2 GiB of codes (K = 14336: about 299 thousand rows per launch) is cut
+    into row chunks; rows on both sides of the cut, the first and last rows and seeded ones are
+    checked against the oracle.  The NVFP4 operands are drawn on the device (any code and any
+    normal scale byte is a valid tensor)."""
+    K = 14336
+    say(f"[gemm] {M}x{N}x{K}: {nv.nvfp4_gemm_plan(M, N, K)}")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(M + N)
+
+    def draw(rows):
+        codes = torch.randint(0, 256, (rows, K // 2), dtype=torch.uint8, device="cuda", generator=gen)
+        scales = torch.randint(40, 72, (rows, K // 16), dtype=torch.uint8, device="cuda", generator=gen)
+        gs = torch.tensor([2.0 ** -9], dtype=torch.float32, device="cuda")
+        return nv.NVFP4Tensor(rows, K, "cuda", codes, scales, gs)
+
+    A, W = draw(M), draw(N)
+    assert max(M, N) * (K // 2) > 2 ** 31
+    y = nv.nvfp4_gemm(A, W, nv.OUT_F32)
+    torch.cuda.synchronize()
+    g = np.random.default_rng(M)
+    cut = 299264                                   # rows per launch at this K
+    big = max(M, N)
+    pick = np.unique(np.concatenate([[0, 1, cut - 1, cut, cut + 1, big - 1], g.integers(0, big, 6)]))
+    sel = torch.as_tensor(pick, device="cuda")
+
+    def host(t, idx=None):
+        c, sc = (t.codes, t.scales) if idx is None else (t.codes[idx], t.scales[idx])
+        return oracle.Q(c.cpu().numpy(), sc.cpu().numpy(), np.float32(2.0 ** -9))
+
+    if M > N:
+        Y, S = oracle.gemm(host(A, sel), host(W))
+        got = y[sel].cpu().numpy()
+    else:
+        Y, S = oracle.gemm(host(A), host(W, sel))
+        got = y[:, sel].cpu().numpy()
+    fro, worst = assert_gemm_close(got, Y, S, f"chunked {M}x{N}x{K}")
+    say(f"        rel fro {fro:.2e}  worst err/S {worst:.2e}")
+    del A, W, y
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("M,N,K", [(5, 8, 16), (7, 12, 48), (9, 4, 80)])
 def test_gemm_small_k_untiled(oracle, M, N, K):
     g = np.random.default_rng(M * N * K)
