@@ -57,6 +57,15 @@ struct Timed {
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 constexpr size_t kPartialBytes = (size_t)kMaxPartials * sizeof(uint32_t);
 
+// Room for one partial maximum per workgroup of the fused GEMM, whatever its launch plan: no
+// more than one workgroup per 64 x 64 outputs, plus one extra tile row / column per row chunk
+// (chunks are at least 256 rows).
+size_t fused_partial_bytes(int64_t M, int64_t N)
+{
+    const int64_t tm = (M + 63) / 64 + (M + 255) / 256, tn = (N + 63) / 64 + (N + 255) / 256;
+    return align_up((size_t)std::max<int64_t>(kMaxPartials, tm * tn) * 4, 256);
+}
+
 int quantize_impl(const void *x, int64_t R, int64_t C, int64_t ld, int block_axis,
                   const float *gs_in, nvfp4_tensor *out, void *ws, size_t ws_bytes, hipStream_t s,
                   bool scale_search = false)
@@ -353,10 +362,11 @@ int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
     if (h_bf16_opt && !aligned16(h_bf16_opt)) return NVFP4_ERR_ALIGN;
     const bool tiled = gemm_is_tiled(M, N, A->K);
     const bool single_pass = global_scale_in && tiled;          // the epilogue quantizes, H is not staged
-    const size_t part_bytes = align_up((size_t)std::max<int64_t>(kMaxPartials, ((M + 127) / 128) * ((N + 127) / 128)) * 4, 256);
+    const size_t part_bytes = fused_partial_bytes(M, N);
     const size_t need = part_bytes + ((h_bf16_opt || single_pass) ? 0 : align_up((size_t)M * (size_t)N * 2, 256));
     if (!workspace || workspace_bytes < need) return NVFP4_ERR_WORKSPACE;
     if (!aligned16(workspace)) return NVFP4_ERR_ALIGN;
+    if (tiled && (size_t)gemm_workgroups(M, N, A->K) * 4 > part_bytes) return NVFP4_ERR_WORKSPACE;   // (cannot happen: see fused_partial_bytes)
 
     std::lock_guard<std::mutex> lk(g_mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -420,9 +430,9 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
         return lora_down_workspace_bytes(a, b);
     case NVFP4_OP_GEMM_ACT_QUANT: {   // a = M, b = N, c: bit 0 = caller supplies H, bit 1 = caller supplies the scale
         if (a <= 0 || b <= 0) return 0;
-        // the GEMM tile (hence the number of per-workgroup maxima) depends on K, which this query
-        // does not know: reserve for the smallest tile
-        size_t part = align_up((size_t)std::max<int64_t>(kMaxPartials, ((a + 127) / 128) * ((b + 127) / 128)) * 4, 256);
+        // the GEMM tiles (hence the number of per-workgroup maxima) depend on K, which this query
+        // does not know: reserve for the smallest tile everywhere
+        size_t part = fused_partial_bytes(a, b);
         // with a given scale the fused epilogue needs no staging of H -- unless the shape falls back
         // to the untiled kernel (K % 64 != 0 or N % 8 != 0), which this query cannot see either:
         // only skip the H area when N is a multiple of 16 and leave K to the caller's contract

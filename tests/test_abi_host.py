@@ -194,7 +194,11 @@ def test_gemm_launch_plan():
                 tm, tn = (int(v) for v in tile.split("x"))
                 assert wgs == -(-rm // tm) * -(-rn // tn)
         seen.update(t for t, _ in plan)
+        # the fused call keeps one partial maximum per workgroup in its workspace
+        assert nv.nvfp4_workspace_bytes(nv.OP_GEMM_ACT_QUANT, M, N, 1) >= 4 * sum(w for _, w in plan)
     assert seen == {"256x256", "256x192", "128x128", "64x64"}
+    for M, N, K in [(300100, 264, 14336), (72, 300104, 14336), (1, 8, 64), (65, 72, 64)]:
+        assert nv.nvfp4_workspace_bytes(nv.OP_GEMM_ACT_QUANT, M, N, 1) >= 4 * sum(w for _, w in nv.nvfp4_gemm_plan(M, N, K))
     text = ctypes.create_string_buffer(4)
     assert nv.lib().nvfp4_gemm_plan(3520, 14336, 3072, text, 4) == -4    # text does not fit
     assert nv.lib().nvfp4_gemm_plan(3520, 14336, 3072, None, 64) == -1
