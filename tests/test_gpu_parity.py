@@ -95,6 +95,48 @@ def test_quantize_transposed(oracle, R, C):
     assert_q_equal(gq, oq, f"transposed {R}x{C}")
 
 
+def test_quantize_random_sweep(oracle):
+    """Seeded sweep over shapes, leading dimensions, value distributions (Gaussian at many
+    magnitudes, coarse grids full of rounding ties, heavy tails, mostly-zero tensors), both block
+    axes, the plain rule and the scale search: every byte equals the oracle's."""
+    g = np.random.default_rng(4242)
+    for case in range(48):
+        axis = int(g.integers(0, 2))
+        if axis == 0:
+            R, C = int(g.integers(1, 500)), 16 * int(g.integers(1, 66))
+        else:
+            R, C = 16 * int(g.integers(1, 40)), 8 * int(g.integers(1, 130))
+        kind = case % 6
+        if kind == 0:
+            x = g.standard_normal((R, C)) * 10.0 ** g.uniform(-6, 6)
+        elif kind == 1:                                       # a grid of 1/8 steps under a power-of-two tensor scale
+            x = g.integers(-42, 43, size=(R, C)) * 0.125
+            x.flat[0] = 5.25
+        elif kind == 2:                                       # heavy tails
+            x = g.standard_cauchy((R, C)).clip(-1e4, 1e4)
+        elif kind == 3:                                       # mostly zeros, signed zeros included
+            x = np.where(g.random((R, C)) < 0.9, 0.0, g.standard_normal((R, C)))
+            x = np.where(g.random((R, C)) < 0.05, -0.0, x)
+        elif kind == 4:                                       # channels of very different size
+            x = g.standard_normal((R, C)) * 2.0 ** g.integers(-12, 13, size=(1, C))
+        else:                                                 # values that are exactly representable
+            x = g.choice([0.5, 1, 1.5, 2, 3, 4, 6], size=(R, C)) * g.choice([-1.0, 1.0], size=(R, C)) * 2.0 ** g.integers(-3, 4, size=(R, 1))
+        pad = 8 * int(g.integers(0, 3))
+        xb = wl.to_bf16_bits(np.asarray(x, np.float32))
+        full = np.zeros((R, C + pad), np.uint16)
+        full[:, :C] = xb
+        view = dev_bf16(full)[:, :C]
+        search = axis == 0 and case % 2 == 1
+        say(f"[quantize] sweep {case}: {R}x{C} ld={C + pad} axis={axis} kind={kind} search={search}")
+        if search:
+            got = nv.nvfp4_quantize_4over6(view)
+            want = oracle.quantize(xb, four_over_six=True)
+        else:
+            got = nv.nvfp4_quantize(view, block_axis=axis)
+            want = oracle.quantize(xb, block_axis=axis)
+        assert_q_equal(got, want, f"sweep {case}")
+
+
 def test_quantize_more_than_2_to_31_elements(oracle):
     """A tensor past 2^31 elements (4.3 GB of bf16): every index in the kernels is 64-bit.  The tensor
     is drawn on the device; rows around the 2^31-element mark, the first and last rows and seeded
@@ -583,6 +625,37 @@ def test_kv_quant_k_smoothing(oracle, T, H, d):
     assert_q_equal(got_q, want_q, "smoothed keys")
     back = nv.nvfp4_kv_dequant_gather([(got_q, got_mean, T)], H, d)
     assert (nv.bits_from_bf16(back).reshape(T * H, d) == oracle.dequant_bf16(want_q, want_mean)).all()
+
+
+def test_kv_cache_random_sweep(oracle):
+    """Seeded sweep over cache shapes and value distributions: plain values, the scale search, the
+    smoothed keys and their reconstruction, all byte for byte against the oracle."""
+    g = np.random.default_rng(777)
+    for case in range(24):
+        d = 16 * 2 ** int(g.integers(0, 7))                  # 16 .. 1024 (the smoothed path needs d / 16 a power of two)
+        T, H = int(g.integers(1, 60)), int(g.integers(1, 9))
+        kind = case % 4
+        x = g.standard_normal((T * H, d))
+        if kind == 0:
+            x = x * g.uniform(0.5, 4, size=(T * H, 1)) + g.uniform(-8, 8, size=(T * H, 1))
+        elif kind == 1:                                       # offsets that dwarf the signal
+            x = x * 2.0 ** -6 + g.choice([-96.0, 0.75, 40.0], size=(T * H, 1))
+        elif kind == 2:                                       # grid values: ties in the mean and in the codes
+            x = g.integers(-24, 25, size=(T * H, d)) * 0.25
+        else:                                                 # sparse rows, some all zero
+            x = np.where(g.random((T * H, d)) < 0.8, 0.0, x)
+            x[:: 5] = 0.0
+        kb = wl.to_bf16_bits(np.asarray(x, np.float32))
+        say(f"[kv] sweep {case}: {T}x{H}x{d} kind={kind}")
+        kv = dev_bf16(kb).reshape(T, H, d)
+        assert_q_equal(nv.nvfp4_kv_quant(kv), oracle.quantize(kb), f"kv sweep {case} plain")
+        assert_q_equal(nv.nvfp4_kv_quant_4over6(kv), oracle.quantize(kb, four_over_six=True), f"kv sweep {case} search")
+        want_mean, want_q = _oracle_k_path(oracle, kb)
+        got_q, got_mean = nv.nvfp4_kv_quant_k(kv)
+        assert (nv.bits_from_bf16(got_mean) == want_mean).all(), f"kv sweep {case} means"
+        assert_q_equal(got_q, want_q, f"kv sweep {case} smoothed")
+        back = nv.nvfp4_kv_dequant_gather([(got_q, got_mean, T)], H, d)
+        assert (nv.bits_from_bf16(back).reshape(T * H, d) == oracle.dequant_bf16(want_q, want_mean)).all()
 
 
 def test_kv_quant_k_degenerate_rows(oracle):
