@@ -1036,12 +1036,15 @@ static hipError_t launch_tiled(const GemmArgs &g, int64_t tiles, hipStream_t s)
 {
     constexpr int smem_main = 2 * (BM + BN) * ROW_BYTES, smem_epi = 4 * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
-    static bool attr_set = false;
-    if (!attr_set) {
+    // the dynamic LDS limit is raised once per kernel variant and device
+    static uint64_t attr_set = 0;
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (((attr_set >> (dev & 63)) & 1u) == 0) {
         hipError_t e = hipFuncSetAttribute((const void *)gemm_ldsf16_kernel<BM, BN, EPI>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set |= 1ull << (dev & 63);
     }
     GemmArgs a = g;
     a.n_tiles_n = (int)((g.N + BN - 1) / BN);
@@ -1056,12 +1059,14 @@ static hipError_t launch_regdq(const GemmArgs &g, int64_t tiles, hipStream_t s)
     constexpr int NW = kRegdqWaves;
     constexpr int smem_main = kCodeStages * (BM + BN) * 64 + 2 * (BM + BN) * 16, smem_epi = NW * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static uint64_t attr_set = 0;                    // per kernel variant and device, as above
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (((attr_set >> (dev & 63)) & 1u) == 0) {
         hipError_t e = hipFuncSetAttribute((const void *)gemm_regdq_kernel<BM, BN, EPI, NW>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set |= 1ull << (dev & 63);
     }
     GemmArgs a = g;
     a.n_tiles_n = (int)((g.N + BN - 1) / BN);
