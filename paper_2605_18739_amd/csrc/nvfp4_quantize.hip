@@ -162,15 +162,12 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
                                                             int heads = 0, int slab_heads = 0, int row_shift = 0)
 {
     __shared__ uint32_t lds4[4];
-    const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
-    const float inv_6sg = 1.0f / (6.0f * sg);
-    const float inv_4sg = 1.0f / (4.0f * sg);
     const int64_t nb_row = C >> 4;
     const int64_t nblk = R * nb_row;
     const int64_t stride = (int64_t)gridDim.x * 256;
     constexpr int U = NVFP4_Q_UNROLL;              // blocks in flight per lane
-    for (int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x; g0 < nblk; g0 += stride * U) {
-        uint4v v0[U], v1[U];
+    uint4v v0[U], v1[U];
+    auto fetch = [&](int64_t g0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t g = g0 + u * stride;
@@ -186,6 +183,16 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
                 v1[u] = __builtin_nontemporal_load(p + 1);
             }
         }
+    };
+    // the first loads do not depend on the tensor scale: they are in flight while the workgroup
+    // reduces the partial maxima
+    const int64_t first = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    fetch(first);
+    const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
+    const float inv_6sg = 1.0f / (6.0f * sg);
+    const float inv_4sg = 1.0f / (4.0f * sg);
+    for (int64_t g0 = first; g0 < nblk; g0 += stride * U) {
+        if (g0 != first) fetch(g0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t g = g0 + u * stride;
