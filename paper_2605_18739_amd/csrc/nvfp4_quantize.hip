@@ -298,17 +298,20 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__re
     __shared__ uint32_t lds4[4];
     __shared__ uint2v lds_codes[kTC][kTR / 16 + 1];     // [column][row block], padded
     __shared__ uint8_t lds_scales[kTC][kTR / 16];
-    const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
-    const float inv_6sg = 1.0f / (6.0f * sg);
     const int cg = threadIdx.x & 31, rb = threadIdx.x >> 5;
     const int64_t r0 = (int64_t)blockIdx.y * kTR, c0 = (int64_t)blockIdx.x * kTC;
     const int64_t r = r0 + rb * 16, c = c0 + cg * 8;
     const bool live = (r < R) && (c < C);      // R % 16 == 0 and C % 8 == 0: whole blocks only
+    // the loads do not depend on the tensor scale: they are in flight while the partial maxima are reduced
+    uint4v v[16];
     if (live) {
-        uint4v v[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i)
             v[i] = __builtin_nontemporal_load((const uint4v *)(x + (r + i) * ld + c));
+    }
+    const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
+    const float inv_6sg = 1.0f / (6.0f * sg);
+    if (live) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {      // column c + j: element j of every loaded vector
             uint32_t w[8];
