@@ -362,23 +362,29 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint16_t *__r
                                                              float *__restrict__ gs_out_t)
 {
     __shared__ uint32_t lds4[4];
+    const int64_t I = (int64_t)blockIdx.y * 16 + (threadIdx.x & 15), J = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int64_t tr = R >> 4, tc = C >> 4;
+    const bool live = I < tr && J < tc;
+    // the tile is loaded (and its maximum taken) while the partial maxima of the tensor are reduced
+    uint32_t w[16][8];
+    uint32_t acc = 0;
+    if (live) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint4v *p = (const uint4v *)(x + (16 * I + i) * ld + 16 * J);
+            const uint4v v0 = __builtin_nontemporal_load(p), v1 = __builtin_nontemporal_load(p + 1);
+            w[i][0] = v0.x; w[i][1] = v0.y; w[i][2] = v0.z; w[i][3] = v0.w;
+            w[i][4] = v1.x; w[i][5] = v1.y; w[i][6] = v1.z; w[i][7] = v1.w;
+        }
+    }
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
     if (gs_out_t && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *gs_out_t = sg;
     const float inv_6sg = 1.0f / (6.0f * sg);
-    const int64_t I = (int64_t)blockIdx.y * 16 + (threadIdx.x & 15), J = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-    const int64_t tr = R >> 4, tc = C >> 4;
-    if (I >= tr || J >= tc) return;
-    uint32_t w[16][8];
-    uint32_t acc = 0;
+    if (!live) return;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const uint4v *p = (const uint4v *)(x + (16 * I + i) * ld + 16 * J);
-        const uint4v v0 = __builtin_nontemporal_load(p), v1 = __builtin_nontemporal_load(p + 1);
-        w[i][0] = v0.x; w[i][1] = v0.y; w[i][2] = v0.z; w[i][3] = v0.w;
-        w[i][4] = v1.x; w[i][5] = v1.y; w[i][6] = v1.z; w[i][7] = v1.w;
+    for (int i = 0; i < 16; ++i)
 #pragma unroll
         for (int k = 0; k < 8; ++k) acc = pk_absmax_u16(acc, w[i][k]);
-    }
     const float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
     const uint32_t sbyte = block_scale_exact(bmax, sg, inv_6sg);
     const float sb = e4m3_to_f32(sbyte);
