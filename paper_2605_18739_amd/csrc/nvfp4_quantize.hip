@@ -151,7 +151,8 @@ __device__ __forceinline__ float resolve_global_scale(const float *gs_in, const 
 // (what the pre-attention all-to-all of sequence-parallel inference sends to each peer).
 // --------------------------------------------------------------------------
 template <bool CONTIG, bool SEARCH = false, bool SMOOTH = false>
-__global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4)))   // at most 128 registers: four waves per SIMD
+void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
                                                             int64_t C, int64_t ld,
                                                             const float *__restrict__ gs_in,
                                                             const uint32_t *__restrict__ partial,
@@ -185,10 +186,12 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t *__re
         }
     };
     // the first loads do not depend on the tensor scale: they are in flight while the workgroup
-    // reduces the partial maxima
+    // reduces the partial maxima (not in the scale-search variants: they are bound by VALU work,
+    // and the registers held across the reduction would cost them a wave of occupancy)
     const int64_t first = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    fetch(first);
+    if constexpr (!SEARCH) fetch(first);
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
+    if constexpr (SEARCH) fetch(first);
     const float inv_6sg = 1.0f / (6.0f * sg);
     const float inv_4sg = 1.0f / (4.0f * sg);
     for (int64_t g0 = first; g0 < nblk; g0 += stride * U) {
