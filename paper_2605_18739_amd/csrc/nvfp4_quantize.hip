@@ -523,6 +523,7 @@ struct GatherTable {
     int wg_start[kMaxKvChunks + 1];               // first workgroup of chunk c
     int n_chunks;
     int nb_row;                                    // blocks per row (d / 16)
+    int row_shift;                                 // log2(nb_row) when that is a power of two, else -1
 };
 
 __global__ __launch_bounds__(256) void dequant_gather_kernel(GatherTable t, uint16_t *__restrict__ out)
@@ -545,6 +546,7 @@ __global__ __launch_bounds__(256) void dequant_gather_kernel(GatherTable t, uint
     for (int it = 0; it < kGatherBlocksPerWg / (256 * U); ++it) {
         uint2v ccs[U];
         uint32_t sbs[U];
+        uint16_t mus[U];                                   // row means of smoothed chunks, fetched with the codes
         const int64_t g0 = first + it * (256 * U) + threadIdx.x;
         if (g0 >= nblk) break;
 #pragma unroll
@@ -553,6 +555,7 @@ __global__ __launch_bounds__(256) void dequant_gather_kernel(GatherTable t, uint
             if (g < nblk) {
                 ccs[u] = __builtin_nontemporal_load((const uint2v *)(codes + (g << 3)));
                 sbs[u] = scales[g] & 0x7Fu;
+                if (mean) mus[u] = mean[t.row_shift >= 0 ? (g >> t.row_shift) : (g / t.nb_row)];
             }
         }
 #pragma unroll
@@ -564,7 +567,7 @@ __global__ __launch_bounds__(256) void dequant_gather_kernel(GatherTable t, uint
             if (!mean) {
                 dequant_block_lookup(cc, table[sbs[u]], o);
             } else {
-                const double mu = (double)__uint_as_float((uint32_t)mean[g / t.nb_row] << 16);
+                const double mu = (double)__uint_as_float((uint32_t)mus[u] << 16);
                 const double den = (double)e4m3_to_f32(sbs[u]) * sg;                // exact
                 typedef float float2v __attribute__((ext_vector_type(2)));
 #define NVFP4_GATHER_PAIR(I, C, SEL)                                                              \
@@ -711,6 +714,7 @@ hipError_t launch_dequant_gather(const KvChunkDesc *chunks, int n_chunks, int64_
     GatherTable t{};
     t.n_chunks = n_chunks;
     t.nb_row = (int)(d >> 4);
+    t.row_shift = (t.nb_row & (t.nb_row - 1)) == 0 ? __builtin_ctz((unsigned)t.nb_row) : -1;
     int64_t blk = 0;
     int wg = 0;
     for (int c = 0; c < n_chunks; ++c) {
