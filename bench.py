@@ -285,6 +285,17 @@ def _rows_train(nv, wl, torch, res, ws):
     ms = _time_op(nv, torch, nv.OP_QUANTIZE, lambda: nv.nvfp4_quantize(dY, global_scale_in=gs, out=out, workspace=ws), 10)
     res["quantize_dY_given_scale"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * Mt * F / ms / 1e6, 1),
                                       "frac_hbm": round(B_PER_ELEM * Mt * F / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    # dY along both axes (dgrad needs it along N, wgrad along the tokens): the second call takes the first one's scale
+    o_c = nv.NVFP4Tensor(F, Mt, dev)
+
+    def both():
+        nv.nvfp4_quantize(dY, out=out, workspace=ws)
+        nv.nvfp4_quantize(dY, block_axis=1, global_scale_in=out.global_scale, out=o_c, workspace=ws)
+
+    ms = 2 * _time_op(nv, torch, nv.OP_QUANTIZE, both, 10)          # the timer averages over calls: two per pair
+    res["quantize_dY_both_axes_shared_scale"] = {"ms": round(ms, 4), "GBs": round((2 + 2 * 0.5625) * Mt * F / ms / 1e6, 1),
+                                                 "frac_hbm": round((2 + 2 * 0.5625) * Mt * F / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    del o_c
     del out, X, dY, W
 
     def gtime(a, w, name, out_dtype=nv.OUT_F32):

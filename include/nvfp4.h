@@ -85,7 +85,10 @@ enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2
  *               re-quantized along its other axis, emitted K-contiguous, as
  *               the backward GEMMs need it).
  * global_scale_in: device pointer to one float, or NULL.  NULL: the scale is
- *               derived from the tensor's amax (one extra pass over x).
+ *               derived from the tensor's amax (one extra pass over x).  A
+ *               tensor that is needed along both axes (every training operand
+ *               is) has one amax: pass the first call's out->global_scale to
+ *               the second call and its extra pass is saved.
  * out: rows/K must already describe the result; codes/scales/global_scale are
  *      written (global_scale receives the scale that was used).
  * workspace: nvfp4_workspace_bytes(NVFP4_OP_QUANTIZE, R, C, 0) bytes; contents
