@@ -42,6 +42,9 @@ def main():
 
     import numpy as np
     import torch
+    from paper_2605_18739_amd import build as hip_build
+    if not os.path.exists(hip_build.LIB):           # the library built in-tree is used as it is; compiled only when there is none
+        hip_build.build(verbose=False)
     import paper_2605_18739_amd as nv
     from paper_2605_18739_amd import workloads as wl
 
