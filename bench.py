@@ -223,7 +223,16 @@ def _rows_kv(nv, wl, torch, res, ws):
     ms = _time_op(nv, torch, nv.OP_KV_DEQUANT, lambda: nv.nvfp4_kv_dequant(q, T, H, d, out=back), 20)
     res["kv_dequant_18480x24x128"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n / ms / 1e6, 1),
                                       "frac_hbm": round(B_PER_ELEM * n / ms / 1e6 / PEAK_HBM_GBS, 4)}
-    del kv, back, q
+    # send buffers of the NVFP4 all-to-all: one device's share of that window among 4 (L/P = 4620 tokens),
+    # cast along d and regrouped into 4 per-destination slabs of 6 heads
+    P = 4
+    Tl = T // P
+    q_a2a = nv.NVFP4Tensor(Tl * H, d, dev)
+    ms = _time_op(nv, torch, nv.OP_QUANTIZE_A2A, lambda: nv.nvfp4_quantize_for_all_to_all(kv[:Tl], P, out=q_a2a, workspace=ws), 20)
+    n_l = Tl * H * d
+    res[f"quantize_for_all_to_all_{Tl}x{H}x{d}_P{P}"] = {"ms": round(ms, 4), "GBs": round(B_PER_ELEM * n_l / ms / 1e6, 1),
+                                                        "frac_hbm": round(B_PER_ELEM * n_l / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    del kv, back, q, q_a2a
 
 
 def _rows_lora(nv, wl, torch, res):

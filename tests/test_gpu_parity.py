@@ -973,3 +973,34 @@ def test_full_size_training_triplet_config5(oracle):
         fro, worst = assert_gemm_close(y.cpu().numpy()[rows], Y, S, what)
         say(f"        rel fro {fro:.2e}  worst err/S {worst:.2e}")
         del y
+
+
+def test_full_size_training_recipe_config5(oracle):
+    """The later rows at the training layer's sizes, in the launch configurations the benchmark times:
+    2-D weight scaling with the transposed operand, the Hadamard-transformed weight-gradient operands,
+    the scale search on activations, and the all-to-all send buffers of one device's share of the
+    attention window.  Every byte against the oracle."""
+    cfg = wl.config5()
+    say("[config5] 2-D scaling of W and W^T")
+    want, want_t = oracle.quantize_2d(cfg["W"])
+    got, got_t = nv.nvfp4_quantize_2d(dev_bf16(cfg["W"]))
+    assert_q_equal(got, want, "W")
+    assert_q_equal(got_t, want_t, "W^T")
+    del got, got_t, want, want_t
+    mask = 0x6D21
+    for name in ("X", "dY"):
+        say(f"[config5] Hadamard transform + transposed quantizer of {name}")
+        want = oracle.quantize(oracle.rht_rows(cfg[name], mask), block_axis=1)
+        got = nv.nvfp4_quantize_rht(dev_bf16(cfg[name]), mask)
+        assert_q_equal(got, want, name)
+        del got, want
+    say("[config5] scale search on X")
+    assert_q_equal(nv.nvfp4_quantize_4over6(dev_bf16(cfg["X"])), oracle.quantize(cfg["X"], four_over_six=True), "X 4over6")
+    T, H, d, P = wl.KV_TOKENS // 4, wl.KV_HEADS, wl.KV_DIM, 4
+    say(f"[config4] all-to-all send buffers {T}x{H}x{d} over {P} peers")
+    xb = wl.config4()["K"][:T].reshape(T * H, d)
+    want = oracle.quantize(xb)
+    codes, scales, gs = host_q(nv.nvfp4_quantize_for_all_to_all(dev_bf16(xb).reshape(T, H, d), P))
+    perm = lambda a: a.reshape(T, P, H // P, -1).transpose(1, 0, 2, 3).reshape(T * H, -1)
+    assert gs.view(np.uint32) == np.float32(want.global_scale).view(np.uint32)
+    assert (codes == perm(want.codes)).all() and (scales == perm(want.scales)).all()
