@@ -101,7 +101,7 @@ def main():
     # bracket both, and the flops are those of the whole projection.
     up_ms = ms_up / max(n_up, 1)
     achieved = flops_gemm / (up_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "up projection 3520x14336x3072, f16 MFMA: gemm_regdq_kernel<256,256,bf16+gelu> (768 tiles) + gemm_ldsf16_kernel<64,64,bf16+gelu> (rest)",
+    roofline = {"bound": "mfma", "kernel": "up projection 3520x14336x3072, f16 MFMA: gemm_regdq_kernel<256,256,bf16+gelu> (768 tiles) + gemm_regdq_kernel<64,64,bf16+gelu> (rest)",
                 "achieved": round(achieved, 1), "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_MFMA_F16_TFLOPS, 4), "traffic": profile_traffic(),
                 "avg_launch_ms": round(up_ms, 4), "launches": n_up}

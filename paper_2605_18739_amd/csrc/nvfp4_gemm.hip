@@ -8,16 +8,13 @@
 // per instruction) and one packed f16 multiply by the block scale
 // (v_cvt_scalef32_pk_f16_fp8 turns the E4M3 byte into f16).
 //
-// Two kernels share the epilogue:
-//  - gemm_regdq_kernel (256x256 and 256x192 tiles): the operands stay 4-bit through
-//    LDS (filled by buffer loads that write LDS directly) and are expanded in
-//    registers in the shadow of the MFMAs that precede their use;
-//  - gemm_ldsf16_kernel (128x128 and 64x64 tiles, small problems and the leftover
-//    rectangle of a launch plan): codes are expanded once per workgroup and staged
-//    in LDS as f16 in an XOR-swizzled layout that both the 128-bit writes and the
-//    128-bit MFMA fragment reads hit without bank conflicts.
-// plan_gemm picks tile shapes and splits a problem into whole waves of large tiles
-// plus the leftover on small ones.
+// One tiled kernel, gemm_regdq_kernel, in four tile shapes (256x256 and 256x192 for the
+// bulk of a problem, 128x128 and 64x64 for small problems and the leftover rectangle of
+// a launch plan): the operands stay 4-bit through LDS (filled by buffer loads that write
+// LDS directly) and are expanded in registers in the shadow of the MFMAs that precede
+// their use.  gemm_generic_kernel takes the shapes the tiles cannot (K or N not a
+// multiple of 64 / 8).  plan_gemm picks tile shapes and splits a problem into whole waves
+// of large tiles plus the leftover on small ones.
 //
 // Orientation: the MFMA's row operand is the W fragment and its column operand
 // the A fragment, so a lane ends up with ONE output row m and runs of four
@@ -30,7 +27,7 @@
 #include <type_traits>
 
 #ifndef NVFP4_SCHED
-#define NVFP4_SCHED 2     // VALU instructions requested after every MFMA of the main loop
+#define NVFP4_SCHED 1     // 1: a scheduling barrier after every MFMA of the main loop keeps the hand-placed order
 #endif
 
 // Empty inline-asm statements that tie values (or memory) to a point of the
@@ -86,17 +83,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
 {
     uint32_t u = __float_as_uint(f);
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
-// Eight codes (one dword, all inside one 16-element block) times the block
-// scale -> eight f16: four conversions (two codes each) and four packed multiplies.
-__device__ __forceinline__ half8v expand_dword(uint32_t w, half2v p)
-{
-    half2v a = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 0) * p;
-    half2v b = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 1) * p;
-    half2v c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2) * p;
-    half2v d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 3) * p;
-    return half8v{a.x, a.y, b.x, b.y, c.x, c.y, d.x, d.y};
 }
 
 // 3-bit swizzle key of a row: distinct over every 8 consecutive rows and,
@@ -256,15 +242,6 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
     }
 }
 
-// staging half-units (x = 0 .. NH-1) handled in MFMA phase kk: phases 0, 1, 2 share them
-__host__ __device__ constexpr int phase_of_half_unit(int x, int NH) { return x * 3 / NH; }
-__host__ __device__ constexpr int half_units_in_phase(int NH, int kk)
-{
-    int n = 0;
-    for (int x = 0; x < NH; ++x) n += phase_of_half_unit(x, NH) == kk;
-    return n;
-}
-
 // f(integral_constant<int, I>) for I = First .. Last - 1: a loop whose index is a compile-time
 // constant in the body (array indices stay constants, guards can be `if constexpr`)
 template <int First, int Last, class F>
@@ -276,279 +253,8 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-// Scheduling request for one phase: NM MFMAs, each followed by its share of NV VALU
-// and ND LDS instructions.
-template <int NV, int ND, int NM, int T = 0>
-__device__ __forceinline__ void sched_phase()
-{
-    if constexpr (T < NM) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        constexpr int v = NV * (T + 1) / NM - NV * T / NM, d = ND * (T + 1) / NM - ND * T / NM;
-        if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x002, v, 0);
-        if constexpr (d > 0) __builtin_amdgcn_sched_group_barrier(0x080, d, 0);
-        sched_phase<NV, ND, NM, T + 1>();
-    }
-}
-
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_ldsf16_kernel(GemmArgs g)
-{
-    constexpr int WM = BM / 2, WN = BN / 2;        // per-wave tile (2 x 2 waves)
-    constexpr int TM = WM / 32, TN = WN / 32;      // 32x32 MFMA tiles per wave
-    // Staging units: 128 staged rows, 16 B of codes per thread and step.  Tiles of 128-row
-    // multiples have whole units of A and of W; the 64 x 64 tile has one unit whose rows
-    // 0..63 are A and 64..127 are W (waves 0-1 stage A, waves 2-3 stage W).
-    constexpr bool MIXED = BM < 128;
-    static_assert(MIXED ? (BM == 64 && BN == 64) : (BM % 128 == 0 && BN % 128 == 0), "tile shape");
-    constexpr int CA = MIXED ? 0 : BM / 128, CW = MIXED ? 0 : BN / 128;
-    constexpr int NU = MIXED ? 1 : CA + CW;
-    constexpr int A_BYTES = BM * ROW_BYTES, W_BYTES = BN * ROW_BYTES;
-    constexpr int W_BASE = 2 * A_BYTES;            // LDS: [A buf0][A buf1][W buf0][W buf1]
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: it selects the operand a unit belongs to
-    const int wm = wave >> 1, wn = wave & 1;
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int64_t m0 = (int64_t)(blockIdx.x / g.n_tiles_n) * BM, n0 = (int64_t)(blockIdx.x % g.n_tiles_n) * BN;
-    const int kbytes = (int)(g.K >> 1), kblocks = (int)(g.K >> 4);
-    const int KT = (int)(g.K / BK);
-
-    // buffer resources: rows past the end of an operand read as zero codes
-    const __amdgpu_buffer_rsrc_t rcA = __builtin_amdgcn_make_buffer_rsrc((void *)g.codesA, 0, (int)(g.M * kbytes), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesA, 0, (int)(g.M * kblocks), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rcW = __builtin_amdgcn_make_buffer_rsrc((void *)g.codesW, 0, (int)(g.N * kbytes), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc((void *)g.scalesW, 0, (int)(g.N * kblocks), 0x00020000);
-
-    // staging: unit u of this thread covers staged row (tid >> 1) + 128 u', half-row (tid & 1);
-    // units 0..CA-1 belong to A, CA..NU-1 to W
-    const int srow = tid >> 1, hsel = tid & 1;
-    auto unit_is_a = [&](int u) { return MIXED ? wave < 2 : u < CA; };
-    int vc[NU], vs[NU];
-#pragma unroll
-    for (int u = 0; u < NU; ++u) {
-        const bool isA = unit_is_a(u);
-        const int64_t gr = MIXED ? (isA ? m0 + srow : n0 + (srow - 64))
-                                 : (u < CA ? m0 : n0) + srow + 128 * (u < CA ? u : u - CA);
-        const int64_t lim = isA ? g.M : g.N;
-        // an out-of-range row gets an offset past the end of the buffer (reads zero)
-        vc[u] = gr < lim ? (int)(gr * kbytes) + hsel * 16 : 0x7FFFFFF0;
-        vs[u] = gr < lim ? (int)(gr * kblocks) + hsel * 2 : 0x7FFFFFF0;
-    }
-    int st_a[4], st_w[4];          // LDS byte offsets of this thread's four chunks of a staged row
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        st_a[i] = lds_chunk_off(MIXED ? (srow & 63) : srow, 4 * hsel + i);
-        st_w[i] = st_a[i] + W_BASE;
-    }
-    int fr_a[4], fr_w[4];          // LDS byte offsets of this lane's fragment in phase kk
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        fr_a[kk] = lds_chunk_off(lrow, 2 * kk + lhalf) + wm * WM * ROW_BYTES;
-        fr_w[kk] = lds_chunk_off(lrow, 2 * kk + lhalf) + W_BASE + wn * WN * ROW_BYTES;
-    }
-
-    uint4v rc[NU];
-    uint32_t rs[NU];
-    auto load_unit = [&](int u, int kt) {
-        kt = min(kt, KT - 1);                      // never read past the last K step of a row
-        if (unit_is_a(u)) {
-            rc[u] = __builtin_amdgcn_raw_buffer_load_b128(rcA, vc[u], kt * 32, 0);
-            rs[u] = __builtin_amdgcn_raw_buffer_load_b16(rsA, vs[u], kt * 4, 0);
-        } else {
-            rc[u] = __builtin_amdgcn_raw_buffer_load_b128(rcW, vc[u], kt * 32, 0);
-            rs[u] = __builtin_amdgcn_raw_buffer_load_b16(rsW, vs[u], kt * 4, 0);
-        }
-    };
-    // half h of unit u: 16 codes = one block -> two 16-byte f16 chunks
-    auto stage_half = [&](int u, int h, int buf) {
-        const bool isA = unit_is_a(u);
-        const int imm = MIXED ? buf * A_BYTES
-                              : (u < CA ? buf * A_BYTES + u * 128 * ROW_BYTES : buf * W_BYTES + (u - CA) * 128 * ROW_BYTES);
-        const int o0 = isA ? st_a[2 * h] : st_w[2 * h], o1 = isA ? st_a[2 * h + 1] : st_w[2 * h + 1];
-        half2v sc = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(rs[u], 1.0f, false);   // both E4M3 scales -> f16
-        half2v p = h ? half2v{sc.y, sc.y} : half2v{sc.x, sc.x};
-        *(half8v *)(lds + o0 + imm) = expand_dword(rc[u][2 * h], p);
-        *(half8v *)(lds + o1 + imm) = expand_dword(rc[u][2 * h + 1], p);
-    };
-
-    float16v acc[TN][TM];
-#pragma unroll
-    for (int i = 0; i < TN; ++i)
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    half8v fa[2][TM], fw[2][TN];
-    auto read_frags = [&](int buf, int kk, int slot) {
-#pragma unroll
-        for (int j = 0; j < TM; ++j)
-            fa[slot][j] = *(const half8v *)(lds + fr_a[kk] + buf * A_BYTES + j * 32 * ROW_BYTES);
-#pragma unroll
-        for (int i = 0; i < TN; ++i)
-            fw[slot][i] = *(const half8v *)(lds + fr_w[kk] + buf * W_BYTES + i * 32 * ROW_BYTES);
-    };
-    auto mfma_range = [&](int kk, int lo, int hi) {
-#pragma unroll
-        for (int t = lo; t < hi; ++t) {
-            const int i = t / TM, j = t % TM;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[kk & 1][i], fa[kk & 1][j], acc[i][j], 0, 0, 0);
-        }
-    };
-
-    if constexpr (MIXED) {
-        // One MFMA tile per wave: the phase-by-phase pipeline below would expose an LDS round
-        // trip per MFMA and one global-load latency per step.  Instead the codes of the next
-        // four steps are kept in flight in registers, all four phases' fragments of a step are
-        // read at once right after the barrier that completes the step's buffer, and the four
-        // MFMAs follow back to back while the next step is expanded into the other buffer.
-        constexpr int D = 4;                        // steps in flight
-        uint4v qc[D];
-        uint32_t qs[D];
-        const bool isA = wave < 2;
-        auto fetch = [&](int slot, int kt) {
-            kt = min(kt, KT - 1);                   // never read past the last K step of a row
-            if (isA) {
-                qc[slot] = __builtin_amdgcn_raw_buffer_load_b128(rcA, vc[0], kt * 32, 0);
-                qs[slot] = __builtin_amdgcn_raw_buffer_load_b16(rsA, vs[0], kt * 4, 0);
-            } else {
-                qc[slot] = __builtin_amdgcn_raw_buffer_load_b128(rcW, vc[0], kt * 32, 0);
-                qs[slot] = __builtin_amdgcn_raw_buffer_load_b16(rsW, vs[0], kt * 4, 0);
-            }
-        };
-        auto stage = [&](int slot, int buf) {       // 32 codes = two blocks -> four 16-byte f16 chunks
-            half2v sc = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(qs[slot], 1.0f, false);
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                half2v p = h ? half2v{sc.y, sc.y} : half2v{sc.x, sc.x};
-                const int o0 = (isA ? st_a[2 * h] : st_w[2 * h]) + buf * A_BYTES;
-                const int o1 = (isA ? st_a[2 * h + 1] : st_w[2 * h + 1]) + buf * A_BYTES;
-                *(half8v *)(lds + o0) = expand_dword(qc[slot][2 * h], p);
-                *(half8v *)(lds + o1) = expand_dword(qc[slot][2 * h + 1], p);
-            }
-        };
-        half8v a4[4], w4[4];
-        auto read_all = [&](int buf) {
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                a4[kk] = *(const half8v *)(lds + fr_a[kk] + buf * A_BYTES);
-                w4[kk] = *(const half8v *)(lds + fr_w[kk] + buf * W_BYTES);
-            }
-        };
-        // slot of step t: t mod D.  Prologue: steps 0 .. D in flight / staged.
-#pragma unroll
-        for (int t = 0; t < D; ++t) fetch(t, t);
-        stage(0, 0);
-        fetch(0, D);
-        __syncthreads();
-        read_all(0);
-        // iteration kt multiplies step kt out of buffer kt & 1, stages step kt + 1 (slot (kt + 1) mod D)
-        // into the other buffer, which was last read before the previous barrier, and refills the slot
-        auto iteration = [&](int kt, auto slot_c) {
-            constexpr int slot = decltype(slot_c)::value;       // (kt + 1) mod D
-            const int buf = kt & 1;
-            stage(slot, buf ^ 1);
-            fetch(slot, kt + 1 + D);
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w4[kk], a4[kk], acc[0][0], 0, 0, 0);
-            __syncthreads();
-            read_all(buf ^ 1);
-        };
-        int kt = 0;
-        for (; kt + 3 < KT; kt += 4) {
-            iteration(kt, std::integral_constant<int, 1>{});
-            iteration(kt + 1, std::integral_constant<int, 2>{});
-            iteration(kt + 2, std::integral_constant<int, 3>{});
-            iteration(kt + 3, std::integral_constant<int, 0>{});
-        }
-        if (kt < KT) iteration(kt, std::integral_constant<int, 1>{});
-        if (kt + 1 < KT) iteration(kt + 1, std::integral_constant<int, 2>{});
-        if (kt + 2 < KT) iteration(kt + 2, std::integral_constant<int, 3>{});
-        gemm_epilogue<TM, TN, EPI>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
-        return;
-    }
-
-    // prologue: step 0 staged, step 1 in registers, fragments of (step 0, phase 0) in flight
-#pragma unroll
-    for (int u = 0; u < NU; ++u) load_unit(u, 0);
-#pragma unroll
-    for (int u = 0; u < NU; ++u) {
-        stage_half(u, 0, 0);
-        stage_half(u, 1, 0);
-    }
-    if (KT > 1) {
-#pragma unroll
-        for (int u = 0; u < NU; ++u) load_unit(u, 1);
-    }
-    __syncthreads();
-    read_frags(0, 0, 0);
-
-    // Iteration kt multiplies out of LDS buffer kt&1 in four 16-wide MFMA phases.
-    // Meanwhile the codes of step kt+1 (already in registers) are expanded into the
-    // other buffer during phases 0..2 and the codes of step kt+2 are fetched.  Every
-    // fragment of the current buffer has been read by the end of phase 2, so the
-    // single barrier sits in the middle of phase 3: after it the other buffer is
-    // complete, its first fragments are requested, and the remaining MFMAs of
-    // phase 3 cover that LDS latency.
-    auto iteration = [&](int kt, auto buf_c, auto stage_next, auto load_next2) {
-        constexpr int buf = decltype(buf_c)::value;
-        constexpr bool kStage = decltype(stage_next)::value, kLoad = decltype(load_next2)::value;
-        constexpr int NH = 2 * NU;                  // half-units to stage
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk < 3) read_frags(buf, kk + 1, (kk + 1) & 1);
-            if (kStage) {
-#pragma unroll
-                for (int x = 0; x < NH; ++x) {
-                    if (phase_of_half_unit(x, NH) == kk) {
-                        stage_half(x >> 1, x & 1, buf ^ 1);
-                        if (kLoad && (x & 1)) load_unit(x >> 1, kt + 2);
-                    }
-                }
-            }
-            if (kk < 3) {
-                mfma_range(kk, 0, TN * TM);
-            } else {
-                mfma_range(kk, 0, TN * TM / 2);
-                __syncthreads();
-                if (kStage) read_frags(buf ^ 1, 0, 0);
-                mfma_range(kk, TN * TM / 2, TN * TM);
-            }
-        }
-#if NVFP4_SCHED
-        // Ask the scheduler for a steady interleave.  Phase kk holds 16 MFMAs, the
-        // eight fragment reads of the next phase, and hu half-units of staging (about
-        // 18 VALU and two LDS writes each, plus a pair of buffer loads per unit); they
-        // are dealt out evenly behind the MFMAs.
-        if constexpr (kStage) {
-            sched_phase<half_units_in_phase(NH, 0) * 18, 8 + 2 * half_units_in_phase(NH, 0), TN * TM>();
-            sched_phase<half_units_in_phase(NH, 1) * 18, 8 + 2 * half_units_in_phase(NH, 1), TN * TM>();
-            sched_phase<half_units_in_phase(NH, 2) * 18, 8 + 2 * half_units_in_phase(NH, 2), TN * TM>();
-        }
-#endif
-    };
-    {
-        // Every iteration stages "the next step" and fetches "the one after"; past the
-        // end of K the fetch is clamped to the last step, and what gets staged from it
-        // is never multiplied.
-        using T = std::true_type;
-        using B0 = std::integral_constant<int, 0>;
-        using B1 = std::integral_constant<int, 1>;
-        int kt = 0;
-        for (; kt + 1 < KT; kt += 2) {          // two steps per trip so the buffer index is a constant
-            iteration(kt, B0{}, T{}, T{});
-            iteration(kt + 1, B1{}, T{}, T{});
-        }
-        if (kt < KT) iteration(kt, B0{}, T{}, T{});
-    }
-
-    gemm_epilogue<TM, TN, EPI>(acc, g, lds, m0 + wm * WM, n0 + wn * WN);
-}
-
 // ============================================================================
-// Register-dequantizing kernel (the fast path for large tiles).
+// Register-dequantizing tiled kernel.
 //
 // The operands stay 4-bit all the way into LDS.  Every 128 k the packed codes of
 // the tile (64 B per row) are copied HBM -> LDS by buffer loads that write LDS
@@ -592,6 +298,12 @@ __device__ __forceinline__ void wait_vmcnt_le()
     static_assert(N >= 0 && N < 64, "vmcnt range");
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | 0x0F70);
 }
+
+// MFMA of a sub-step behind which fragment f is read (and, two sub-steps later, its scales converted): one
+// fragment per MFMA where a sub-step has at least as many MFMAs as fragments (the large tiles), otherwise
+// the fragments are dealt over the MFMAs there are
+template <int NMF, int NF>
+constexpr int frag_slot(int f) { return NMF >= NF ? f : f * NMF / NF; }
 
 template <int BM, int BN, int EPI, int NW>
 __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
@@ -853,7 +565,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
                         else expand_piece(set ^ 1, 0, pc);
                     }
                 });
-                if constexpr (j == 0 && t < NF) read_frag(rs + 1, set ^ 1, t, half == 1);
+                // fragment f of the next register step is read behind MFMA frag_slot(f) of sub-step 0
+                static_for<0, NF>([&](auto f_c) {
+                    constexpr int f = decltype(f_c)::value;
+                    if constexpr (j == 0 && frag_slot<NMF, NF>(f) == t) read_frag(rs + 1, set ^ 1, f, half == 1);
+                    // the next step's scales (read during sub-step 0) become f16 during sub-step 2
+                    if constexpr (j == 2 && frag_slot<NMF, NF>(f) == t) convert_scales(set ^ 1, f, half == 0);
+                });
                 if constexpr (half == 1 && j == 1) {
                     static_for<0, UPW>([&](auto x_c) {
                         constexpr int x = decltype(x_c)::value;
@@ -861,8 +579,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
                     });
                     if constexpr (quarter == 3 && t == NMF - 1) copy_scales(ng >> 1);   // ng is even here: a new scale group
                 }
-                // the next step's scales (read during sub-step 0) become f16 during sub-step 2
-                if constexpr (j == 2 && t < NF) convert_scales(set ^ 1, t, half == 0);
 #if NVFP4_SCHED
                 __builtin_amdgcn_sched_barrier(0);
 #endif
@@ -1032,34 +748,13 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g)
 }
 
 template <int BM, int BN, int EPI>
-static hipError_t launch_tiled(const GemmArgs &g, int64_t tiles, hipStream_t s)
-{
-    constexpr int smem_main = 2 * (BM + BN) * ROW_BYTES, smem_epi = 4 * 16384;
-    constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
-    // the dynamic LDS limit is raised once per kernel variant and device
-    static uint64_t attr_set = 0;
-    int dev = 0;
-    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
-    if (((attr_set >> (dev & 63)) & 1u) == 0) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_ldsf16_kernel<BM, BN, EPI>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set |= 1ull << (dev & 63);
-    }
-    GemmArgs a = g;
-    a.n_tiles_n = (int)((g.N + BN - 1) / BN);
-    const unsigned grid = (unsigned)tiles;          // a prefix of the row-major tile grid
-    gemm_ldsf16_kernel<BM, BN, EPI><<<grid, 256, smem, s>>>(a);
-    return hipGetLastError();
-}
-
-template <int BM, int BN, int EPI>
 static hipError_t launch_regdq(const GemmArgs &g, int64_t tiles, hipStream_t s)
 {
     constexpr int NW = kRegdqWaves;
     constexpr int smem_main = kCodeStages * (BM + BN) * 64 + 2 * (BM + BN) * 16, smem_epi = NW * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
-    static uint64_t attr_set = 0;                    // per kernel variant and device, as above
+    // the dynamic LDS limit is raised once per kernel variant and device
+    static uint64_t attr_set = 0;
     int dev = 0;
     if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
     if (((attr_set >> (dev & 63)) & 1u) == 0) {
@@ -1080,7 +775,7 @@ static hipError_t launch_regdq(const GemmArgs &g, int64_t tiles, hipStream_t s)
 // a fixed per-tile overhead worth about 8 steps), plus about 4 for the launch itself.
 enum TileKind { kTile128 = 0, kTile256x256 = 1, kTile256x192 = 2, kTile64 = 3 };
 struct TileShape { int bm, bn; double step_cost; };
-static const TileShape kShapes[4] = {{128, 128, 0.45}, {256, 256, 1.0}, {256, 192, 0.80}, {64, 64, 0.22}};
+static const TileShape kShapes[4] = {{128, 128, 0.30}, {256, 256, 1.0}, {256, 192, 0.80}, {64, 64, 0.16}};
 constexpr int kCUs = 256;
 
 static double tile_cost(int64_t M, int64_t N, int64_t K, const TileShape &t)
@@ -1219,8 +914,8 @@ static hipError_t launch_kind(TileKind kind, const GemmArgs &g, int64_t tiles, h
     case kTile256x192: return launch_regdq<256, 192, EPI>(g, tiles, s);
     default:
         if constexpr ((EPI & kEpiLora) != 0) return hipErrorInvalidValue;   // planned with the 256-row tiles only
-        else if (kind == kTile64) return launch_tiled<64, 64, EPI>(g, tiles, s);
-        else return launch_tiled<128, 128, EPI>(g, tiles, s);
+        else if (kind == kTile64) return launch_regdq<64, 64, EPI>(g, tiles, s);
+        else return launch_regdq<128, 128, EPI>(g, tiles, s);
     }
 }
 
