@@ -750,7 +750,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g)
 template <int BM, int BN, int EPI>
 static hipError_t launch_regdq(const GemmArgs &g, int64_t tiles, hipStream_t s)
 {
-    constexpr int NW = kRegdqWaves;
+    constexpr int NW = BM >= 256 ? kRegdqWaves : 4;   // the small tiles always run four waves
     constexpr int smem_main = kCodeStages * (BM + BN) * 64 + 2 * (BM + BN) * 16, smem_epi = NW * 16384;
     constexpr int smem = smem_main > smem_epi ? smem_main : smem_epi;
     // the dynamic LDS limit is raised once per kernel variant and device
