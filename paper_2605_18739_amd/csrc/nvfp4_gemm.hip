@@ -840,6 +840,22 @@ static LaunchPlan plan_gemm(int64_t M, int64_t N, int64_t K, bool big_only = fal
         extra[i].tiles = ((extra[i].m_hi - extra[i].m_lo + ts.bm - 1) / ts.bm) * ((extra[i].n_hi - extra[i].n_lo + ts.bn - 1) / ts.bn);
         split += ci;
     }
+    // alternative when the main launch would end inside a tile row: end it at the last whole tile row
+    // instead, so that the leftover is one rectangle (one more launch instead of two)
+    if (c != 0 && q > 0) {
+        SubLaunch below = {q * t.bm, M, 0, N, kTile128, 0};
+        double cb;
+        below.kind = choose_tile(M - below.m_lo, N, K, &cb, big_only);
+        const TileShape &ts = kShapes[below.kind];
+        below.tiles = ((M - below.m_lo + ts.bm - 1) / ts.bm) * ((N + ts.bn - 1) / ts.bn);
+        const int64_t rows_tiles = q * tn;
+        const double by_rows = (double)((rows_tiles + kCUs - 1) / kCUs) * ((double)(K / BK) * t.step_cost + 8.0) + 4.0 + cb;
+        if (by_rows < whole && by_rows < split) {
+            p.part[0].tiles = rows_tiles;
+            p.part[p.n++] = below;
+            return p;
+        }
+    }
     if (split < whole) {
         p.part[0].tiles = main_tiles;
         for (int i = 0; i < ne; ++i) p.part[p.n++] = extra[i];

@@ -164,6 +164,9 @@ def test_gemm_launch_plan():
     # positions (192 valid rows x 4096 columns) run as 3 x 64 tiles of 64x64
     assert nv.nvfp4_gemm_plan(3520, 14336, 3072) == [("256x256", 768), ("64x64", 192)]
     assert nv.nvfp4_gemm_plan(3520, 3072, 14336) == [("256x192", 224)]
+    # the training layer's weight gradient: 672 tiles = 2.6 waves; 42 whole tile rows (two waves, the
+    # second 97 % full), then the 14 tile rows below as one wave of 256x192 tiles
+    assert nv.nvfp4_gemm_plan(14336, 3072, 17600) == [("256x256", 504), ("256x192", 224)]
     assert nv.nvfp4_gemm_plan(64, 64, 48) == [("generic", 0)]          # K % 64 != 0
     assert nv.nvfp4_gemm_plan(130, 260, 128) == [("generic", 0)]       # N % 8 != 0
     rng = np.random.default_rng(5)
@@ -179,9 +182,10 @@ def test_gemm_launch_plan():
         if len(plan) == 1:
             assert main == -(-M // bm) * tiles_n
         else:
-            # the main launch is a whole number of waves and stops inside tile row q at column c;
-            # the other launches tile [row q, from column c] and [rows below q] completely
-            assert main % 256 == 0
+            # the main launch is a whole number of waves and stops inside tile row q at column c,
+            # or it ends with tile row q - 1 (c = 0); the other launches tile [row q, from column c]
+            # and [rows below] completely
+            assert main % 256 == 0 or main % tiles_n == 0
             q, c = divmod(main, tiles_n)
             rects = []
             if c:

@@ -264,8 +264,8 @@ def test_gemm_random_shapes(oracle):
     shapes = [(int(g.integers(1, 900)), 8 * int(g.integers(1, 260)), 64 * int(g.integers(1, 9))) for _ in range(10)]
     shapes += [(1290, 2056, 192), (2400, 2304, 64), (4600, 1800, 320), (9000, 4104, 64), (17000, 3080, 64)]
     # whole waves of 256x256 tiles plus one or two more launches: rows below the last full wave, the tail
-    # of a tile row, and both
-    shapes += [(5489, 2928, 768), (6418, 7544, 512), (7226, 7000, 1856)]
+    # of a tile row, a main launch that ends with a whole tile row, and both kinds of leftover
+    shapes += [(5489, 2928, 768), (6418, 7544, 512), (7226, 7000, 1856), (7040, 5296, 2368)]
     for M, N, K in shapes:
         plan = nv.nvfp4_gemm_plan(M, N, K)
         kinds.update(t for t, _ in plan)
@@ -274,7 +274,8 @@ def test_gemm_random_shapes(oracle):
         rows = None if M * N * K < 3e9 else np.unique(np.concatenate([g.integers(0, M, 200), [0, M - 1]]))
         _gemm_case(oracle, ab, wb, f"sweep {M}x{N}x{K} {plan}", rows=rows, check_bf16=False)
     assert kinds >= {"64x64", "128x128", "256x192", "256x256"}, kinds
-    assert [len(nv.nvfp4_gemm_plan(*shp)) for shp in shapes[-3:]] == [2, 2, 3]
+    assert [len(nv.nvfp4_gemm_plan(*shp)) for shp in shapes[-4:]] == [2, 2, 2, 3]
+    assert nv.nvfp4_gemm_plan(7226, 7000, 1856)[0][1] % 256 != 0       # 27 whole tile rows of 28 tiles
 
 
 @pytest.mark.parametrize("M,N", [(300100, 264), (72, 300104)])
