@@ -725,7 +725,7 @@ def test_kv_dequant_gather_window(oracle):
 
 # --------------------------------------------------- fused activation + quantize
 
-def _act_quant_case(oracle, M, N, K, given_scale, what):
+def _act_quant_case(oracle, M, N, K, given_scale, what, max_flips=0.02):
     say(f"[act-quant] {what} {M}x{N}x{K} given_scale={given_scale}")
     g = np.random.default_rng(M + N)
     ab = wl.activation_with_outliers(M, K, 2, 0)
@@ -746,7 +746,7 @@ def _act_quant_case(oracle, M, N, K, given_scale, what):
     got = wl.bf16_bits_to_f32(hb).astype(np.float64)
     tol = 2.0 ** -7 * np.abs(want) + 2.0 ** -15 * S + 1e-30      # one bf16 ulp + GEMM bound
     assert (np.abs(got - want) <= tol).all()
-    assert (got != want).mean() < 0.02                            # and it is the same bf16 almost everywhere
+    assert (got != want).mean() < max_flips                       # and it is the same bf16 almost everywhere
     # (3) without the optional H buffer the bytes are the same
     out2 = nv.nvfp4_gemm_act_quant(ga, gw, nv.ACT_GELU_TANH, global_scale_in=gs)
     a, b = host_q(out), host_q(out2)
@@ -761,6 +761,12 @@ def test_gemm_act_quant(oracle, given_scale):
     _act_quant_case(oracle, 2100, 2064, 256, given_scale, "256x192 tiles")
     _act_quant_case(oracle, 4200, 3072, 128, given_scale, "256x256 tiles")
     _act_quant_case(oracle, 40, 48, 48, given_scale, "untiled K")
+    # whole waves of 256x256 tiles, then the tail of a tile row on 64x64 tiles and the rows below on
+    # 128x128 tiles: three launches share the output pitch and the table of partial maxima
+    assert len(nv.nvfp4_gemm_plan(7040, 5296, 2368)) == 3
+    # (the fp32 accumulation error grows with K against the fixed bf16 ulp, so more results land on the
+    # other side of a rounding boundary than at K = 256: 3 % here)
+    _act_quant_case(oracle, 7040, 5296, 2368, given_scale, "three launches", max_flips=0.06)
 
 
 # -------------------------------------------------------- full benchmark sizes
