@@ -288,8 +288,8 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c);
  * for an [M, K] x [N, K] problem, as text: one "BMxBN:workgroups" item per launch in
  * launch order, separated by spaces (tile shape and number of workgroups; "generic"
  * for shapes only the untiled fallback kernel takes).  The plan follows the tiling
- * of Sec. 3.1's fused W4A4 GEMM onto 256 compute units: whole waves of large tiles,
- * then the leftover rectangle on smaller ones.  Host pointers; nothing is launched.
+ * of Sec. 3.1's fused W4A4 GEMM onto 256 compute units: whole waves (or whole tile rows)
+ * of large tiles, then the leftover rectangles on tiles that suit them.  Host pointers; nothing is launched.
  * Returns the number of launches, NVFP4_ERR_WORKSPACE if text_bytes is too small. */
 int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, char *text, size_t text_bytes);
 
