@@ -217,6 +217,24 @@ int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_t
                    void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * nvfp4_kv_quant for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments and the same bytes as nvfp4_kv_quant, minus the workspace: the
+ * partial maxima live in a fixed array inside the library's device image (4 KB on every GPU
+ * the library runs on, held until the process ends; its address is looked up on the first
+ * call on a device).  The call allocates nothing, frees nothing and calls no allocating
+ * routine; launch timing does not record it.
+ * Limit: T * H * d <= NVFP4_NOALLOC_MAX_ELEMENTS, NVFP4_ERR_SHAPE beyond it.
+ * All calls on one GPU share that array, and it keeps the last call's contents (every slot a
+ * call reads it has written before, so nothing needs clearing): calls that overlap on one GPU
+ * (different streams, or several host threads' work in flight together) race on it and
+ * must be ordered by the caller.
+ */
+#define NVFP4_NOALLOC_MAX_ELEMENTS ((int64_t)1 << 32)
+int nvfp4_kv_quant_noalloc(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
+                           void *stream);
+
+/*
  * KV-cache quantization with the Four-over-Six scale search, the variant the
  * paper applies to the cache (Sec. 3.2; Appendix, Eq. 12-13).  Arguments as
  * nvfp4_kv_quant (workspace size: NVFP4_OP_KV_QUANT_4OVER6); the result is read

@@ -19,6 +19,7 @@ ACT_NONE, ACT_GELU_TANH = 0, 1
 OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT, OP_GEMM_ACT_QUANT_GEMM = 0, 1, 2, 3, 4, 5
 OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6, OP_KV_QUANT_K, OP_KV_DEQUANT_GATHER = 6, 7, 8, 9
 KV_MAX_CHUNKS = 64
+NOALLOC_MAX_ELEMENTS = 1 << 32
 OP_QUANTIZE_2D, OP_QUANTIZE_RHT, OP_QUANTIZE_A2A, OP_LORA_DOWN, OP_GEMM_LORA = 10, 11, 12, 13, 14
 LORA_RANK = 128
 
@@ -59,6 +60,8 @@ def lib():
         L.nvfp4_gemm_act_quant.argtypes = [tp, tp, c.c_int, vp, tp, vp, vp, sz, vp]
         L.nvfp4_kv_quant.restype = c.c_int
         L.nvfp4_kv_quant.argtypes = [vp, i64, i64, i64, tp, vp, sz, vp]
+        L.nvfp4_kv_quant_noalloc.restype = c.c_int
+        L.nvfp4_kv_quant_noalloc.argtypes = [vp, i64, i64, i64, tp, vp]
         L.nvfp4_kv_dequant.restype = c.c_int
         L.nvfp4_kv_dequant.argtypes = [tp, vp, i64, i64, i64, vp]
         L.nvfp4_quantize_4over6.restype = c.c_int
@@ -216,6 +219,15 @@ def nvfp4_kv_quant(kv, out=None, workspace=None, stream=None):
     ct = out.c()
     _check(lib().nvfp4_kv_quant(_ptr(kv), T, H, d, ctypes.byref(ct), _ptr(workspace), workspace.numel(),
                                 _stream(stream)))
+    return out
+
+
+def nvfp4_kv_quant_noalloc(kv, out, stream=None):
+    """kv: contiguous bf16 [T, H, d]; `out` must be given: this entry point (and this wrapper) allocates nothing."""
+    assert kv.dtype == torch.bfloat16 and kv.dim() == 3 and kv.is_contiguous()
+    T, H, d = kv.shape
+    ct = out.c()
+    _check(lib().nvfp4_kv_quant_noalloc(_ptr(kv), T, H, d, ctypes.byref(ct), _stream(stream)))
     return out
 
 

@@ -10,6 +10,12 @@
 
 using namespace nvfp4;
 
+// Scratch memory of the allocation-free entry point (nvfp4_kv_quant_noalloc): the partial maxima
+// that the ordinary entry points keep in the caller's workspace.  Every GPU the library runs on
+// holds its own copy of this array at its own address; in host code the name is only a handle
+// for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) uint32_t scratch[kMaxPartials];
+
 namespace {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -95,6 +101,22 @@ int quantize_impl(const void *x, int64_t R, int64_t C, int64_t ld, int block_axi
     return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
 }
 
+// Device address of `scratch` on the current device, resolved once per device (first call there).
+constexpr int kMaxDevices = 64;
+uint32_t *g_scratch_ptr[kMaxDevices] = {};
+int scratch_on_current_device(uint32_t **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return NVFP4_ERR_LAUNCH;
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return NVFP4_ERR_LAUNCH;
+        g_scratch_ptr[dev] = static_cast<uint32_t *>(p);
+    }
+    *ptr = g_scratch_ptr[dev];
+    return NVFP4_OK;
+}
+
 int check_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W)
 {
     if (int rc = check_tensor(A)) return rc;
@@ -126,6 +148,19 @@ int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_t
     Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_KV_QUANT);
     return quantize_impl(kv_bf16, T * H, d, d, 0, nullptr, out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(stream));
+}
+
+int nvfp4_kv_quant_noalloc(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_tensor *out,
+                           void *stream)
+{
+    if (T <= 0 || H <= 0 || d <= 0) return NVFP4_ERR_SHAPE;
+    // T * H * d <= NVFP4_NOALLOC_MAX_ELEMENTS, tested without forming a product that could overflow
+    if (T > NVFP4_NOALLOC_MAX_ELEMENTS / H || T * H > NVFP4_NOALLOC_MAX_ELEMENTS / d) return NVFP4_ERR_SHAPE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    uint32_t *ws = nullptr;
+    if (int rc = scratch_on_current_device(&ws)) return rc;
+    // no launch timing here: recording it would create events on first use
+    return quantize_impl(kv_bf16, T * H, d, d, 0, nullptr, out, ws, kPartialBytes, static_cast<hipStream_t>(stream));
 }
 
 int nvfp4_quantize_4over6(const void *x_bf16, int64_t R, int64_t C, int64_t ld,

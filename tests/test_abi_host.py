@@ -26,7 +26,8 @@ def test_library_exports_every_declared_symbol():
             "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string",
             "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6", "nvfp4_kv_quant_k",
             "nvfp4_kv_dequant_gather", "nvfp4_quantize_2d", "nvfp4_quantize_rht",
-            "nvfp4_quantize_for_all_to_all", "nvfp4_lora_down", "nvfp4_gemm_lora"} <= set(names)
+            "nvfp4_quantize_for_all_to_all", "nvfp4_lora_down", "nvfp4_gemm_lora",
+            "nvfp4_kv_quant_noalloc"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
