@@ -54,7 +54,7 @@ typedef enum nvfp4_status {
     NVFP4_OK = 0,
     NVFP4_ERR_NULL = -1,       /* a required pointer is NULL */
     NVFP4_ERR_SHAPE = -2,      /* non-positive size, K not a multiple of 16, K mismatch, bad enum */
-    NVFP4_ERR_ALIGN = -3,      /* pointer not 16-byte aligned, or ld not a multiple of 8 elements */
+    NVFP4_ERR_ALIGN = -3,      /* pointer not 16-byte aligned, or a row stride that does not keep rows 16-byte aligned */
     NVFP4_ERR_WORKSPACE = -4,  /* workspace NULL or smaller than nvfp4_workspace_bytes() */
     NVFP4_ERR_LAUNCH = -5      /* the HIP runtime refused a launch */
 } nvfp4_status;
@@ -114,9 +114,9 @@ int nvfp4_quantize_4over6(const void *x_bf16, int64_t R, int64_t C, int64_t ld,
                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Quantizer for the operands of the weight-gradient GEMM with the Random
- * Hadamard Transform in front (Sec. 2.2 "Multi-Shot AR NVFP4 Training": RHT
- * before quantization on the operands of the weight-gradient GEMM).  x_bf16
+ * Quantizer for the two operands of dW = dY^T X with a random Hadamard transform
+ * applied first (the outlier-spreading step of the training recipe in Sec. 2.2
+ * "Multi-Shot AR NVFP4 Training").  x_bf16
  * [R, C] is contracted over R (tokens).  Every group of 16 consecutive rows of a
  * column, v = x[16g .. 16g+15, c], is replaced by
  *   y = RN_bf16( (1/4) H16 diag(s) v ),  H16[i][j] = (-1)^popcount(i & j),
@@ -134,8 +134,9 @@ int nvfp4_quantize_rht(const void *x_bf16, int64_t R, int64_t C, int64_t ld, uin
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Weight quantizer with 2-D block scaling (Sec. 2.2 "Multi-Shot AR NVFP4
- * Training": 2-D block scaling for weights, 1-D for activations and gradients):
+ * Weight quantizer with square scaling tiles (the weight half of the training
+ * recipe in Sec. 2.2 "Multi-Shot AR NVFP4 Training"; activations and gradients
+ * keep the 16-element row blocks of nvfp4_quantize):
  * one E4M3 scale per 16 x 16 tile, from the tile's maximum, so that the forward
  * operand W [R, C] (blocks along C) and the backward operand W^T [C, R] (blocks
  * along R) contain the same quantized values.  The tensor format is unchanged:
@@ -155,8 +156,10 @@ int nvfp4_quantize_2d(const void *w_bf16, int64_t R, int64_t C, int64_t ld,
  * operands are all NVFP4):
  *   Y[m,n] = gsA*gsW * sum_b sA[m,b] sW[n,b] * sum_{j in b} cA[m,j] cW[n,j]
  * A: [M, K], W: [N, K], both K-contiguous ("NT").  Y: device [M, N], row
- * stride ldy elements, fp32 (NVFP4_OUT_F32) or bf16 (NVFP4_OUT_BF16, the fp32
- * result rounded to nearest even).  dgrad and wgrad are this same call on
+ * stride ldy elements (ldy >= N and a multiple of 4; a multiple of 8 for bf16
+ * output on the tiled kernels, so that every row starts on a 16-byte boundary:
+ * NVFP4_ERR_ALIGN otherwise), fp32 (NVFP4_OUT_F32) or bf16
+ * (NVFP4_OUT_BF16, the fp32 result rounded to nearest even).  dgrad and wgrad are this same call on
  * operands produced by nvfp4_quantize with the matching block_axis.
  * K % 64 == 0 and N % 8 == 0 run on the tiled MFMA kernels at any M and N
  * (operands of 2 GiB and more are cut into row chunks, one set of launches per
@@ -305,9 +308,10 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c);
 /* The kernel launches nvfp4_gemm (and the GEMM inside nvfp4_gemm_act_quant) issues
  * for an [M, K] x [N, K] problem, as text: one "BMxBN:workgroups" item per launch in
  * launch order, separated by spaces (tile shape and number of workgroups; "generic"
- * for shapes only the untiled fallback kernel takes).  The plan follows the tiling
- * of Sec. 3.1's fused W4A4 GEMM onto 256 compute units: whole waves (or whole tile rows)
- * of large tiles, then the leftover rectangles on tiles that suit them.  Host pointers; nothing is launched.
+ * for shapes only the untiled fallback kernel takes).  The plan is this library's own
+ * (a small cost model over its tile shapes and the 256 compute units): whole waves, or
+ * whole tile rows, of large tiles, then the leftover rectangles on tiles that suit them.
+ * Host pointers; nothing is launched.
  * Returns the number of launches, NVFP4_ERR_WORKSPACE if text_bytes is too small. */
 int nvfp4_gemm_plan(int64_t M, int64_t N, int64_t K, char *text, size_t text_bytes);
 

@@ -330,7 +330,9 @@ int nvfp4_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y, int64_t ld
     if (int rc = check_gemm(A, W)) return rc;
     if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16) return NVFP4_ERR_SHAPE;
     if (ldy < W->rows) return NVFP4_ERR_SHAPE;
-    if (!aligned16(Y) || (ldy & 3) != 0) return NVFP4_ERR_ALIGN;
+    // the tiled kernels store 16-byte vectors: every row of Y must start 16-byte aligned
+    const bool vec_rows = gemm_is_tiled(A->rows, W->rows, A->K);
+    if (!aligned16(Y) || (ldy & ((vec_rows && out_dtype == NVFP4_OUT_BF16) ? 7 : 3)) != 0) return NVFP4_ERR_ALIGN;
     std::lock_guard<std::mutex> lk(g_mu);
     Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_GEMM);
     GemmEpilogue ep{};
@@ -368,7 +370,8 @@ int nvfp4_gemm_lora(const nvfp4_tensor *A, const nvfp4_tensor *W, const void *t_
     if (out_dtype != NVFP4_OUT_F32 && out_dtype != NVFP4_OUT_BF16) return NVFP4_ERR_SHAPE;
     if (ldy < W->rows) return NVFP4_ERR_SHAPE;
     if (!gemm_is_tiled(A->rows, W->rows, A->K)) return NVFP4_ERR_SHAPE;   // K % 64 == 0 and N % 8 == 0 for the fused branch
-    if (!aligned16(Y) || (ldy & 3) != 0 || !aligned16(t_bf16) || !aligned16(b_bf16)) return NVFP4_ERR_ALIGN;
+    if (!aligned16(Y) || (ldy & (out_dtype == NVFP4_OUT_BF16 ? 7 : 3)) != 0 || !aligned16(t_bf16) || !aligned16(b_bf16))
+        return NVFP4_ERR_ALIGN;
     std::lock_guard<std::mutex> lk(g_mu);
     Timed t(static_cast<hipStream_t>(stream), NVFP4_OP_GEMM_LORA);
     GemmEpilogue ep{};
@@ -485,7 +488,7 @@ const char *nvfp4_status_string(int status)
     case NVFP4_OK: return "ok";
     case NVFP4_ERR_NULL: return "a required pointer is NULL";
     case NVFP4_ERR_SHAPE: return "bad shape: sizes must be positive, K a multiple of 16, operands must agree";
-    case NVFP4_ERR_ALIGN: return "bad alignment: pointers 16-byte aligned, leading dimensions multiples of 8 (4 for outputs)";
+    case NVFP4_ERR_ALIGN: return "bad alignment: pointers 16-byte aligned, row strides multiples of 8 elements (4 for fp32 outputs)";
     case NVFP4_ERR_WORKSPACE: return "workspace missing or too small (see nvfp4_workspace_bytes)";
     case NVFP4_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
     default: return "unknown status";

@@ -31,10 +31,6 @@
 #include <cstdio>
 #include <type_traits>
 
-#ifndef NVFP4_SCHED
-#define NVFP4_SCHED 1     // 1: a scheduling barrier after every MFMA of the main loop keeps the hand-placed order
-#endif
-
 // Empty inline-asm statements that tie values (or memory) to a point of the
 // instruction stream; register constraints only exist in the device pass.
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -72,16 +68,17 @@ struct GemmArgs {
     float lora_scale;
 };
 
-// tanh-form GELU in fp32: 0.5 y (1 + tanh(u)), u = sqrt(2/pi) (y + 0.044715 y^3), with
-// tanh(u) = 1 - 2 / (exp(2u) + 1), so gelu = y - y / (exp(2u) + 1).  exp and the
-// reciprocal are the hardware approximations (1 ulp); the result is rounded to bf16.
+// tanh-form GELU in fp32: 0.5 y (1 + tanh(u)), u = sqrt(2/pi) (y + 0.044715 y^3).  With
+// e = exp(2u), 0.5 (1 + tanh(u)) = e / (e + 1), so gelu = y e / (e + 1): no subtraction, hence no
+// cancellation for negative y.  exp and the reciprocal are the hardware approximations (1 ulp);
+// the exponent is clamped so that e stays finite (for large y, e / (e + 1) is 1 to fp32 anyway).
 __device__ __forceinline__ float gelu_tanh_f32(float y)
 {
     const float c2 = 2.0f * 0.7978845608028654f * 1.4426950408889634f;   // 2 sqrt(2/pi) log2(e)
     const float y2 = y * y;
-    const float t = y * (c2 + (c2 * 0.044715f) * y2);                    // 2u log2(e)
+    const float t = fminf(y * (c2 + (c2 * 0.044715f) * y2), 64.0f);      // 2u log2(e)
     const float e = __builtin_amdgcn_exp2f(t);
-    return y - y * __builtin_amdgcn_rcpf(e + 1.0f);
+    return (y * e) * __builtin_amdgcn_rcpf(e + 1.0f);
 }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f)
@@ -288,10 +285,7 @@ __device__ __forceinline__ void static_for(F &&f)
 // one chunk -- what a fragment read touches per LDS cycle -- fall on distinct
 // banks.
 // ============================================================================
-#ifndef NVFP4_REGDQ_WAVES
-#define NVFP4_REGDQ_WAVES 4
-#endif
-constexpr int kRegdqWaves = NVFP4_REGDQ_WAVES;   // waves per workgroup of the register-dequantizing kernel (4 or 8)
+constexpr int kRegdqWaves = 4;         // waves per workgroup: 2 x 2, one per SIMD (two per SIMD measured no faster)
 constexpr int kCodeStages = 4;         // LDS ring of 128-k code stages: copies run three copy steps ahead, one barrier per two
 constexpr int kScaleSteps = 2;         // copy steps covered by one 16-byte run of scales
 
@@ -584,9 +578,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
                     });
                     if constexpr (quarter == 3 && t == NMF - 1) copy_scales(ng >> 1);   // ng is even here: a new scale group
                 }
-#if NVFP4_SCHED
-                __builtin_amdgcn_sched_barrier(0);
-#endif
+                __builtin_amdgcn_sched_barrier(0);      // keeps the hand-placed order: nothing moves across an MFMA
             });
         });
     };

@@ -7,23 +7,10 @@
 #include <algorithm>
 #include "nvfp4_kernels.h"
 
-#ifndef NVFP4_Q_PLAIN_STORE
-#define NVFP4_Q_PLAIN_STORE 0
-#endif
-#ifndef NVFP4_Q_UNROLL
-#define NVFP4_Q_UNROLL 2
-#endif
-#ifndef NVFP4_DQ_UNROLL
-#define NVFP4_DQ_UNROLL 2
-#endif
-#ifndef NVFP4_DQ_GRID
-#define NVFP4_DQ_GRID 8192
-#endif
-#ifndef NVFP4_Q_GRID
-#define NVFP4_Q_GRID 16384
-#endif
-
 namespace nvfp4 {
+
+// blocks in flight per lane and the largest grids of the streaming kernels (measured choices)
+constexpr int kQuantUnroll = 2, kDequantUnroll = 2, kQuantMaxGrid = 16384, kDequantMaxGrid = 8192;
 
 // --------------------------------------------------------------------------
 // Pass 1: per-workgroup partial amax (largest |bf16| bit pattern).
@@ -166,7 +153,7 @@ void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
     const int64_t nb_row = C >> 4;
     const int64_t nblk = R * nb_row;
     const int64_t stride = (int64_t)gridDim.x * 256;
-    constexpr int U = NVFP4_Q_UNROLL;              // blocks in flight per lane
+    constexpr int U = kQuantUnroll;              // blocks in flight per lane
     uint4v v0[U], v1[U];
     auto fetch = [&](int64_t g0) {
 #pragma unroll
@@ -222,11 +209,7 @@ void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
                     const int64_t slab = h / slab_heads, hl = h - slab * slab_heads;
                     go = ((slab * (R / heads) + t) * slab_heads + hl) * nb_row + b;
                 }
-#if NVFP4_Q_PLAIN_STORE
-                *(uint2v *)(codes + (go << 3)) = cc;
-#else
                 __builtin_nontemporal_store(cc, (uint2v *)(codes + (go << 3)));
-#endif
                 scales[go] = (uint8_t)sbyte;
             }
         }
@@ -475,7 +458,7 @@ __global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__rest
     build_dequant_table(table, (double)*gs);
     __syncthreads();
     const int64_t stride = (int64_t)gridDim.x * 256;
-    constexpr int U = NVFP4_DQ_UNROLL;             // blocks in flight per lane
+    constexpr int U = kDequantUnroll;             // blocks in flight per lane
     for (int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x; g0 < nblk; g0 += stride * U) {
         uint2v ccs[U];
         uint32_t sbs[U];
@@ -611,7 +594,7 @@ hipError_t launch_quantize_rows(const uint16_t *x, int64_t R, int64_t C, int64_t
                                 const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
                                 float *gs_out, hipStream_t s, bool scale_search)
 {
-    int grid = grid_for(R * (C >> 4), NVFP4_Q_GRID);
+    int grid = grid_for(R * (C >> 4), kQuantMaxGrid);
     if (scale_search) {
         if (ld == C)
             quantize_rows_kernel<true, true><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes,
@@ -661,7 +644,7 @@ hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, cons
                                int64_t K, uint16_t *out, hipStream_t s)
 {
     int64_t nblk = rows * (K >> 4);
-    int grid = grid_for(nblk, NVFP4_DQ_GRID);
+    int grid = grid_for(nblk, kDequantMaxGrid);
     dequant_bf16_kernel<<<grid, 256, 0, s>>>(codes, scales, gs, nblk, out);
     return hipGetLastError();
 }
@@ -681,7 +664,7 @@ hipError_t launch_quantize_rows_slabs(const uint16_t *x, int64_t T, int64_t H, i
                                       const float *gs_in, const uint32_t *partial, int n_partial,
                                       uint8_t *codes, uint8_t *scales, float *gs_out, hipStream_t s)
 {
-    int grid = grid_for(T * H * (d >> 4), NVFP4_Q_GRID);
+    int grid = grid_for(T * H * (d >> 4), kQuantMaxGrid);
     quantize_rows_kernel<true, false, false><<<grid, 256, 0, s>>>(x, T * H, d, d, gs_in, partial, n_partial, codes,
                                                                   scales, gs_out, nullptr, (int)H, slab_heads);
     return hipGetLastError();
@@ -701,7 +684,7 @@ hipError_t launch_quantize_rows_smooth(const uint16_t *x, int64_t rows, int d, c
                                        const uint32_t *partial, int n_partial, uint8_t *codes,
                                        uint8_t *scales, float *gs_out, hipStream_t s)
 {
-    int grid = grid_for(rows * (d >> 4), NVFP4_Q_GRID);
+    int grid = grid_for(rows * (d >> 4), kQuantMaxGrid);
     quantize_rows_kernel<true, true, true><<<grid, 256, 0, s>>>(x, rows, d, d, nullptr, partial, n_partial, codes,
                                                                 scales, gs_out, row_mean, 0, 0,
                                                                 __builtin_ctz((unsigned)(d >> 4)));

@@ -84,6 +84,8 @@ def test_gemm_and_kv_reject_bad_arguments_on_the_host():
     assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 4, 0, None) == -2                  # ldy < N
     assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 8, 7, None) == -2                  # bad dtype
     assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 10, 0, None) == -3                 # ldy % 4
+    a64, w64 = _t(rows=4, K=64), _t(rows=8, K=64)                                                 # a shape the tiled kernels take
+    assert L.nvfp4_gemm(ctypes.byref(a64), ctypes.byref(w64), y, 12, 1, None) == -3              # bf16 rows must stay 16-byte aligned: ldy % 8
     # LoRA branch: rank-128 operands are required; the fused call only takes tiled shapes
     tb = ctypes.c_void_p(0x80000)
     lw = ctypes.c_void_p(0x90000)

@@ -433,6 +433,113 @@ def test_four_over_six_never_worse_and_brute(oracle):
     assert (q46.codes[same] == q6.codes[same]).all()
 
 
+def _four_over_six_brute(xb, gs_in=None):
+    """Appendix Eq. 12-13 in exact rationals, independent of the oracle: for every block BOTH
+    candidates (block maximum mapped to 6 and to 4) are encoded in distance-argmin form, their
+    squared errors sum_j (|x_j| - m_j s_b s_g)^2 are formed exactly, and the 4-based candidate is
+    taken only when its error is strictly smaller.  Returns codes, scales, the tensor scale, and
+    per block (err6, err4) as Fractions."""
+    x = wl.bf16_bits_to_f32(xb).astype(np.float64)
+    R, K = x.shape
+    amax = Fraction(float(np.abs(x).max()))
+    sg = np.float32(gs_in) if gs_in is not None else (np.float32(1.0) if amax == 0 else _fp32_nearest(amax / 2688))
+    sgF = Fraction(float(sg))
+    e4 = [Fraction(float(v)) for v in E4M3_VALUES[:127]]
+    mags = [Fraction(v) for v in _gold_e2m1()]
+    codes = np.zeros((R, K // 2), np.uint8)
+    scales = np.zeros((R, K // 16), np.uint8)
+    errs = {}
+    for r in range(R):
+        for b in range(K // 16):
+            blk = x[r, b * 16:(b + 1) * 16]
+            ax = [Fraction(float(abs(v))) for v in blk]
+            bmax = max(ax)
+            cand = []
+            for target in (6, 4):
+                sb = _nearest_brute(e4, bmax / (target * sgF))
+                den = e4[sb] * sgF
+                idx = [0 if den == 0 else _nearest_brute(mags, a / den) for a in ax]
+                err = sum((a - mags[i] * den) ** 2 for a, i in zip(ax, idx))
+                cand.append((sb, idx, err))
+            pick = 1 if cand[1][2] < cand[0][2] else 0          # equal errors keep the 6-based encoding
+            errs[(r, b)] = (cand[0][2], cand[1][2])
+            scales[r, b] = cand[pick][0]
+            for j, i in enumerate(cand[pick][1]):
+                c = i | (8 if np.signbit(blk[j]) else 0)
+                codes[r, b * 8 + j // 2] |= c << (4 * (j % 2))
+    return codes, scales, sg, errs
+
+
+def _four_over_six_cases():
+    g = np.random.default_rng(46)
+    act = wl.bf16_bits_to_f32(wl.config2(seed=1, M=12)["A"][:, :192])          # N(0,1), outlier channels x20
+    kv = wl.bf16_bits_to_f32(wl.kv_tensor(2, 6, 128, 4, 0).reshape(12, 128))   # per-head scales
+    grad = (g.standard_normal((6, 96)) * 1e-3).astype(np.float32)              # gradient-sized values
+    # values on a coarse grid: many blocks where both candidates reconstruct exactly or equally badly
+    grid = (g.integers(-12, 13, size=(8, 96)) * 0.25).astype(np.float32)
+    grid[0, :16] = 0.0                                                         # a zero block
+    grid[1, 16:32] = 0.0
+    grid[1, 16] = 3.0                                                          # a lone maximum
+    grid[2, 32:48] = np.float32(1.5)                                           # a constant block
+    spread = (g.standard_normal((4, 64)) * np.exp2(g.integers(-12, 4, size=(4, 64)))).astype(np.float32)
+    # exact ties between two DIFFERENT encodings: with the tensor maximum 2688 the tensor scale is 1, and a
+    # block whose values are 6 v, 3 v, ... for an E4M3 value v is reconstructed without error on scale v
+    # (target 6) and on scale 1.5 v (target 4) alike
+    lone = np.zeros((4, 128), np.float32)
+    lone[0, 0] = 2688.0
+    for b, v in enumerate([1.0, 2.0, 0.5, 16.0, 0.25, 1.25, 40.0]):
+        lone[1, 16 * b] = 6.0 * v                     # a lone maximum
+        lone[2, 16 * b: 16 * b + 3] = [6.0 * v, -3.0 * v, 1.5 * v]
+        lone[3, 16 * b: 16 * b + 16] = 6.0 * v        # a constant block
+    return [("activations", act, None), ("kv", kv, None), ("gradients", grad, None), ("grid", grid, None),
+            ("wide dynamic range", spread, None), ("exact ties", lone, None),
+            # tensor scales given by the caller: block scales that saturate at 448, and that underflow
+            ("given scale, saturating", act[:3, :64], np.float32(2.0 ** -14)),
+            ("given scale, underflowing", grad[:3, :64], np.float32(8.0))]
+
+
+def test_four_over_six_both_candidates_in_exact_rationals(oracle):
+    """Every block of several seeded tensors: the oracle's scale byte and all sixteen codes equal
+    those of the candidate that an exact evaluation of both encodings and both squared errors
+    selects (Appendix Eq. 12-13).  A search that is biased towards 6, that compares with <= instead
+    of <, or that mis-encodes the codes of the blocks it switches, fails here."""
+    switched = ties = total = 0
+    for name, x, gs in _four_over_six_cases():
+        xb = wl.to_bf16_bits(np.ascontiguousarray(x, dtype=np.float32))
+        q = oracle.quantize(xb, four_over_six=True, global_scale_in=gs)
+        codes, scales, sg, errs = _four_over_six_brute(xb, gs)
+        assert q.global_scale == sg, name
+        bad = np.argwhere(q.scales != scales)
+        assert bad.size == 0, f"{name}: scale byte of block {tuple(bad[0])}: oracle {q.scales[tuple(bad[0])]:#x}, " \
+                              f"exact {scales[tuple(bad[0])]:#x}, errors (6, 4) = {[float(e) for e in errs[tuple(bad[0])]]}"
+        assert (q.codes == codes).all(), name
+        e6 = np.array([[float(errs[(r, b)][0]) for b in range(scales.shape[1])] for r in range(scales.shape[0])])
+        e4 = np.array([[float(errs[(r, b)][1]) for b in range(scales.shape[1])] for r in range(scales.shape[0])])
+        switched += int(sum(1 for v in errs.values() if v[1] < v[0]))
+        ties += int(sum(1 for v in errs.values() if v[1] == v[0]))
+        total += len(errs)
+        assert np.isfinite(e6).all() and np.isfinite(e4).all()
+    # the cases exercise all three outcomes many times over
+    assert switched > 100 and ties > 20 and total - switched - ties > 100, (switched, ties, total)
+
+
+def test_four_over_six_exact_ties_between_different_encodings(oracle):
+    """Blocks that both targets reconstruct without error, on different scales: the 6-based encoding
+    stays (a search that takes the 4-based candidate on equal error changes these bytes)."""
+    name, x, gs = [c for c in _four_over_six_cases() if c[0] == "exact ties"][0]
+    xb = wl.to_bf16_bits(x)
+    q = oracle.quantize(xb, four_over_six=True)
+    codes, scales, sg, errs = _four_over_six_brute(xb)
+    differing_ties = 0
+    for (r, b), (e6, e4) in errs.items():
+        if e6 == e4 and r >= 1 and b < 7:
+            differing_ties += 1
+            assert e6 == 0
+    assert differing_ties >= 15
+    assert (q.scales == scales).all() and (q.codes == codes).all()
+    assert (q.scales == oracle.quantize(xb).scales).all()          # i.e. exactly the plain max -> 6 rule here
+
+
 def test_four_over_six_equal_error_keeps_six(oracle):
     """A block holding only its maximum is exact under both targets; the reading keeps 6."""
     x = np.zeros((1, 32), np.float32)
