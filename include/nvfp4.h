@@ -75,7 +75,8 @@ enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2
        NVFP4_OP_QUANTIZE_4OVER6 = 6, NVFP4_OP_KV_QUANT_4OVER6 = 7, NVFP4_OP_KV_QUANT_K = 8,
        NVFP4_OP_KV_DEQUANT_GATHER = 9, NVFP4_OP_QUANTIZE_2D = 10,
        NVFP4_OP_QUANTIZE_RHT = 11, NVFP4_OP_QUANTIZE_A2A = 12,
-       NVFP4_OP_LORA_DOWN = 13, NVFP4_OP_GEMM_LORA = 14 };
+       NVFP4_OP_LORA_DOWN = 13, NVFP4_OP_GEMM_LORA = 14,
+       NVFP4_OP_PROBE = 15 /* timing only: nvfp4_probe */ };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
@@ -330,6 +331,20 @@ const char *nvfp4_status_string(int status);
 void nvfp4_set_timing(int enabled);
 void nvfp4_set_timing_ops(uint32_t op_mask);
 int  nvfp4_timing_read(int op, int *calls, float *total_ms);
+
+/* Every recorded duration of entry point `op`, in call order: up to max_records values in ms_out
+ * (host pointer); returns how many were written, or a negative status.  Waits for the events. */
+int  nvfp4_timing_read_all(int op, float *ms_out, int max_records);
+
+/* Ceiling probes for benchmarks (no part of the NVFP4 path): what the GPU sustains on plain
+ * streaming kernels and on back-to-back matrix instructions, to set the library's kernels against.
+ *   kind 0: read `bytes` of a once (b: a sink of >= 8 KB, practically never written)
+ *   kind 1: write `bytes` to b          kind 2: copy `bytes` from a to b
+ *   kind 3: 256 workgroups x 4 waves, each `iters` x 64 v_mfma_f32_32x32x16_f16 on register-resident
+ *           pseudo-random operands (b: a sink of >= 256 KB, practically never written);
+ *           flops of one call = 256 * 4 * iters * 64 * 32768
+ * a, b: device, 16-byte aligned; bytes a multiple of 16.  Recorded by the launch timing as NVFP4_OP_PROBE. */
+int nvfp4_probe(int kind, const void *a, void *b, size_t bytes, int iters, void *stream);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,7 @@ OP_QUANTIZE, OP_KV_QUANT, OP_GEMM_ACT_QUANT, OP_GEMM, OP_KV_DEQUANT, OP_GEMM_ACT
 OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6, OP_KV_QUANT_K, OP_KV_DEQUANT_GATHER = 6, 7, 8, 9
 KV_MAX_CHUNKS = 64
 NOALLOC_MAX_ELEMENTS = 1 << 32
-OP_QUANTIZE_2D, OP_QUANTIZE_RHT, OP_QUANTIZE_A2A, OP_LORA_DOWN, OP_GEMM_LORA = 10, 11, 12, 13, 14
+OP_QUANTIZE_2D, OP_QUANTIZE_RHT, OP_QUANTIZE_A2A, OP_LORA_DOWN, OP_GEMM_LORA, OP_PROBE = 10, 11, 12, 13, 14, 15
 LORA_RANK = 128
 
 
@@ -90,6 +90,10 @@ def lib():
         L.nvfp4_set_timing_ops.argtypes = [c.c_uint32]
         L.nvfp4_timing_read.restype = c.c_int
         L.nvfp4_timing_read.argtypes = [c.c_int, c.POINTER(c.c_int), c.POINTER(c.c_float)]
+        L.nvfp4_timing_read_all.restype = c.c_int
+        L.nvfp4_timing_read_all.argtypes = [c.c_int, c.POINTER(c.c_float), c.c_int]
+        L.nvfp4_probe.restype = c.c_int
+        L.nvfp4_probe.argtypes = [c.c_int, vp, vp, sz, c.c_int, vp]
         _lib = L
     return _lib
 
@@ -370,6 +374,23 @@ def nvfp4_timing_read(op):
     n, ms = ctypes.c_int(0), ctypes.c_float(0)
     _check(lib().nvfp4_timing_read(op, ctypes.byref(n), ctypes.byref(ms)))
     return n.value, ms.value
+
+
+def nvfp4_timing_read_all(op, max_records=8192):
+    """-> list of the recorded durations (ms) of entry point `op`, in call order."""
+    buf = (ctypes.c_float * max_records)()
+    n = lib().nvfp4_timing_read_all(op, buf, max_records)
+    _check(min(n, 0))
+    return [buf[i] for i in range(n)]
+
+
+PROBE_READ, PROBE_WRITE, PROBE_COPY, PROBE_MFMA = 0, 1, 2, 3
+PROBE_MFMA_FLOPS_PER_ITER = 256 * 4 * 64 * 32768
+
+
+def nvfp4_probe(kind, a, b, nbytes=0, iters=0, stream=None):
+    """Ceiling probe (see include/nvfp4.h): a, b device tensors (a may be None for write / mfma)."""
+    _check(lib().nvfp4_probe(kind, _ptr(a), _ptr(b), int(nbytes), int(iters), _stream(stream)))
 
 
 def bf16_from_bits(bits_np, device="cuda"):

@@ -515,6 +515,33 @@ void nvfp4_set_timing_ops(uint32_t op_mask)
     g_used = 0;
 }
 
+int nvfp4_timing_read_all(int op, float *ms_out, int max_records)
+{
+    if (!ms_out || max_records < 0) return NVFP4_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_mu);
+    int n = 0;
+    for (int i = 0; i < g_used && n < max_records; ++i) {
+        if (g_pool[i].op != op) continue;
+        float ms = 0.0f;
+        if (hipEventSynchronize(g_pool[i].e1) != hipSuccess) return NVFP4_ERR_LAUNCH;
+        if (hipEventElapsedTime(&ms, g_pool[i].e0, g_pool[i].e1) != hipSuccess) return NVFP4_ERR_LAUNCH;
+        ms_out[n++] = ms;
+    }
+    return n;
+}
+
+int nvfp4_probe(int kind, const void *a, void *b, size_t bytes, int iters, void *stream)
+{
+    if (kind < 0 || kind > 3) return NVFP4_ERR_SHAPE;
+    if (!b || (kind != 1 && kind != 3 && !a)) return NVFP4_ERR_NULL;
+    if (kind == 3 ? iters <= 0 : (bytes == 0 || (bytes & 15) != 0)) return NVFP4_ERR_SHAPE;
+    if (!aligned16(a) || !aligned16(b)) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timed t(s, NVFP4_OP_PROBE);
+    return launch_probe(kind, a, b, (int64_t)bytes, iters, s) == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
 int nvfp4_timing_read(int op, int *calls, float *total_ms)
 {
     std::lock_guard<std::mutex> lk(g_mu);

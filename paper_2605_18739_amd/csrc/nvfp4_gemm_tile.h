@@ -485,8 +485,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
     // piece pc (0 .. 2 NF - 1) of sub-step j of register set `set`: half a fragment
     auto expand_piece = [&](int set, int j, int pc) {
         const int f = pc >> 1, hp = pc & 1;
+        // the block scale of this sub-step sits in the LOW half of scf (see shift_scale below): a packed multiply
+        // that broadcasts the low half of its first operand is the one form the compiler follows with an MFMA
+        // without a wait state in between
+        (void)j;
         const half2v sc = __builtin_bit_cast(half2v, scf[set][f]);
-        half2v p = (j >> 1) ? half2v{sc.y, sc.y} : half2v{sc.x, sc.x};
+        const half2v p = half2v{sc.x, sc.x};
         const uint32_t w = codes[set][f][j];
         const int d0 = 2 * hp, d1 = 2 * hp + 1;
         half2v e0 = hp ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2) : __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 0);
@@ -556,12 +560,25 @@ __global__ __launch_bounds__(NW * 64) void gemm_regdq_kernel(GemmArgs g)
                 acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, frag[j & 1][TM + i]),
                                                                      __builtin_bit_cast(half8v, frag[j & 1][jj]),
                                                                      acc[i][jj], 0, 0, 0);
+                // the MFMA stays first in its slot: left to itself the scheduler moves it behind the slot's copy
+                // instruction, and two MFMAs then issue back to back with nothing in the first one's shadow
+                __builtin_amdgcn_sched_barrier(0);
                 // next sub-step's fragments: 2 NF pieces dealt over the NMF MFMAs
                 static_for<0, 2 * NF>([&](auto pc_c) {
                     constexpr int pc = decltype(pc_c)::value;
                     if constexpr (pc * NMF / (2 * NF) == t) {
                         if constexpr (j < 3) expand_piece(set, j + 1, pc);
                         else expand_piece(set ^ 1, 0, pc);
+                    }
+                });
+                // scf[set][f] holds (scale of sub-steps 0, 1 | scale of sub-steps 2, 3); once the fragment's pieces for
+                // sub-step 1 are out (they are dealt during sub-step 0) the pair moves down by 16 bits, in place
+                static_for<0, NF>([&](auto f_c) {
+                    constexpr int f = decltype(f_c)::value;
+                    if constexpr (j == 0 && (2 * f + 1) * NMF / (2 * NF) == t) {
+                        uint32_t x = scf[set][f] >> 16;
+                        NVFP4_PIN1(x);
+                        scf[set][f] = x;
                     }
                 });
                 // fragment f of the next register step is read behind MFMA frag_slot(f) of sub-step 0

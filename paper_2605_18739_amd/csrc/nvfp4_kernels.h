@@ -54,6 +54,10 @@ struct KvChunkDesc { const uint8_t *codes, *scales; const float *global_scale; c
 hipError_t launch_dequant_gather(const KvChunkDesc *chunks, int n_chunks, int64_t H, int64_t d, uint16_t *out,
                                  hipStream_t s);
 
+// Ceiling probes (benchmark utilities): kind 0 read `bytes` of a (b: a sink of at least 8 KB), 1 write `bytes` to b,
+// 2 copy a -> b, 3 `iters` x 64 register-resident MFMAs per wave on 256 x 4 waves (b: a sink of at least 256 KB)
+hipError_t launch_probe(int kind, const void *a, void *b, int64_t bytes, int iters, hipStream_t s);
+
 // Epilogue of the GEMM
 struct GemmEpilogue {
     int out_dtype;            // 0 fp32, 1 bf16, 2 none (quantized output only)
