@@ -86,7 +86,10 @@ enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2
  *               re-quantized along its other axis, emitted K-contiguous, as
  *               the backward GEMMs need it).
  * global_scale_in: device pointer to one float, or NULL.  NULL: the scale is
- *               derived from the tensor's amax (one extra pass over x).  A
+ *               derived from the tensor's amax: contiguous row-block tensors of up
+ *               to ~120 MB are held on the chip between the two steps (one launch,
+ *               one pass over x; the launch occupies every compute unit while it
+ *               runs), larger or strided ones take one extra pass over x.  A
  *               tensor that is needed along both axes (every training operand
  *               is) has one amax: pass the first call's out->global_scale to
  *               the second call and its extra pass is saved.
@@ -331,6 +334,13 @@ const char *nvfp4_status_string(int status);
 void nvfp4_set_timing(int enabled);
 void nvfp4_set_timing_ops(uint32_t op_mask);
 int  nvfp4_timing_read(int op, int *calls, float *total_ms);
+
+/* The one-launch quantizers (tensors that fit on the chip) make the tensor maximum known to all
+ * workgroups through a grid-wide wait that is bounded: a workgroup that has waited longer than this
+ * many 10 ns ticks stops waiting and derives the maximum from the tensor itself (slow, same result).
+ * Default 200000 (2 ms); 0 makes every workgroup give up at once, which is how the tests exercise
+ * that path; 0xFFFFFFFF restores the default.  Applies to calls made afterwards. */
+void nvfp4_set_sync_spin_limit(uint32_t ticks_10ns);
 
 /* Every recorded duration of entry point `op`, in call order: up to max_records values in ms_out
  * (host pointer); returns how many were written, or a negative status.  Waits for the events. */

@@ -92,6 +92,8 @@ def lib():
         L.nvfp4_timing_read.argtypes = [c.c_int, c.POINTER(c.c_int), c.POINTER(c.c_float)]
         L.nvfp4_timing_read_all.restype = c.c_int
         L.nvfp4_timing_read_all.argtypes = [c.c_int, c.POINTER(c.c_float), c.c_int]
+        L.nvfp4_set_sync_spin_limit.restype = None
+        L.nvfp4_set_sync_spin_limit.argtypes = [c.c_uint32]
         L.nvfp4_probe.restype = c.c_int
         L.nvfp4_probe.argtypes = [c.c_int, vp, vp, sz, c.c_int, vp]
         _lib = L
@@ -374,6 +376,11 @@ def nvfp4_timing_read(op):
     n, ms = ctypes.c_int(0), ctypes.c_float(0)
     _check(lib().nvfp4_timing_read(op, ctypes.byref(n), ctypes.byref(ms)))
     return n.value, ms.value
+
+
+def nvfp4_set_sync_spin_limit(ticks_10ns=0xFFFFFFFF):
+    """Bound of the grid-wide wait of the one-launch quantizers (10 ns ticks; 0: give up at once; default: restore)."""
+    lib().nvfp4_set_sync_spin_limit(ticks_10ns)
 
 
 def nvfp4_timing_read_all(op, max_records=8192):

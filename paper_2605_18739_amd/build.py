@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnvfp4_hip.so")
 SOURCES = ["nvfp4_gemm_tile_256x256.hip", "nvfp4_gemm_tile_256x192.hip", "nvfp4_gemm_tile_128x128.hip",
-           "nvfp4_gemm_tile_64x64.hip", "nvfp4_quantize.hip", "nvfp4_gemm.hip", "nvfp4_probe.hip", "nvfp4_api.hip"]
+           "nvfp4_gemm_tile_64x64.hip", "nvfp4_quantize.hip", "nvfp4_quantize_resident.hip", "nvfp4_gemm.hip", "nvfp4_probe.hip", "nvfp4_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-FP32 instructions are kept out of every kernel
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -90,6 +90,12 @@ int quantize_impl(const void *x, int64_t R, int64_t C, int64_t ld, int block_axi
     const uint16_t *xb = static_cast<const uint16_t *>(x);
     uint32_t *partial = static_cast<uint32_t *>(ws);
     int n_partial = 0;
+    if (!gs_in && block_axis == 0 && quantize_rows_resident_fits(R, C, ld, false)) {
+        // the tensor fits on the chip: one launch, one pass over the input
+        hipError_t e = launch_quantize_rows_resident(xb, R, C, partial, out->codes, out->scales, out->global_scale,
+                                                     scale_search, nullptr, s);
+        return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+    }
     if (!gs_in) {
         if (launch_amax(xb, R, C, ld, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
     }
@@ -279,6 +285,11 @@ int nvfp4_kv_quant_k(const void *k_bf16, int64_t T, int64_t H, int64_t d, nvfp4_
     uint16_t *mean = static_cast<uint16_t *>(row_mean_bf16_out);
     uint32_t *partial = static_cast<uint32_t *>(workspace);
     int n_partial = 0;
+    if (quantize_rows_resident_fits(T * H, d, d, true)) {
+        hipError_t e = launch_quantize_rows_resident(x, T * H, d, partial, out->codes, out->scales, out->global_scale, true,
+                                                     mean, s);
+        return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+    }
     if (launch_amax_smooth(x, T * H, (int)d, mean, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
     hipError_t e = launch_quantize_rows_smooth(x, T * H, (int)d, mean, partial, n_partial, out->codes,
                                                out->scales, out->global_scale, s);
@@ -513,6 +524,12 @@ void nvfp4_set_timing_ops(uint32_t op_mask)
     std::lock_guard<std::mutex> lk(g_mu);
     g_timing = op_mask;
     g_used = 0;
+}
+
+void nvfp4_set_sync_spin_limit(uint32_t ticks_10ns)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    set_resident_spin_limit(ticks_10ns == 0xFFFFFFFFu ? 200000u : ticks_10ns);
 }
 
 int nvfp4_timing_read_all(int op, float *ms_out, int max_records)

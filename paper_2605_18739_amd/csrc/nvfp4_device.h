@@ -111,13 +111,50 @@ __device__ __forceinline__ double e2m1_midpoint(uint32_t i)
     return i < 4u ? 0.25 + 0.5 * (double)i : (i == 4u ? 2.5 : (i == 5u ? 3.5 : 5.0));
 }
 
-// Exact E2M1 decision for one element whose bracket ends gave neighbouring
-// indices lo < hi: compare |x| with midpoint * s_b * s_g (<= 3 + 4 + 24 bits).
-__device__ __forceinline__ uint32_t e2m1_resolve(float ax, uint32_t lo, uint32_t hi, double den)
+// Settle the nibbles on which the two ends of the bracket disagree.  l holds the codes of the lower end, h of the
+// upper end (neighbouring magnitudes, same sign).  Such an element lies within 2^-19 of the midpoint T between the
+// two magnitudes times s_b s_g, and which side it lies on is the sign of  T s_b s_g - |x|:  c = T s_b is exact in
+// fp32 (3 + 4 bits), the fused multiply-add rounds c s_g - |x| once, and because the two terms nearly cancel
+// (the difference has at most 12 significant bits) that one rounding is exact.  Tensor scales so small that the
+// difference could leave the normal range take the same comparison in fp64.  A tie goes to the even code.
+// One nibble per pass of the loop; a wave runs as many passes as its busiest lane needs (rarely more than two).
+__device__ __forceinline__ void resolve_codes(const uint32_t (&w)[8], float sb, float sg, uint32_t &l0, uint32_t &l1,
+                                              uint32_t h0, uint32_t h1)
 {
-    double t = e2m1_midpoint(lo) * den;
-    double a = (double)ax;
-    return (a > t) ? hi : ((a < t) ? lo : ((lo & 1u) ? hi : lo));
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    uint32_t d0 = l0 ^ h0, d1 = l1 ^ h1;
+    const bool wide = sg >= 0x1p-80f;                                      // (the same for every lane)
+    while (__builtin_expect((d0 | d1) != 0u, 0)) {                         // (selects, no branches, inside)
+        const bool first = d0 != 0u;
+        const uint32_t d = first ? d0 : d1, lw = first ? l0 : l1;
+        const uint32_t sh = (uint32_t)__builtin_ctz(d) & 28u;              // bit position of the nibble in its word
+        const bool odd = (sh & 8u) != 0u, upper = (sh & 16u) != 0u;        // which of the word's four bf16 pairs
+        const uint32_t w01 = odd ? w[1] : w[0], w23 = odd ? w[3] : w[2];
+        const uint32_t w45 = odd ? w[5] : w[4], w67 = odd ? w[7] : w[6];
+        const uint32_t wlo = upper ? w23 : w01, whi = upper ? w67 : w45;
+        const uint32_t ww = first ? wlo : whi;
+        const float ax = __uint_as_float((ww >> ((sh & 4u) << 2) << 16) & 0x7FFF0000u);
+        const uint32_t lo = (lw >> sh) & 7u;
+        const float2v m = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(lo | ((lo + 1u) << 4), 1.0f, 0);
+        const float c = (0.5f * (m.x + m.y)) * sb;                         // midpoint times block scale, exact
+        bool above, equal;
+        if (wide) {
+            const float t = __builtin_fmaf(c, sg, -ax);
+            above = t < 0.0f;
+            equal = t == 0.0f;
+        } else {
+            const double t = (double)c * (double)sg, a = (double)ax;
+            above = a > t;
+            equal = a == t;
+        }
+        const bool up = above | (equal & ((lo & 1u) != 0u));
+        const uint32_t nib = d & (0xFu << sh);
+        const uint32_t nw = lw ^ (up ? nib : 0u), nd = d ^ nib;
+        l0 = first ? nw : l0;
+        l1 = first ? l1 : nw;
+        d0 = first ? nd : d0;
+        d1 = first ? d1 : nd;
+    }
 }
 
 // 16 consecutive bf16 (8 dwords) -> 16 E2M1 codes (2 dwords) on the scale
@@ -139,22 +176,7 @@ __device__ __forceinline__ void encode_block16(const uint32_t (&w)[8], float sb,
     NVFP4_CVT(l0, h0, w[0], 0) NVFP4_CVT(l0, h0, w[1], 1) NVFP4_CVT(l0, h0, w[2], 2) NVFP4_CVT(l0, h0, w[3], 3)
     NVFP4_CVT(l1, h1, w[4], 0) NVFP4_CVT(l1, h1, w[5], 1) NVFP4_CVT(l1, h1, w[6], 2) NVFP4_CVT(l1, h1, w[7], 3)
 #undef NVFP4_CVT
-    if (__builtin_expect((l0 != h0) | (l1 != h1), 0)) {
-        double den = (double)sb * (double)sg;      // exact
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            uint32_t &L = (j < 8) ? l0 : l1;
-            uint32_t H = (j < 8) ? h0 : h1;
-            int sh = 4 * (j & 7);
-            uint32_t a = (L >> sh) & 7u, b = (H >> sh) & 7u;
-            if (a != b) {
-                uint32_t ww = w[j >> 1];
-                float ax = fabsf((j & 1) ? bf16hi_to_f32(ww) : bf16lo_to_f32(ww));
-                uint32_t r = e2m1_resolve(ax, a, b, den);
-                L = (L & ~(7u << sh)) | (r << sh);
-            }
-        }
-    }
+    resolve_codes(w, sb, sg, l0, l1, h0, h1);
     c0 = l0;
     c1 = l1;
 }
@@ -199,6 +221,28 @@ __device__ __forceinline__ double block_error_f64(const uint32_t (&w)[8], uint32
     return err;
 }
 
+// The same sum, operation for operation, as a rolled loop: a few dozen instructions instead of several hundred,
+// for callers that inline the fallback many times and take it rarely.
+__device__ __forceinline__ double block_error_f64_rolled(const uint32_t (&w)[8], uint32_t c0, uint32_t c1, float sb, float sg)
+{
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    const double den = (double)sb * (double)sg;     // exact
+    double err = 0.0;
+#pragma unroll 1
+    for (uint32_t j = 0; j < 16; ++j) {
+        const bool odd = (j & 2u) != 0u, upper = (j & 4u) != 0u, second = (j & 8u) != 0u;
+        const uint32_t w01 = odd ? w[1] : w[0], w23 = odd ? w[3] : w[2], w45 = odd ? w[5] : w[4], w67 = odd ? w[7] : w[6];
+        const uint32_t wlo = upper ? w23 : w01, whi = upper ? w67 : w45;
+        const uint32_t ww = second ? whi : wlo;
+        const double a = (double)__uint_as_float((ww >> ((j & 1u) << 4) << 16) & 0x7FFF0000u);
+        const uint32_t idx = ((second ? c1 : c0) >> (4u * (j & 7u))) & 7u;
+        const float2v m = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(idx, 1.0f, 0);       // the code's magnitude, exact
+        const double d = __dsub_rn(a, __dmul_rn((double)m.x, den));
+        err = __dadd_rn(err, __dmul_rn(d, d));
+    }
+    return err;
+}
+
 // Scale search for one block: encode with the block maximum mapped to 6 and to 4, keep the
 // encoding with the strictly smaller squared error (equal errors keep 6).  The fp32 errors
 // decide whenever they differ by more than their own uncertainty; otherwise fp64 does.
@@ -236,6 +280,235 @@ __device__ __forceinline__ void encode_block16_4over6(const uint32_t (&w)[8], fl
         c0 = b0;
         c1 = b1;
     }
+}
+
+// ---- fp64 forms for tensor scales outside the range in which the fp32 quotients above are safe
+// (global scales below 2^-100 or above 2^100: the reciprocal 1 / (M s_g) or the products s_b s_g
+// leave the normal fp32 range).  Every decision by cross-multiplication in fp64, which has the
+// exponent range to spare; slow, and only ever taken for such tensors.
+__device__ __forceinline__ bool scale_needs_f64(float sg) { return !(sg >= 0x1p-100f && sg <= 0x1p100f); }
+
+__device__ inline uint32_t block_scale_f64(float bmax, float sg, double target)
+{
+    const double num = (double)bmax, den = target * (double)sg;       // exact (2 + 24 bits)
+    uint32_t lo = 0, hi = 126;                                        // the answer lies in [lo, hi]
+    while (lo < hi) {
+        const uint32_t m = (lo + hi) >> 1;
+        const double t = 0.5 * ((double)e4m3_to_f32(m) + (double)e4m3_to_f32(m + 1)) * den;   // exact (5 + 26 bits)
+        if (num > t || (num == t && (m & 1u))) lo = m + 1;            // a tie goes to the even byte
+        else hi = m;
+    }
+    return lo;
+}
+
+__device__ inline void encode_block16_f64(const uint32_t (&w)[8], float sb, float sg, uint32_t &c0, uint32_t &c1)
+{
+    const double den = (double)sb * (double)sg;                       // exact
+    uint32_t out[2] = {0, 0};
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const uint32_t ww = w[j >> 1];
+        const float x = (j & 1) ? bf16hi_to_f32(ww) : bf16lo_to_f32(ww);
+        const double a = (double)fabsf(x);
+        uint32_t idx = 7;
+        if (den == 0.0) idx = 0;
+        else {
+#pragma unroll
+            for (int i = 6; i >= 0; --i) {
+                const double t = e2m1_midpoint((uint32_t)i) * den;
+                if (a < t || (a == t && !(i & 1))) idx = (uint32_t)i;   // below the midpoint, or on it with the lower index even
+            }
+        }
+        out[j >> 3] |= (idx | ((__float_as_uint(x) >> 28) & 8u)) << (4 * (j & 7));
+    }
+    c0 = out[0];
+    c1 = out[1];
+}
+
+// ---- straight-line forms for kernels that hold many blocks per lane -------------------------------
+// The functions above take one block from start to end.  The forms below run two independent chains of
+// work through one stretch of code -- two blocks for the plain rule, the two candidates of one block for
+// the scale search -- so that the latency of one chain's dependent instructions (a conversion writes one
+// byte of its destination, so the four that fill a code word wait on one another) hides behind the other.
+// The results are the exact ones: the common case is decided by fp32 arithmetic alone, and the rare
+// near-tie drops into the same exact resolution the functions above use.
+
+// Block scale byte for quotient q = bmax * inv_msg in the normal E4M3 range, by integer arithmetic on
+// the bits of q.  "unsure" is raised when q lies within 24 ulps of a rounding tie (the true quotient lies
+// within 16 ulps of q), below the normal range (subnormal scales, zero blocks), or is not an ordinary
+// number; the caller then calls block_scale_exact.
+__device__ __forceinline__ uint32_t block_scale_fast(float q, bool &unsure)
+{
+    q = fminf(q, kFp8Max);
+    const uint32_t u = __float_as_uint(q);
+    const uint32_t b = ((u + 0x7FFFFu + ((u >> 20) & 1u)) >> 20) - 960u;
+    unsure = ((u & 0xFFFFFu) - (0x80000u - 24u) <= 48u) | !(q >= 0.015625f * 1.0001f);
+    return b;
+}
+
+// E4M3 byte (normal range, as block_scale_fast returns it) -> f32, one instruction
+__device__ __forceinline__ float e4m3_normal_to_f32(uint32_t b) { return __uint_as_float((b << 20) + (120u << 23)); }
+
+// largest magnitude of 16 bf16 values as a float (exact: a maximum of exact values)
+__device__ __forceinline__ float block_absmax_f32(const uint32_t (&w)[8])
+{
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m = fmaxf(fmaxf(fabsf(bf16lo_to_f32(w[i])), fabsf(bf16hi_to_f32(w[i]))), m);
+    return m;
+}
+
+// sixteen values -> their largest magnitude through a tree of three-operand maxima (depth 3 instead of 8)
+__device__ __forceinline__ float absmax16_tree(const float (&f)[16])
+{
+    auto m3 = [](float a, float b, float c) { return fmaxf(fmaxf(fabsf(a), fabsf(b)), fabsf(c)); };
+    const float t0 = m3(f[0], f[1], f[2]), t1 = m3(f[3], f[4], f[5]), t2 = m3(f[6], f[7], f[8]);
+    const float t3 = m3(f[9], f[10], f[11]), t4 = m3(f[12], f[13], f[14]);
+    return fmaxf(m3(t0, t1, t2), m3(t3, t4, f[15]));
+}
+
+__device__ __forceinline__ void unpack16(const uint32_t (&w)[8], float (&f)[16])
+{
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        f[2 * i] = bf16lo_to_f32(w[i]);
+        f[2 * i + 1] = bf16hi_to_f32(w[i]);
+    }
+}
+
+// Scale byte, its value and the reciprocal of s_b s_g for one block (target magnitude M = 6 or 4).
+__device__ __forceinline__ void block_scale_inline(float bmax, float sg, float inv_msg, double target, uint32_t &sbyte,
+                                                   float &sb, float &inv)
+{
+    bool unsure;
+    sbyte = block_scale_fast(bmax * inv_msg, unsure);
+    sb = e4m3_normal_to_f32(sbyte);
+    inv = __builtin_amdgcn_rcpf(sb * sg);
+    if (__builtin_expect(unsure, 0)) {
+        sbyte = block_scale_exact(bmax, sg, inv_msg, target);
+        sb = e4m3_to_f32(sbyte);
+        inv = (sb == 0.0f) ? 0.0f : __builtin_amdgcn_rcpf(sb * sg);
+    }
+}
+
+// one step of four conversions: pair K of the block(s) into byte K % 4 of code word K / 4, for four chains
+#define NVFP4_CVT4(K, SEL, A, FA, MA, B, FB, MB, C, FC, MC, D, FD, MD)                                              \
+    A[K >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(A[K >> 2], FA[2 * K] * MA, FA[2 * K + 1] * MA, 1.0f, SEL);  \
+    B[K >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(B[K >> 2], FB[2 * K] * MB, FB[2 * K + 1] * MB, 1.0f, SEL);  \
+    C[K >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(C[K >> 2], FC[2 * K] * MC, FC[2 * K + 1] * MC, 1.0f, SEL);  \
+    D[K >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(D[K >> 2], FD[2 * K] * MD, FD[2 * K + 1] * MD, 1.0f, SEL);
+
+// Plain rule (Eq. 1: block maximum -> 6) on two blocks side by side; the results of quantize_block16_exact
+// for tensor scales inside the fp32-safe range.
+__device__ __forceinline__ void quantize_pair16(const uint32_t (&wa)[8], const uint32_t (&wb)[8], float sg, float inv_6sg,
+                                                uint32_t &sa, uint32_t &a0, uint32_t &a1,
+                                                uint32_t &sb, uint32_t &b0, uint32_t &b1)
+{
+    float fa[16], fb[16];
+    unpack16(wa, fa);
+    unpack16(wb, fb);
+    float sva, svb, inva, invb;
+    block_scale_inline(absmax16_tree(fa), sg, inv_6sg, 6.0, sa, sva, inva);
+    block_scale_inline(absmax16_tree(fb), sg, inv_6sg, 6.0, sb, svb, invb);
+    const float ila = inva * kBracketLo, iha = inva * kBracketHi, ilb = invb * kBracketLo, ihb = invb * kBracketHi;
+    uint32_t la[2] = {0, 0}, ha[2] = {0, 0}, lb[2] = {0, 0}, hb[2] = {0, 0};
+#define NVFP4_STEP(K, SEL) NVFP4_CVT4(K, SEL, la, fa, ila, ha, fa, iha, lb, fb, ilb, hb, fb, ihb)
+    NVFP4_STEP(0, 0) NVFP4_STEP(1, 1) NVFP4_STEP(2, 2) NVFP4_STEP(3, 3)
+    NVFP4_STEP(4, 0) NVFP4_STEP(5, 1) NVFP4_STEP(6, 2) NVFP4_STEP(7, 3)
+#undef NVFP4_STEP
+    resolve_codes(wa, sva, sg, la[0], la[1], ha[0], ha[1]);
+    resolve_codes(wb, svb, sg, lb[0], lb[1], hb[0], hb[1]);
+    a0 = la[0]; a1 = la[1];
+    b0 = lb[0]; b1 = lb[1];
+}
+
+// Scale search (Eq. 12-13) on one block, the two candidates side by side; the results of
+// quantize_block16_4over6_exact for tensor scales inside the fp32-safe range.  The fp32 squared errors
+// are summed in four partial sums (the bound r of encode_block16_4over6 holds for any order of summation).
+__device__ __forceinline__ void quantize_block16_4over6_inline(const uint32_t (&w)[8], float sg, float inv_6sg, float inv_4sg,
+                                                               uint32_t &sbyte, uint32_t &c0, uint32_t &c1)
+{
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    float f[16];
+    unpack16(w, f);
+    const float bmax = absmax16_tree(f);
+    uint32_t s6, s4;
+    float sb6, sb4, inv6, inv4;
+    block_scale_inline(bmax, sg, inv_6sg, 6.0, s6, sb6, inv6);
+    block_scale_inline(bmax, sg, inv_4sg, 4.0, s4, sb4, inv4);
+    const float il6 = inv6 * kBracketLo, ih6 = inv6 * kBracketHi, il4 = inv4 * kBracketLo, ih4 = inv4 * kBracketHi;
+    uint32_t l6[2] = {0, 0}, h6[2] = {0, 0}, l4[2] = {0, 0}, h4[2] = {0, 0};
+#define NVFP4_STEP(K, SEL) NVFP4_CVT4(K, SEL, l6, f, il6, h6, f, ih6, l4, f, il4, h4, f, ih4)
+    NVFP4_STEP(0, 0) NVFP4_STEP(1, 1) NVFP4_STEP(2, 2) NVFP4_STEP(3, 3)
+    NVFP4_STEP(4, 0) NVFP4_STEP(5, 1) NVFP4_STEP(6, 2) NVFP4_STEP(7, 3)
+#undef NVFP4_STEP
+    resolve_codes(w, sb6, sg, l6[0], l6[1], h6[0], h6[1]);
+    resolve_codes(w, sb4, sg, l4[0], l4[1], h4[0], h4[1]);
+    const float den6 = sb6 * sg, den4 = sb4 * sg;
+    float e6a = 0.0f, e6b = 0.0f, e4a = 0.0f, e4b = 0.0f;
+#define NVFP4_STEP(K, SEL)                                                                                        \
+    {                                                                                                             \
+        const float2v q6 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(l6[K >> 2], 1.0f, SEL);                       \
+        const float2v q4 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(l4[K >> 2], 1.0f, SEL);                       \
+        const float d60 = __builtin_fmaf(-q6.x, den6, f[2 * K]), d61 = __builtin_fmaf(-q6.y, den6, f[2 * K + 1]); \
+        const float d40 = __builtin_fmaf(-q4.x, den4, f[2 * K]), d41 = __builtin_fmaf(-q4.y, den4, f[2 * K + 1]); \
+        e6a = __builtin_fmaf(d60, d60, e6a);                                                                      \
+        e6b = __builtin_fmaf(d61, d61, e6b);                                                                      \
+        e4a = __builtin_fmaf(d40, d40, e4a);                                                                      \
+        e4b = __builtin_fmaf(d41, d41, e4b);                                                                      \
+    }
+    NVFP4_STEP(0, 0) NVFP4_STEP(1, 1) NVFP4_STEP(2, 2) NVFP4_STEP(3, 3)
+    NVFP4_STEP(4, 0) NVFP4_STEP(5, 1) NVFP4_STEP(6, 2) NVFP4_STEP(7, 3)
+#undef NVFP4_STEP
+    const float e6 = e6a + e6b, e4 = e4a + e4b;
+    const float u6 = 0x1p-22f * (bmax + 6.0f * den6), u4 = 0x1p-22f * (bmax + 6.0f * den4);
+    const float r6 = u6 * (8.02f * __builtin_amdgcn_sqrtf(e6) + 16.0f * u6) + 0x1p-19f * e6;   // (eight fused steps and one
+    const float r4 = u4 * (8.02f * __builtin_amdgcn_sqrtf(e4) + 16.0f * u4) + 0x1p-19f * e4;   //  addition: below 2^-19 as well)
+    const bool tiny = fminf(e4, e6) < 0x1p-100f;
+    const bool same = s4 == s6;                    // (saturated scales, zero blocks: same codes, same error, 6 is kept)
+    bool pick4 = e4 + r4 < e6 - r6;
+    if (__builtin_expect(!same & (tiny | !(pick4 | (e4 - r4 > e6 + r6))), 0))
+        pick4 = block_error_f64_rolled(w, l4[0], l4[1], sb4, sg) < block_error_f64_rolled(w, l6[0], l6[1], sb6, sg);
+    pick4 &= !same;
+    sbyte = pick4 ? s4 : s6;
+    c0 = pick4 ? l4[0] : l6[0];
+    c1 = pick4 ? l4[1] : l6[1];
+}
+#undef NVFP4_CVT4
+
+// the one-block-at-a-time counterparts for any tensor scale (the fp64 forms when the scale needs them)
+__device__ __forceinline__ void quantize_block16_exact(const uint32_t (&w)[8], float sg, float inv_6sg, uint32_t &sbyte,
+                                                       uint32_t &c0, uint32_t &c1)
+{
+    const float bmax = block_absmax_f32(w);
+    if (__builtin_expect(scale_needs_f64(sg), 0)) {
+        sbyte = block_scale_f64(bmax, sg, 6.0);
+        encode_block16_f64(w, e4m3_to_f32(sbyte), sg, c0, c1);
+        return;
+    }
+    sbyte = block_scale_exact(bmax, sg, inv_6sg);
+    encode_block16(w, e4m3_to_f32(sbyte), sg, c0, c1);
+}
+
+__device__ __forceinline__ void quantize_block16_4over6_exact(const uint32_t (&w)[8], float sg, float inv_6sg, float inv_4sg,
+                                                              uint32_t &sbyte, uint32_t &c0, uint32_t &c1)
+{
+    const float bmax = block_absmax_f32(w);
+    if (__builtin_expect(scale_needs_f64(sg), 0)) {
+        const uint32_t s6 = block_scale_f64(bmax, sg, 6.0), s4 = block_scale_f64(bmax, sg, 4.0);
+        encode_block16_f64(w, e4m3_to_f32(s6), sg, c0, c1);
+        sbyte = s6;
+        if (s4 == s6) return;
+        uint32_t b0, b1;
+        encode_block16_f64(w, e4m3_to_f32(s4), sg, b0, b1);
+        if (block_error_f64(w, b0, b1, e4m3_to_f32(s4), sg) < block_error_f64(w, c0, c1, e4m3_to_f32(s6), sg)) {
+            sbyte = s4;
+            c0 = b0;
+            c1 = b1;
+        }
+        return;
+    }
+    encode_block16_4over6(w, bmax, sg, inv_6sg, inv_4sg, sbyte, c0, c1);
 }
 
 // Round a non-negative exact product held in a double to bf16 once (nearest

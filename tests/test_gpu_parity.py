@@ -179,6 +179,37 @@ def test_quantize_more_than_2_to_31_elements(oracle):
     torch.cuda.empty_cache()
 
 
+def test_quantize_one_launch_path_with_and_without_the_grid_wide_wait(oracle):
+    """Tensors that fit on the chip are quantized by one launch whose workgroups exchange their maxima through
+    a bounded grid-wide wait.  With the bound set to zero from the host every workgroup gives up at once and
+    derives the tensor maximum from the tensor itself: same bytes, every kernel still ends normally.  Sizes: one
+    workgroup; many workgroups, one block per lane with a ragged tail; several register slots; register and
+    LDS slots together (more than 20 blocks per lane on 256 workgroups)."""
+    g = np.random.default_rng(2024)
+    cases = [(40, 208), (1000, 1040), (3520, 3072), (22000, 2048)]
+    tensors = []
+    for R, C in cases:
+        x = g.standard_normal((R, C)).astype(np.float32)
+        x[g.integers(0, R), g.integers(0, C)] = 300.0          # the tensor maximum sits in ONE workgroup's slice
+        tensors.append(wl.to_bf16_bits(x))
+    want = [(oracle.quantize(b), oracle.quantize(b, four_over_six=True)) for b in tensors]
+    kb = wl.to_bf16_bits(wl.bf16_bits_to_f32(wl.kv_tensor(300, 24, 128, 8, 1)).reshape(7200, 128) + np.float32(1.5))
+    want_k = _oracle_k_path(oracle, kb)
+    for limit in (None, 0):
+        say(f"[one launch] wait bound {'default' if limit is None else limit}")
+        if limit is not None:
+            nv.nvfp4_set_sync_spin_limit(limit)
+        try:
+            for b, (w6, w46) in zip(tensors, want):
+                assert_q_equal(nv.nvfp4_quantize(dev_bf16(b)), w6, f"plain {b.shape} limit {limit}")
+                assert_q_equal(nv.nvfp4_quantize_4over6(dev_bf16(b)), w46, f"search {b.shape} limit {limit}")
+            gq, gm = nv.nvfp4_kv_quant_k(dev_bf16(kb).reshape(300, 24, 128))
+            assert (nv.bits_from_bf16(gm) == want_k[0]).all()
+            assert_q_equal(gq, want_k[1], f"smoothed keys limit {limit}")
+        finally:
+            nv.nvfp4_set_sync_spin_limit()                     # back to the default bound
+
+
 def test_quantize_is_deterministic():
     xb = wl.activation_with_outliers(512, 3072, 1, 0)
     x = dev_bf16(xb)
