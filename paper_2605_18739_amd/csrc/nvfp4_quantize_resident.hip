@@ -128,13 +128,12 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
     const Pass2Out out{__builtin_amdgcn_make_buffer_rsrc((void *)a.codes, 0, (int)(a.nblk << 3), 0x00020000),
                        __builtin_amdgcn_make_buffer_rsrc((void *)a.scales, 0, (int)a.nblk, 0x00020000)};
     const int tid = threadIdx.x, G = gridDim.x;
-#ifdef RES_CLOCKS
-    const uint64_t rc0 = wall_clock64();
-#endif
     const int64_t wg_first = (int64_t)blockIdx.x * kResThreads + tid;  // block index in slot 0
     const int64_t slot_stride = (int64_t)G * kResThreads;
     const int nr = min(a.nb, kResRegSlots), nl = a.nb - nr;            // register slots / LDS slots in use
     auto block_of = [&](int slot) { return wg_first + (int64_t)slot * slot_stride; };
+    uint32_t *queue_head = lds_red + 12;                               // tickets for the LDS slots in pass 2
+    if (tid == 0) *queue_head = 0;
 
     // ---- pass 1: load every block once; registers first (all loads in flight together), then LDS slots
     uint4v r0[kResRegSlots], r1[kResRegSlots];
@@ -187,9 +186,6 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
         }
     });
 
-#ifdef RES_CLOCKS
-    const uint64_t rc1 = wall_clock64();
-#endif
     // ---- this workgroup's maximum, then the grid-wide exchange.  The words are agent-scope atomics (they
     // bypass the per-XCD caches by themselves): no cache write-back or invalidation is needed around them.
     uint32_t m = wave_max_u32(pk_hmax_u16(amax));
@@ -220,9 +216,6 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
             __builtin_amdgcn_s_sleep(1);
         }
     }
-#ifdef RES_CLOCKS
-    if (tid == 0) lds_red[10] = (uint32_t)(wall_clock64() - rc1);
-#endif
     const bool arrived = __syncthreads_and(seen) != 0;
     if (!arrived) {
         // gave up waiting: the tensor maximum from the tensor itself, this workgroup alone
@@ -248,9 +241,6 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
     const float sg = global_scale_from_amax_bits(tmax);
     if (blockIdx.x == 0 && tid == 0) *a.gs_out = sg;
     const float inv_6sg = 1.0f / (6.0f * sg), inv_4sg = 1.0f / (4.0f * sg);
-#ifdef RES_CLOCKS
-    const uint64_t rc2 = wall_clock64();
-#endif
     if (__builtin_expect(scale_needs_f64(sg), 0)) {
         // A tensor scale outside the range in which fp32 quotients are safe: every block the fp64 way, from
         // memory (the smoothed keys re-derive the block from the stored mean, which a lane of this workgroup wrote
@@ -285,22 +275,25 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
             pair_pass2<SEARCH>(wa, wb, block_of(i), i + 1 < nr ? block_of(i + 1) : a.nblk, a.nblk, sg, inv_6sg, inv_4sg, out);
         }
     });
-    for (int s = 0; s < nl; s += 2) {
+    // The blocks in LDS belong to no wave in particular, so they are handed out from a queue: 64 lanes x 2 slots per
+    // item.  The arbiter favours the older of the two waves on a SIMD, which therefore finishes its register slots
+    // first and takes more of these items, and the two reach the end of the kernel together.
+    const int lane = tid & 63, n_items = ((nl + 1) >> 1) * (kResThreads / 64);
+    for (;;) {
+        uint32_t ticket = 0;
+        if (lane == 0) ticket = atomicAdd(queue_head, 1u);
+        const int item = (int)__builtin_amdgcn_readfirstlane(ticket);
+        if (item >= n_items) break;                                       // (every wave draws tickets until they run out)
+        const int s = (item >> 3) << 1, t = ((item & 7) << 6) + lane;     // first slot of the pair, lane slot in the workgroup
         const uint4v z = {0, 0, 0, 0};
         const bool two = s + 1 < nl;
-        const uint4v v0 = lds_blk[(2 * s) * kResThreads + tid], v1 = lds_blk[(2 * s + 1) * kResThreads + tid];
-        const uint4v v2 = two ? lds_blk[(2 * s + 2) * kResThreads + tid] : z, v3 = two ? lds_blk[(2 * s + 3) * kResThreads + tid] : z;
+        const uint4v v0 = lds_blk[(2 * s) * kResThreads + t], v1 = lds_blk[(2 * s + 1) * kResThreads + t];
+        const uint4v v2 = two ? lds_blk[(2 * s + 2) * kResThreads + t] : z, v3 = two ? lds_blk[(2 * s + 3) * kResThreads + t] : z;
         const uint32_t wa[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
         const uint32_t wb[8] = {v2.x, v2.y, v2.z, v2.w, v3.x, v3.y, v3.z, v3.w};
-        pair_pass2<SEARCH>(wa, wb, block_of(kResRegSlots + s), two ? block_of(kResRegSlots + s + 1) : a.nblk, a.nblk, sg, inv_6sg,
-                           inv_4sg, out);
+        const int64_t ga = (int64_t)blockIdx.x * kResThreads + t + (int64_t)(kResRegSlots + s) * slot_stride;
+        pair_pass2<SEARCH>(wa, wb, ga, two ? ga + slot_stride : a.nblk, a.nblk, sg, inv_6sg, inv_4sg, out);
     }
-#ifdef RES_CLOCKS
-    if (tid == 0 && blockIdx.x < 120) {
-        uint32_t *o = a.partial + 512 + 4 * blockIdx.x;
-        o[0] = lds_red[10] & 0xFFFFu; o[1] = (uint32_t)(rc1 - rc0); o[2] = (uint32_t)(rc2 - rc1); o[3] = (uint32_t)(wall_clock64() - rc2);
-    }
-#endif
 }
 
 // ---- host side ------------------------------------------------------------------------------------
