@@ -10,7 +10,7 @@
 namespace nvfp4 {
 
 // blocks in flight per lane and the largest grids of the streaming kernels (measured choices)
-constexpr int kQuantUnroll = 2, kDequantUnroll = 2, kQuantMaxGrid = 16384, kDequantMaxGrid = 8192;
+constexpr int kQuantUnroll = 2, kDequantUnroll = 4, kQuantMaxGrid = 16384, kDequantMaxGrid = 8192;
 
 // --------------------------------------------------------------------------
 // Pass 1: per-workgroup partial amax (largest |bf16| bit pattern).
@@ -404,7 +404,9 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint16_t *__r
 // one rounding.  For a given tensor there are only 127 * 8 distinct magnitudes,
 // so each workgroup builds that table exactly (fp64) in LDS once, split into a
 // low-byte and a high-byte plane per scale, and every element is then two
-// byte-permute lookups.  One lane per 16-element block.
+// byte-permute lookups.  One lane per half block (8 elements): a wave's loads and
+// stores are then each one contiguous stretch (256 bytes of codes in, 1 KB of bf16
+// out), which is worth a fifth more bandwidth than 32 bytes per lane in two pieces.
 // --------------------------------------------------------------------------
 // table[scale byte] = {low bytes of magnitudes 0-3, low bytes 4-7, high bytes 0-3, high bytes 4-7}
 __device__ __forceinline__ void build_dequant_table(uint4v *table, double sg)
@@ -425,28 +427,24 @@ __device__ __forceinline__ void build_dequant_table(uint4v *table, double sg)
     }
 }
 
-// sixteen codes (two dwords) -> sixteen bf16 (eight dwords) through the table row t of their scale
-__device__ __forceinline__ void dequant_block_lookup(uint2v cc, uint4v t, uint32_t (&o)[8])
+// eight codes (one dword) -> eight bf16 (four dwords) through the table row t of their scale
+__device__ __forceinline__ void dequant_half_lookup(uint32_t cw, uint4v t, uint32_t (&o)[4])
 {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        uint32_t cw = h ? cc.y : cc.x;
-        // selectors: magnitude index of the even / odd elements, one per byte
-        uint32_t se = cw & 0x07070707u, so = (cw >> 4) & 0x07070707u;
-        uint32_t lo_e = __builtin_amdgcn_perm(t.y, t.x, se), lo_o = __builtin_amdgcn_perm(t.y, t.x, so);
-        uint32_t hi_e = __builtin_amdgcn_perm(t.w, t.z, se), hi_o = __builtin_amdgcn_perm(t.w, t.z, so);
-        hi_e |= (cw << 4) & 0x80808080u;      // sign of even elements: bit 3 of each byte
-        hi_o |= cw & 0x80808080u;             // sign of odd elements: bit 7
-        // element 2b = (hi_e.b, lo_e.b), element 2b+1 = (hi_o.b, lo_o.b); dword b = elems 2b, 2b+1
-        uint32_t e01 = __builtin_amdgcn_perm(hi_e, lo_e, 0x05010400u);  // even elems of bytes 0, 1
-        uint32_t e23 = __builtin_amdgcn_perm(hi_e, lo_e, 0x07030602u);
-        uint32_t o01 = __builtin_amdgcn_perm(hi_o, lo_o, 0x05010400u);
-        uint32_t o23 = __builtin_amdgcn_perm(hi_o, lo_o, 0x07030602u);
-        o[4 * h + 0] = __builtin_amdgcn_perm(o01, e01, 0x05040100u);
-        o[4 * h + 1] = __builtin_amdgcn_perm(o01, e01, 0x07060302u);
-        o[4 * h + 2] = __builtin_amdgcn_perm(o23, e23, 0x05040100u);
-        o[4 * h + 3] = __builtin_amdgcn_perm(o23, e23, 0x07060302u);
-    }
+    // selectors: magnitude index of the even / odd elements, one per byte
+    uint32_t se = cw & 0x07070707u, so = (cw >> 4) & 0x07070707u;
+    uint32_t lo_e = __builtin_amdgcn_perm(t.y, t.x, se), lo_o = __builtin_amdgcn_perm(t.y, t.x, so);
+    uint32_t hi_e = __builtin_amdgcn_perm(t.w, t.z, se), hi_o = __builtin_amdgcn_perm(t.w, t.z, so);
+    hi_e |= (cw << 4) & 0x80808080u;      // sign of even elements: bit 3 of each byte
+    hi_o |= cw & 0x80808080u;             // sign of odd elements: bit 7
+    // element 2b = (hi_e.b, lo_e.b), element 2b+1 = (hi_o.b, lo_o.b); dword b = elems 2b, 2b+1
+    uint32_t e01 = __builtin_amdgcn_perm(hi_e, lo_e, 0x05010400u);  // even elems of bytes 0, 1
+    uint32_t e23 = __builtin_amdgcn_perm(hi_e, lo_e, 0x07030602u);
+    uint32_t o01 = __builtin_amdgcn_perm(hi_o, lo_o, 0x05010400u);
+    uint32_t o23 = __builtin_amdgcn_perm(hi_o, lo_o, 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(o01, e01, 0x05040100u);
+    o[1] = __builtin_amdgcn_perm(o01, e01, 0x07060302u);
+    o[2] = __builtin_amdgcn_perm(o23, e23, 0x05040100u);
+    o[3] = __builtin_amdgcn_perm(o23, e23, 0x07060302u);
 }
 
 __global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__restrict__ codes,
@@ -457,32 +455,27 @@ __global__ __launch_bounds__(256) void dequant_bf16_kernel(const uint8_t *__rest
     __shared__ uint4v table[128];
     build_dequant_table(table, (double)*gs);
     __syncthreads();
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    constexpr int U = kDequantUnroll;             // blocks in flight per lane
-    for (int64_t g0 = (int64_t)blockIdx.x * 256 + threadIdx.x; g0 < nblk; g0 += stride * U) {
-        uint2v ccs[U];
-        uint32_t sbs[U];
+    // One lane per half block (eight codes in, sixteen bytes out): every load and every store instruction of a wave
+    // covers one contiguous stretch.  A workgroup takes the units of 256 * U half blocks at a grid-wide stride.
+    constexpr int U = kDequantUnroll;             // half blocks in flight per lane
+    const int64_t nhalf = nblk << 1;
+    for (int64_t h0 = (int64_t)blockIdx.x * (256 * U) + threadIdx.x; h0 < nhalf; h0 += (int64_t)gridDim.x * (256 * U)) {
+        uint32_t cws[U], sbs[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t g = g0 + u * stride;
-            if (g < nblk) {
-                ccs[u] = __builtin_nontemporal_load((const uint2v *)(codes + (g << 3)));
-                sbs[u] = scales[g];
+            const int64_t h = h0 + u * 256;
+            if (h < nhalf) {
+                cws[u] = __builtin_nontemporal_load((const uint32_t *)codes + h);
+                sbs[u] = scales[h >> 1];
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t g = g0 + u * stride;
-            if (g >= nblk) continue;
-            uint32_t o[8];
-            dequant_block_lookup(ccs[u], table[sbs[u] & 0x7Fu], o);
-            uint4v a = {o[0], o[1], o[2], o[3]}, b = {o[4], o[5], o[6], o[7]};
-            // plain stores: a lane writes two 16-byte halves of a 32-byte run, and the
-            // cache merges neighbouring lanes' halves into full lines (streaming stores
-            // of half lines reach only about 2 TB/s here)
-            uint4v *q = (uint4v *)(out + (g << 4));
-            q[0] = a;
-            q[1] = b;
+            const int64_t h = h0 + u * 256;
+            if (h >= nhalf) continue;
+            uint32_t o[4];
+            dequant_half_lookup(cws[u], table[sbs[u] & 0x7Fu], o);
+            *(uint4v *)(out + (h << 3)) = uint4v{o[0], o[1], o[2], o[3]};
         }
     }
 }
@@ -525,48 +518,44 @@ __global__ __launch_bounds__(256) void dequant_gather_kernel(GatherTable t, uint
         build_dequant_table(table, sg);
         __syncthreads();
     }
-    constexpr int U = 2;                                   // blocks in flight per lane
-    for (int it = 0; it < kGatherBlocksPerWg / (256 * U); ++it) {
-        uint2v ccs[U];
-        uint32_t sbs[U];
+    constexpr int U = 4;                                   // half blocks in flight per lane
+    const int64_t nhalf = nblk << 1;
+    for (int it = 0; it < 2 * kGatherBlocksPerWg / (256 * U); ++it) {
+        uint32_t cws[U], sbs[U];
         uint16_t mus[U];                                   // row means of smoothed chunks, fetched with the codes
-        const int64_t g0 = first + it * (256 * U) + threadIdx.x;
-        if (g0 >= nblk) break;
+        const int64_t h0 = 2 * first + it * (256 * U) + threadIdx.x;
+        if (h0 >= nhalf) break;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t g = g0 + u * 256;
-            if (g < nblk) {
-                ccs[u] = __builtin_nontemporal_load((const uint2v *)(codes + (g << 3)));
-                sbs[u] = scales[g] & 0x7Fu;
-                if (mean) mus[u] = mean[t.row_shift >= 0 ? (g >> t.row_shift) : (g / t.nb_row)];
+            const int64_t h = h0 + u * 256;
+            if (h < nhalf) {
+                cws[u] = __builtin_nontemporal_load((const uint32_t *)codes + h);
+                sbs[u] = scales[h >> 1] & 0x7Fu;
+                if (mean) mus[u] = mean[t.row_shift >= 0 ? (h >> (t.row_shift + 1)) : ((h >> 1) / t.nb_row)];
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t g = g0 + u * 256;
-            if (g >= nblk) continue;
-            const uint2v cc = ccs[u];
-            uint32_t o[8];
+            const int64_t h = h0 + u * 256;
+            if (h >= nhalf) continue;
+            const uint32_t cw = cws[u];
+            uint32_t o[4];
             if (!mean) {
-                dequant_block_lookup(cc, table[sbs[u]], o);
+                dequant_half_lookup(cw, table[sbs[u]], o);
             } else {
                 const double mu = (double)__uint_as_float((uint32_t)mus[u] << 16);
                 const double den = (double)e4m3_to_f32(sbs[u]) * sg;                // exact
                 typedef float float2v __attribute__((ext_vector_type(2)));
-#define NVFP4_GATHER_PAIR(I, C, SEL)                                                              \
+#define NVFP4_GATHER_PAIR(I, SEL)                                                                 \
     {                                                                                             \
-        const float2v q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(C, 1.0f, SEL);                 \
+        const float2v q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cw, 1.0f, SEL);                \
         o[I] = bf16_rne_signed_from_f64((double)q.x * den + mu) |                                 \
                (bf16_rne_signed_from_f64((double)q.y * den + mu) << 16);                          \
     }
-                NVFP4_GATHER_PAIR(0, cc.x, 0) NVFP4_GATHER_PAIR(1, cc.x, 1) NVFP4_GATHER_PAIR(2, cc.x, 2) NVFP4_GATHER_PAIR(3, cc.x, 3)
-                NVFP4_GATHER_PAIR(4, cc.y, 0) NVFP4_GATHER_PAIR(5, cc.y, 1) NVFP4_GATHER_PAIR(6, cc.y, 2) NVFP4_GATHER_PAIR(7, cc.y, 3)
+                NVFP4_GATHER_PAIR(0, 0) NVFP4_GATHER_PAIR(1, 1) NVFP4_GATHER_PAIR(2, 2) NVFP4_GATHER_PAIR(3, 3)
 #undef NVFP4_GATHER_PAIR
             }
-            uint4v a = {o[0], o[1], o[2], o[3]}, b = {o[4], o[5], o[6], o[7]};
-            uint4v *q = (uint4v *)(dst + (g << 4));
-            q[0] = a;
-            q[1] = b;
+            *(uint4v *)(dst + (h << 3)) = uint4v{o[0], o[1], o[2], o[3]};
         }
     }
 }
@@ -644,7 +633,7 @@ hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, cons
                                int64_t K, uint16_t *out, hipStream_t s)
 {
     int64_t nblk = rows * (K >> 4);
-    int grid = grid_for(nblk, kDequantMaxGrid);
+    int grid = grid_for((2 * nblk + kDequantUnroll - 1) / kDequantUnroll, kDequantMaxGrid);      // at most one workgroup per unit
     dequant_bf16_kernel<<<grid, 256, 0, s>>>(codes, scales, gs, nblk, out);
     return hipGetLastError();
 }
