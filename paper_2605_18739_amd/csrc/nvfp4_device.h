@@ -301,28 +301,47 @@ __device__ inline uint32_t block_scale_f64(float bmax, float sg, double target)
     return lo;
 }
 
+// (rolled loops: these forms are inlined wherever a quantizer runs and are taken for out-of-range tensors only,
+// so they are written for small code, not for speed)
 __device__ inline void encode_block16_f64(const uint32_t (&w)[8], float sb, float sg, uint32_t &c0, uint32_t &c1)
 {
     const double den = (double)sb * (double)sg;                       // exact
     uint32_t out[2] = {0, 0};
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const uint32_t ww = w[j >> 1];
-        const float x = (j & 1) ? bf16hi_to_f32(ww) : bf16lo_to_f32(ww);
-        const double a = (double)fabsf(x);
-        uint32_t idx = 7;
-        if (den == 0.0) idx = 0;
-        else {
-#pragma unroll
+#pragma unroll 1
+    for (uint32_t j = 0; j < 16; ++j) {
+        const bool odd = (j & 2u) != 0u, upper = (j & 4u) != 0u, second = (j & 8u) != 0u;
+        const uint32_t w01 = odd ? w[1] : w[0], w23 = odd ? w[3] : w[2], w45 = odd ? w[5] : w[4], w67 = odd ? w[7] : w[6];
+        const uint32_t wlo = upper ? w23 : w01, whi = upper ? w67 : w45;
+        const uint32_t xb = ((second ? whi : wlo) >> ((j & 1u) << 4)) << 16;    // the element as fp32 bits
+        const double a = (double)__uint_as_float(xb & 0x7FFF0000u);
+        uint32_t idx = 0;
+        if (den != 0.0) {
+            idx = 7;
+#pragma unroll 1
             for (int i = 6; i >= 0; --i) {
                 const double t = e2m1_midpoint((uint32_t)i) * den;
                 if (a < t || (a == t && !(i & 1))) idx = (uint32_t)i;   // below the midpoint, or on it with the lower index even
             }
         }
-        out[j >> 3] |= (idx | ((__float_as_uint(x) >> 28) & 8u)) << (4 * (j & 7));
+        const uint32_t nib = (idx | ((xb >> 28) & 8u)) << (4u * (j & 7u));
+        if (second) out[1] |= nib;
+        else out[0] |= nib;
     }
     c0 = out[0];
     c1 = out[1];
+}
+
+// Block scale and block encoding for ANY tensor scale: the fp32 forms inside their safe range, the fp64 forms
+// outside it (the test is the same for every lane of a kernel, so it costs a scalar branch).
+__device__ __forceinline__ uint32_t block_scale_any(float bmax, float sg, float inv_msg, double target = 6.0)
+{
+    if (__builtin_expect(scale_needs_f64(sg), 0)) return block_scale_f64(bmax, sg, target);
+    return block_scale_exact(bmax, sg, inv_msg, target);
+}
+__device__ __forceinline__ void encode_block16_any(const uint32_t (&w)[8], float sb, float sg, uint32_t &c0, uint32_t &c1)
+{
+    if (__builtin_expect(scale_needs_f64(sg), 0)) encode_block16_f64(w, sb, sg, c0, c1);
+    else encode_block16(w, sb, sg, c0, c1);
 }
 
 // ---- straight-line forms for kernels that hold many blocks per lane -------------------------------
@@ -480,20 +499,13 @@ __device__ __forceinline__ void quantize_block16_4over6_inline(const uint32_t (&
 __device__ __forceinline__ void quantize_block16_exact(const uint32_t (&w)[8], float sg, float inv_6sg, uint32_t &sbyte,
                                                        uint32_t &c0, uint32_t &c1)
 {
-    const float bmax = block_absmax_f32(w);
-    if (__builtin_expect(scale_needs_f64(sg), 0)) {
-        sbyte = block_scale_f64(bmax, sg, 6.0);
-        encode_block16_f64(w, e4m3_to_f32(sbyte), sg, c0, c1);
-        return;
-    }
-    sbyte = block_scale_exact(bmax, sg, inv_6sg);
-    encode_block16(w, e4m3_to_f32(sbyte), sg, c0, c1);
+    sbyte = block_scale_any(block_absmax_f32(w), sg, inv_6sg);
+    encode_block16_any(w, e4m3_to_f32(sbyte), sg, c0, c1);
 }
 
-__device__ __forceinline__ void quantize_block16_4over6_exact(const uint32_t (&w)[8], float sg, float inv_6sg, float inv_4sg,
-                                                              uint32_t &sbyte, uint32_t &c0, uint32_t &c1)
+__device__ __forceinline__ void encode_block16_4over6_any(const uint32_t (&w)[8], float bmax, float sg, float inv_6sg,
+                                                          float inv_4sg, uint32_t &sbyte, uint32_t &c0, uint32_t &c1)
 {
-    const float bmax = block_absmax_f32(w);
     if (__builtin_expect(scale_needs_f64(sg), 0)) {
         const uint32_t s6 = block_scale_f64(bmax, sg, 6.0), s4 = block_scale_f64(bmax, sg, 4.0);
         encode_block16_f64(w, e4m3_to_f32(s6), sg, c0, c1);
@@ -501,7 +513,7 @@ __device__ __forceinline__ void quantize_block16_4over6_exact(const uint32_t (&w
         if (s4 == s6) return;
         uint32_t b0, b1;
         encode_block16_f64(w, e4m3_to_f32(s4), sg, b0, b1);
-        if (block_error_f64(w, b0, b1, e4m3_to_f32(s4), sg) < block_error_f64(w, c0, c1, e4m3_to_f32(s6), sg)) {
+        if (block_error_f64_rolled(w, b0, b1, e4m3_to_f32(s4), sg) < block_error_f64_rolled(w, c0, c1, e4m3_to_f32(s6), sg)) {
             sbyte = s4;
             c0 = b0;
             c1 = b1;
@@ -509,6 +521,12 @@ __device__ __forceinline__ void quantize_block16_4over6_exact(const uint32_t (&w
         return;
     }
     encode_block16_4over6(w, bmax, sg, inv_6sg, inv_4sg, sbyte, c0, c1);
+}
+
+__device__ __forceinline__ void quantize_block16_4over6_exact(const uint32_t (&w)[8], float sg, float inv_6sg, float inv_4sg,
+                                                              uint32_t &sbyte, uint32_t &c0, uint32_t &c1)
+{
+    encode_block16_4over6_any(w, block_absmax_f32(w), sg, inv_6sg, inv_4sg, sbyte, c0, c1);
 }
 
 // Round a non-negative exact product held in a double to bf16 once (nearest

@@ -214,9 +214,9 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
 #pragma unroll
                         for (int q = 0; q < 8; ++q) am = pk_absmax_u16(am, w[q]);
                         const float bmax = __uint_as_float(pk_hmax_u16(am) << 16);
-                        const uint32_t sbyte = block_scale_exact(bmax, q_sg, q_inv_6sg);
+                        const uint32_t sbyte = block_scale_any(bmax, q_sg, q_inv_6sg);
                         uint32_t c0, c1;
-                        encode_block16(w, e4m3_to_f32(sbyte), q_sg, c0, c1);
+                        encode_block16_any(w, e4m3_to_f32(sbyte), q_sg, c0, c1);
                         uint2v cc = {c0, c1};
                         *(uint2v *)(ep.q_codes + m * (g.q_pitch >> 1) + (n >> 1)) = cc;
                         ep.q_scales[m * (g.q_pitch >> 4) + (n >> 4)] = (uint8_t)sbyte;

@@ -6,43 +6,57 @@
 
 namespace nvfp4 {
 
-constexpr int kProbeThreads = 256, kProbeGrid = 256 * 4;   // four workgroups per compute unit (measured best of 2, 4, 8, 16)
+// Each workgroup streams one contiguous stretch of the buffer, four 16-byte vectors per lane in flight.  Contiguous
+// stretches per workgroup sustain about a fifth more than the same loop at a grid-wide stride (reads 6.9 against
+// 5.7 TB/s, writes 5.9 against 4.4, copies 5.7 against 4.5 on the 1 GiB buffers of the benchmark), and the grids
+// below are the best of 512 .. 16384 workgroups for each kind.
+constexpr int kProbeThreads = 256, kProbeGridRead = 4096, kProbeGridWrite = 4096, kProbeGridCopy = 16384;
+
+struct ProbeRange { int64_t begin, end; };
+__device__ __forceinline__ ProbeRange probe_range(int64_t nvec)
+{
+    const int64_t per = (nvec + gridDim.x - 1) / gridDim.x, b = per * blockIdx.x;
+    return {b, b + per < nvec ? b + per : nvec};
+}
 
 // every 16-byte vector of the buffer is read once; the XOR of what a workgroup read goes to sink[]
 __global__ __launch_bounds__(kProbeThreads) void probe_read_kernel(const uint4v *__restrict__ src, int64_t nvec,
                                                                    uint32_t *__restrict__ sink)
 {
     uint4v acc = {0, 0, 0, 0};
-    const int64_t stride = (int64_t)gridDim.x * kProbeThreads;
-    int64_t i = (int64_t)blockIdx.x * kProbeThreads + threadIdx.x;
-    for (; i + 3 * stride < nvec; i += 4 * stride) {          // four loads in flight per lane
-        const uint4v a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
-        const uint4v c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
+    const ProbeRange r = probe_range(nvec);
+    int64_t i = r.begin + threadIdx.x;
+    for (; i + 3 * kProbeThreads < r.end; i += 4 * kProbeThreads) {
+        const uint4v a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + kProbeThreads);
+        const uint4v c = __builtin_nontemporal_load(src + i + 2 * kProbeThreads), d = __builtin_nontemporal_load(src + i + 3 * kProbeThreads);
         acc ^= a ^ b ^ c ^ d;
     }
-    for (; i < nvec; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    for (; i < r.end; i += kProbeThreads) acc ^= __builtin_nontemporal_load(src + i);
     const uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
     if (x == 0x9E3779B9u) sink[blockIdx.x] = x;                // practically never true: the loads cannot be dropped
 }
 
 __global__ __launch_bounds__(kProbeThreads) void probe_write_kernel(uint4v *__restrict__ dst, int64_t nvec, uint32_t seed)
 {
-    const int64_t stride = (int64_t)gridDim.x * kProbeThreads;
+    const ProbeRange r = probe_range(nvec);
     const uint4v v = {seed, seed + 1, seed + 2, seed + threadIdx.x};
-    for (int64_t i = (int64_t)blockIdx.x * kProbeThreads + threadIdx.x; i < nvec; i += stride) dst[i] = v;
+    for (int64_t i = r.begin + threadIdx.x; i < r.end; i += kProbeThreads) dst[i] = v;
 }
 
 __global__ __launch_bounds__(kProbeThreads) void probe_copy_kernel(const uint4v *__restrict__ src, uint4v *__restrict__ dst,
                                                                    int64_t nvec)
 {
-    const int64_t stride = (int64_t)gridDim.x * kProbeThreads;
-    int64_t i = (int64_t)blockIdx.x * kProbeThreads + threadIdx.x;
-    for (; i + stride < nvec; i += 2 * stride) {
-        const uint4v a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
-        dst[i] = a;
-        dst[i + stride] = b;
+    const ProbeRange r = probe_range(nvec);
+    int64_t i = r.begin + threadIdx.x;
+    for (; i + 3 * kProbeThreads < r.end; i += 4 * kProbeThreads) {
+        const uint4v a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + kProbeThreads);
+        const uint4v c = __builtin_nontemporal_load(src + i + 2 * kProbeThreads), d = __builtin_nontemporal_load(src + i + 3 * kProbeThreads);
+        __builtin_nontemporal_store(a, dst + i);
+        __builtin_nontemporal_store(b, dst + i + kProbeThreads);
+        __builtin_nontemporal_store(c, dst + i + 2 * kProbeThreads);
+        __builtin_nontemporal_store(d, dst + i + 3 * kProbeThreads);
     }
-    for (; i < nvec; i += stride) dst[i] = __builtin_nontemporal_load(src + i);
+    for (; i < r.end; i += kProbeThreads) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 // 64 MFMAs per iteration on sixteen accumulators; the operands are eight register-resident fragments, a
@@ -92,9 +106,9 @@ hipError_t launch_probe(int kind, const void *a, void *b, int64_t bytes, int ite
 {
     const int64_t nvec = bytes >> 4;
     switch (kind) {
-    case 0: probe_read_kernel<<<kProbeGrid, kProbeThreads, 0, s>>>((const uint4v *)a, nvec, (uint32_t *)b); break;
-    case 1: probe_write_kernel<<<kProbeGrid, kProbeThreads, 0, s>>>((uint4v *)b, nvec, 0x01234567u); break;
-    case 2: probe_copy_kernel<<<kProbeGrid, kProbeThreads, 0, s>>>((const uint4v *)a, (uint4v *)b, nvec); break;
+    case 0: probe_read_kernel<<<kProbeGridRead, kProbeThreads, 0, s>>>((const uint4v *)a, nvec, (uint32_t *)b); break;
+    case 1: probe_write_kernel<<<kProbeGridWrite, kProbeThreads, 0, s>>>((uint4v *)b, nvec, 0x01234567u); break;
+    case 2: probe_copy_kernel<<<kProbeGridCopy, kProbeThreads, 0, s>>>((const uint4v *)a, (uint4v *)b, nvec); break;
     case 3: probe_mfma_kernel<<<256, 256, 0, s>>>(iters, 0x2545F491u, (float *)b); break;
     default: return hipErrorInvalidValue;
     }

@@ -196,10 +196,10 @@ void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
                 float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
                 uint32_t sbyte, c0, c1;
                 if constexpr (SEARCH) {
-                    encode_block16_4over6(w, bmax, sg, inv_6sg, inv_4sg, sbyte, c0, c1);
+                    encode_block16_4over6_any(w, bmax, sg, inv_6sg, inv_4sg, sbyte, c0, c1);
                 } else {
-                    sbyte = block_scale_exact(bmax, sg, inv_6sg);
-                    encode_block16(w, e4m3_to_f32(sbyte), sg, c0, c1);
+                    sbyte = block_scale_any(bmax, sg, inv_6sg);
+                    encode_block16_any(w, e4m3_to_f32(sbyte), sg, c0, c1);
                 }
                 uint2v cc = {c0, c1};
                 int64_t go = g;                       // output block index
@@ -307,9 +307,9 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__re
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
             float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
-            uint32_t sbyte = block_scale_exact(bmax, sg, inv_6sg);
+            uint32_t sbyte = block_scale_any(bmax, sg, inv_6sg);
             uint32_t k0, k1;
-            encode_block16(w, e4m3_to_f32(sbyte), sg, k0, k1);
+            encode_block16_any(w, e4m3_to_f32(sbyte), sg, k0, k1);
             uint2v cc = {k0, k1};
             lds_codes[cg * 8 + j][rb] = cc;
             lds_scales[cg * 8 + j][rb] = (uint8_t)sbyte;
@@ -372,12 +372,12 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint16_t *__r
 #pragma unroll
         for (int k = 0; k < 8; ++k) acc = pk_absmax_u16(acc, w[i][k]);
     const float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
-    const uint32_t sbyte = block_scale_exact(bmax, sg, inv_6sg);
+    const uint32_t sbyte = block_scale_any(bmax, sg, inv_6sg);
     const float sb = e4m3_to_f32(sbyte);
     uint32_t c0[16], c1[16];                       // row i of the tile: codes of columns 0-7, 8-15
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        encode_block16(w[i], sb, sg, c0[i], c1[i]);
+        encode_block16_any(w[i], sb, sg, c0[i], c1[i]);
         const int64_t row = 16 * I + i;
         *(uint2v *)(codes + row * (C >> 1) + 8 * J) = uint2v{c0[i], c1[i]};
         scales[row * tc + J] = (uint8_t)sbyte;

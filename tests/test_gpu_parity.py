@@ -210,6 +210,35 @@ def test_quantize_one_launch_path_with_and_without_the_grid_wide_wait(oracle):
             nv.nvfp4_set_sync_spin_limit()                     # back to the default bound
 
 
+@pytest.mark.parametrize("magnitude", [1e-33, 1e-36, 3e-39, 1e30, 3e37])
+def test_quantize_tensor_scales_outside_the_fp32_safe_range(oracle, magnitude):
+    """Tensors whose scale amax / 2688 lies below 2^-100 or above 2^100 (the reciprocal 1 / (6 s_g) and the products
+    s_b s_g leave the normal fp32 range there, bf16 subnormals included): every route through the quantizers -- one
+    launch, streaming with a padded row stride, a given scale, blocks along the rows, the scale search, 16 x 16
+    tiles -- still returns the oracle's bytes."""
+    g = np.random.default_rng(int(-np.log10(magnitude)) + 100)
+    R, C = 96, 208
+    xb = wl.to_bf16_bits(g.standard_normal((R, C)).astype(np.float32) * np.float32(magnitude))
+    say(f"[quantize] magnitude {magnitude}: one launch")
+    want = oracle.quantize(xb)
+    assert_q_equal(nv.nvfp4_quantize(dev_bf16(xb)), want, f"one launch {magnitude}")
+    assert_q_equal(nv.nvfp4_quantize_4over6(dev_bf16(xb)), oracle.quantize(xb, four_over_six=True), f"search {magnitude}")
+    full = np.zeros((R, C + 16), np.uint16)
+    full[:, :C] = xb
+    view = dev_bf16(full)[:, :C]
+    say(f"[quantize] magnitude {magnitude}: streaming, padded rows")
+    assert_q_equal(nv.nvfp4_quantize(view), want, f"strided {magnitude}")
+    assert_q_equal(nv.nvfp4_quantize_4over6(view), oracle.quantize(xb, four_over_six=True), f"strided search {magnitude}")
+    gs = float(want.global_scale) * 1.5
+    gsd = torch.tensor([gs], dtype=torch.float32, device="cuda")
+    if np.isfinite(np.float32(gs)) and np.float32(gs) > 0:
+        say(f"[quantize] magnitude {magnitude}: given scale")
+        assert_q_equal(nv.nvfp4_quantize(dev_bf16(xb), global_scale_in=gsd),
+                       oracle.quantize(xb, global_scale_in=float(np.float32(gs))), f"given scale {magnitude}")
+    say(f"[quantize] magnitude {magnitude}: blocks along the rows")
+    assert_q_equal(nv.nvfp4_quantize(dev_bf16(xb), block_axis=1), oracle.quantize(xb, block_axis=1), f"transposed {magnitude}")
+
+
 def test_quantize_is_deterministic():
     xb = wl.activation_with_outliers(512, 3072, 1, 0)
     x = dev_bf16(xb)
