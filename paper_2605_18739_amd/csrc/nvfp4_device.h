@@ -24,6 +24,15 @@ constexpr float kFp8Max = 448.0f;    // M^FP8
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+// two fp32 -> packed bf16 (round to nearest even), one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+    float2v v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
+}
+
 // max of the absolute values of two packed bf16 pairs, on their bit patterns
 // (|bf16| patterns order like unsigned integers).
 __device__ __forceinline__ uint32_t pk_absmax_u16(uint32_t acc, uint32_t w)
@@ -102,13 +111,6 @@ __device__ __forceinline__ uint32_t block_scale_exact(float bmax, float sg, floa
         blo = (b > t) ? bhi : ((b < t) ? blo : ((blo & 1u) ? bhi : blo));
     }
     return blo;
-}
-
-// midpoint between E2M1 magnitude index i and i+1
-__device__ __forceinline__ double e2m1_midpoint(uint32_t i)
-{
-    // magnitudes 0 .5 1 1.5 2 3 4 6 -> midpoints .25 .75 1.25 1.75 2.5 3.5 5
-    return i < 4u ? 0.25 + 0.5 * (double)i : (i == 4u ? 2.5 : (i == 5u ? 3.5 : 5.0));
 }
 
 // Settle the nibbles on which the two ends of the bracket disagree.  l holds the codes of the lower end, h of the
@@ -205,25 +207,9 @@ __device__ __forceinline__ float block_error_f32(const uint32_t (&w)[8], uint32_
 // The same error as the fp64 definition evaluates it: every difference |x| - m s_b s_g taken
 // once in fp64, squared, and summed in element order, each operation rounded on its own (no
 // fused multiply-add), so that "is candidate 4 strictly better" has one answer everywhere.
+// (A rolled loop: the fallback is inlined wherever a block is encoded and taken rarely, so it is written for
+// small code, not for speed.)
 __device__ __forceinline__ double block_error_f64(const uint32_t (&w)[8], uint32_t c0, uint32_t c1, float sb, float sg)
-{
-    const double den = (double)sb * (double)sg;     // exact
-    double err = 0.0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const uint32_t ww = w[j >> 1];
-        const double a = (double)fabsf((j & 1) ? bf16hi_to_f32(ww) : bf16lo_to_f32(ww));
-        const uint32_t idx = (((j < 8) ? c0 : c1) >> (4 * (j & 7))) & 7u;
-        const double m = idx < 4u ? 0.5 * (double)idx : (idx == 4u ? 2.0 : (idx == 5u ? 3.0 : (idx == 6u ? 4.0 : 6.0)));
-        const double d = __dsub_rn(a, __dmul_rn(m, den));
-        err = __dadd_rn(err, __dmul_rn(d, d));
-    }
-    return err;
-}
-
-// The same sum, operation for operation, as a rolled loop: a few dozen instructions instead of several hundred,
-// for callers that inline the fallback many times and take it rarely.
-__device__ __forceinline__ double block_error_f64_rolled(const uint32_t (&w)[8], uint32_t c0, uint32_t c1, float sb, float sg)
 {
     typedef float float2v __attribute__((ext_vector_type(2)));
     const double den = (double)sb * (double)sg;     // exact
@@ -282,66 +268,20 @@ __device__ __forceinline__ void encode_block16_4over6(const uint32_t (&w)[8], fl
     }
 }
 
-// ---- fp64 forms for tensor scales outside the range in which the fp32 quotients above are safe
-// (global scales below 2^-100 or above 2^100: the reciprocal 1 / (M s_g) or the products s_b s_g
-// leave the normal fp32 range).  Every decision by cross-multiplication in fp64, which has the
-// exponent range to spare; slow, and only ever taken for such tensors.
-__device__ __forceinline__ bool scale_needs_f64(float sg) { return !(sg >= 0x1p-100f && sg <= 0x1p100f); }
-
-__device__ inline uint32_t block_scale_f64(float bmax, float sg, double target)
+// ---- tensor scales outside the range in which the fp32 quotients above are safe ----------------------
+// Below s_g = 2^-100 or above 2^100 the reciprocal 1 / (M s_g) or the products s_b s_g leave the normal fp32
+// range.  Every decision of the quantizer compares ratios, so it commutes with multiplying the tensor AND its
+// scale by a power of two: such tensors are encoded as (x 2^k, s_g 2^k) with k = +96 or -96, which puts the scale
+// back into range.  The scaled elements are exact (bf16 has the exponent range of fp32) except those that underflow
+// when a huge tensor is scaled down: they are below 2^-30, more than a hundred binades under a quarter of the
+// smallest block scale times s_g, so their code is zero either way, and so is the scale of a block made of them.
+// The stored tensor scale is the unscaled one.  The test is the same for every lane: a scalar branch.
+__device__ __forceinline__ bool scale_out_of_range(float sg) { return !(sg >= 0x1p-100f && sg <= 0x1p100f); }
+__device__ __forceinline__ float range_shift(float sg) { return sg < 0x1p-100f ? 0x1p96f : (sg > 0x1p100f ? 0x1p-96f : 1.0f); }
+__device__ __forceinline__ void rescale_block16(uint32_t (&w)[8], float f)
 {
-    const double num = (double)bmax, den = target * (double)sg;       // exact (2 + 24 bits)
-    uint32_t lo = 0, hi = 126;                                        // the answer lies in [lo, hi]
-    while (lo < hi) {
-        const uint32_t m = (lo + hi) >> 1;
-        const double t = 0.5 * ((double)e4m3_to_f32(m) + (double)e4m3_to_f32(m + 1)) * den;   // exact (5 + 26 bits)
-        if (num > t || (num == t && (m & 1u))) lo = m + 1;            // a tie goes to the even byte
-        else hi = m;
-    }
-    return lo;
-}
-
-// (rolled loops: these forms are inlined wherever a quantizer runs and are taken for out-of-range tensors only,
-// so they are written for small code, not for speed)
-__device__ inline void encode_block16_f64(const uint32_t (&w)[8], float sb, float sg, uint32_t &c0, uint32_t &c1)
-{
-    const double den = (double)sb * (double)sg;                       // exact
-    uint32_t out[2] = {0, 0};
-#pragma unroll 1
-    for (uint32_t j = 0; j < 16; ++j) {
-        const bool odd = (j & 2u) != 0u, upper = (j & 4u) != 0u, second = (j & 8u) != 0u;
-        const uint32_t w01 = odd ? w[1] : w[0], w23 = odd ? w[3] : w[2], w45 = odd ? w[5] : w[4], w67 = odd ? w[7] : w[6];
-        const uint32_t wlo = upper ? w23 : w01, whi = upper ? w67 : w45;
-        const uint32_t xb = ((second ? whi : wlo) >> ((j & 1u) << 4)) << 16;    // the element as fp32 bits
-        const double a = (double)__uint_as_float(xb & 0x7FFF0000u);
-        uint32_t idx = 0;
-        if (den != 0.0) {
-            idx = 7;
-#pragma unroll 1
-            for (int i = 6; i >= 0; --i) {
-                const double t = e2m1_midpoint((uint32_t)i) * den;
-                if (a < t || (a == t && !(i & 1))) idx = (uint32_t)i;   // below the midpoint, or on it with the lower index even
-            }
-        }
-        const uint32_t nib = (idx | ((xb >> 28) & 8u)) << (4u * (j & 7u));
-        if (second) out[1] |= nib;
-        else out[0] |= nib;
-    }
-    c0 = out[0];
-    c1 = out[1];
-}
-
-// Block scale and block encoding for ANY tensor scale: the fp32 forms inside their safe range, the fp64 forms
-// outside it (the test is the same for every lane of a kernel, so it costs a scalar branch).
-__device__ __forceinline__ uint32_t block_scale_any(float bmax, float sg, float inv_msg, double target = 6.0)
-{
-    if (__builtin_expect(scale_needs_f64(sg), 0)) return block_scale_f64(bmax, sg, target);
-    return block_scale_exact(bmax, sg, inv_msg, target);
-}
-__device__ __forceinline__ void encode_block16_any(const uint32_t (&w)[8], float sb, float sg, uint32_t &c0, uint32_t &c1)
-{
-    if (__builtin_expect(scale_needs_f64(sg), 0)) encode_block16_f64(w, sb, sg, c0, c1);
-    else encode_block16(w, sb, sg, c0, c1);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i] = pack_bf16x2(bf16lo_to_f32(w[i]) * f, bf16hi_to_f32(w[i]) * f);
 }
 
 // ---- straight-line forms for kernels that hold many blocks per lane -------------------------------
@@ -487,7 +427,7 @@ __device__ __forceinline__ void quantize_block16_4over6_inline(const uint32_t (&
     const bool same = s4 == s6;                    // (saturated scales, zero blocks: same codes, same error, 6 is kept)
     bool pick4 = e4 + r4 < e6 - r6;
     if (__builtin_expect(!same & (tiny | !(pick4 | (e4 - r4 > e6 + r6))), 0))
-        pick4 = block_error_f64_rolled(w, l4[0], l4[1], sb4, sg) < block_error_f64_rolled(w, l6[0], l6[1], sb6, sg);
+        pick4 = block_error_f64(w, l4[0], l4[1], sb4, sg) < block_error_f64(w, l6[0], l6[1], sb6, sg);
     pick4 &= !same;
     sbyte = pick4 ? s4 : s6;
     c0 = pick4 ? l4[0] : l6[0];
@@ -495,38 +435,20 @@ __device__ __forceinline__ void quantize_block16_4over6_inline(const uint32_t (&
 }
 #undef NVFP4_CVT4
 
-// the one-block-at-a-time counterparts for any tensor scale (the fp64 forms when the scale needs them)
-__device__ __forceinline__ void quantize_block16_exact(const uint32_t (&w)[8], float sg, float inv_6sg, uint32_t &sbyte,
+// the one-block-at-a-time counterparts, for any tensor scale (sgq, inv_6sgq, inv_4sgq: the scale after range_shift)
+__device__ __forceinline__ void quantize_block16_exact(uint32_t (&w)[8], float shift, float sgq, float inv_6sgq, uint32_t &sbyte,
                                                        uint32_t &c0, uint32_t &c1)
 {
-    sbyte = block_scale_any(block_absmax_f32(w), sg, inv_6sg);
-    encode_block16_any(w, e4m3_to_f32(sbyte), sg, c0, c1);
+    if (__builtin_expect(shift != 1.0f, 0)) rescale_block16(w, shift);
+    sbyte = block_scale_exact(block_absmax_f32(w), sgq, inv_6sgq);
+    encode_block16(w, e4m3_to_f32(sbyte), sgq, c0, c1);
 }
 
-__device__ __forceinline__ void encode_block16_4over6_any(const uint32_t (&w)[8], float bmax, float sg, float inv_6sg,
-                                                          float inv_4sg, uint32_t &sbyte, uint32_t &c0, uint32_t &c1)
+__device__ __forceinline__ void quantize_block16_4over6_exact(uint32_t (&w)[8], float shift, float sgq, float inv_6sgq,
+                                                              float inv_4sgq, uint32_t &sbyte, uint32_t &c0, uint32_t &c1)
 {
-    if (__builtin_expect(scale_needs_f64(sg), 0)) {
-        const uint32_t s6 = block_scale_f64(bmax, sg, 6.0), s4 = block_scale_f64(bmax, sg, 4.0);
-        encode_block16_f64(w, e4m3_to_f32(s6), sg, c0, c1);
-        sbyte = s6;
-        if (s4 == s6) return;
-        uint32_t b0, b1;
-        encode_block16_f64(w, e4m3_to_f32(s4), sg, b0, b1);
-        if (block_error_f64_rolled(w, b0, b1, e4m3_to_f32(s4), sg) < block_error_f64_rolled(w, c0, c1, e4m3_to_f32(s6), sg)) {
-            sbyte = s4;
-            c0 = b0;
-            c1 = b1;
-        }
-        return;
-    }
-    encode_block16_4over6(w, bmax, sg, inv_6sg, inv_4sg, sbyte, c0, c1);
-}
-
-__device__ __forceinline__ void quantize_block16_4over6_exact(const uint32_t (&w)[8], float sg, float inv_6sg, float inv_4sg,
-                                                              uint32_t &sbyte, uint32_t &c0, uint32_t &c1)
-{
-    encode_block16_4over6_any(w, block_absmax_f32(w), sg, inv_6sg, inv_4sg, sbyte, c0, c1);
+    if (__builtin_expect(shift != 1.0f, 0)) rescale_block16(w, shift);
+    encode_block16_4over6(w, block_absmax_f32(w), sgq, inv_6sgq, inv_4sgq, sbyte, c0, c1);
 }
 
 // Round a non-negative exact product held in a double to bf16 once (nearest
@@ -547,15 +469,6 @@ __device__ __forceinline__ uint32_t bf16_rne_signed_from_f64(double v)
 {
     const uint32_t sign = (uint32_t)(__double_as_longlong(v) >> 48) & 0x8000u;
     return sign | bf16_rne_from_f64(fabs(v));
-}
-
-// two fp32 -> packed bf16 (round to nearest even), one v_cvt_pk_bf16_f32
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
-{
-    typedef float float2v __attribute__((ext_vector_type(2)));
-    typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-    float2v v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2v));
 }
 
 // K-smoothing (Sec. 3.2, Eq. 6) of one 16-element block given its row mean (a bf16 value):

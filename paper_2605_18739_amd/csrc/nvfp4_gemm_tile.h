@@ -116,11 +116,13 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
     uint8_t *slab = lds + wave * 16384;
     uint32_t hmax = 0;                            // largest |bf16(H)| pattern seen by this lane
     // fused quantizer: the tensor scale comes from the caller
-    float q_sg = 1.0f, q_inv_6sg = 1.0f;
+    float q_sg = 1.0f, q_inv_6sg = 1.0f, q_shift = 1.0f;
     if constexpr (EPI == kEpiQuant) {
-        q_sg = *ep.q_scale;
+        const float sg_given = *ep.q_scale;
+        if (blockIdx.x == 0 && tid == 0) *ep.q_scale_out = sg_given;
+        q_shift = range_shift(sg_given);                  // 1 unless the scale is outside the fp32-safe range
+        q_sg = sg_given * q_shift;
         q_inv_6sg = 1.0f / (6.0f * q_sg);
-        if (blockIdx.x == 0 && tid == 0) *ep.q_scale_out = q_sg;
     }
     // granule swizzle: XOR with as many key bits as keep the index inside a row
     constexpr int KEYMASK = (WN % 64 == 0) ? 7 : 3;
@@ -210,13 +212,14 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
                     const int64_t m = wave_m0 + j * 32 + r, n = wave_n0 + b * 16;
                     if (m < g.M && n < g.N) {                 // N % 16 == 0: a block is all in or all out
                         uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+                        if (__builtin_expect(q_shift != 1.0f, 0)) rescale_block16(w, q_shift);
                         uint32_t am = 0;
 #pragma unroll
                         for (int q = 0; q < 8; ++q) am = pk_absmax_u16(am, w[q]);
                         const float bmax = __uint_as_float(pk_hmax_u16(am) << 16);
-                        const uint32_t sbyte = block_scale_any(bmax, q_sg, q_inv_6sg);
+                        const uint32_t sbyte = block_scale_exact(bmax, q_sg, q_inv_6sg);
                         uint32_t c0, c1;
-                        encode_block16_any(w, e4m3_to_f32(sbyte), q_sg, c0, c1);
+                        encode_block16(w, e4m3_to_f32(sbyte), q_sg, c0, c1);
                         uint2v cc = {c0, c1};
                         *(uint2v *)(ep.q_codes + m * (g.q_pitch >> 1) + (n >> 1)) = cc;
                         ep.q_scales[m * (g.q_pitch >> 4) + (n >> 4)] = (uint8_t)sbyte;

@@ -179,8 +179,9 @@ void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
     if constexpr (!SEARCH) fetch(first);
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
     if constexpr (SEARCH) fetch(first);
-    const float inv_6sg = 1.0f / (6.0f * sg);
-    const float inv_4sg = 1.0f / (4.0f * sg);
+    const float shift = range_shift(sg), sgq = sg * shift;      // (1 and s_g unless the tensor scale is out of the fp32-safe range)
+    const float inv_6sg = 1.0f / (6.0f * sgq);
+    const float inv_4sg = 1.0f / (4.0f * sgq);
     for (int64_t g0 = first; g0 < nblk; g0 += stride * U) {
         if (g0 != first) fetch(g0);
 #pragma unroll
@@ -190,16 +191,17 @@ void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
                 uint32_t w[8] = {v0[u].x, v0[u].y, v0[u].z, v0[u].w, v1[u].x, v1[u].y, v1[u].z, v1[u].w};
                 // SMOOTH: C / 16 = 1 << row_shift blocks per row
                 if constexpr (SMOOTH) smooth_block16(w, __uint_as_float((uint32_t)row_mean[g >> row_shift] << 16));
+                if (__builtin_expect(shift != 1.0f, 0)) rescale_block16(w, shift);
                 uint32_t acc = 0;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
                 float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
                 uint32_t sbyte, c0, c1;
                 if constexpr (SEARCH) {
-                    encode_block16_4over6_any(w, bmax, sg, inv_6sg, inv_4sg, sbyte, c0, c1);
+                    encode_block16_4over6(w, bmax, sgq, inv_6sg, inv_4sg, sbyte, c0, c1);
                 } else {
-                    sbyte = block_scale_any(bmax, sg, inv_6sg);
-                    encode_block16_any(w, e4m3_to_f32(sbyte), sg, c0, c1);
+                    sbyte = block_scale_exact(bmax, sgq, inv_6sg);
+                    encode_block16(w, e4m3_to_f32(sbyte), sgq, c0, c1);
                 }
                 uint2v cc = {c0, c1};
                 int64_t go = g;                       // output block index
@@ -296,20 +298,22 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__re
             v[i] = __builtin_nontemporal_load((const uint4v *)(x + (r + i) * ld + c));
     }
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
-    const float inv_6sg = 1.0f / (6.0f * sg);
+    const float shift = range_shift(sg), sgq = sg * shift;      // (1 and s_g unless the tensor scale is out of the fp32-safe range)
+    const float inv_6sg = 1.0f / (6.0f * sgq);
     if (live) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {      // column c + j: element j of every loaded vector
             uint32_t w[8];
             column_of(v, j, w);
             if constexpr (RHT) rht_block16(w, sign_mask);
+            if (__builtin_expect(shift != 1.0f, 0)) rescale_block16(w, shift);
             uint32_t acc = 0;
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
             float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
-            uint32_t sbyte = block_scale_any(bmax, sg, inv_6sg);
+            uint32_t sbyte = block_scale_exact(bmax, sgq, inv_6sg);
             uint32_t k0, k1;
-            encode_block16_any(w, e4m3_to_f32(sbyte), sg, k0, k1);
+            encode_block16(w, e4m3_to_f32(sbyte), sgq, k0, k1);
             uint2v cc = {k0, k1};
             lds_codes[cg * 8 + j][rb] = cc;
             lds_scales[cg * 8 + j][rb] = (uint8_t)sbyte;
@@ -365,19 +369,24 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const uint16_t *__r
     }
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
     if (gs_out_t && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *gs_out_t = sg;
-    const float inv_6sg = 1.0f / (6.0f * sg);
+    const float shift = range_shift(sg), sgq = sg * shift;      // (1 and s_g unless the tensor scale is out of the fp32-safe range)
+    const float inv_6sg = 1.0f / (6.0f * sgq);
     if (!live) return;
+    if (__builtin_expect(shift != 1.0f, 0)) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) rescale_block16(w[i], shift);
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i)
 #pragma unroll
         for (int k = 0; k < 8; ++k) acc = pk_absmax_u16(acc, w[i][k]);
     const float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
-    const uint32_t sbyte = block_scale_any(bmax, sg, inv_6sg);
+    const uint32_t sbyte = block_scale_exact(bmax, sgq, inv_6sg);
     const float sb = e4m3_to_f32(sbyte);
     uint32_t c0[16], c1[16];                       // row i of the tile: codes of columns 0-7, 8-15
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        encode_block16_any(w[i], sb, sg, c0[i], c1[i]);
+        encode_block16(w[i], sb, sgq, c0[i], c1[i]);
         const int64_t row = 16 * I + i;
         *(uint2v *)(codes + row * (C >> 1) + 8 * J) = uint2v{c0[i], c1[i]};
         scales[row * tc + J] = (uint8_t)sbyte;

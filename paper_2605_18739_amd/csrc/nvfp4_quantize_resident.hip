@@ -246,8 +246,9 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
     const float sg = global_scale_from_amax_bits(tmax);
     if (blockIdx.x == 0 && tid == 0) *a.gs_out = sg;
     const float inv_6sg = 1.0f / (6.0f * sg), inv_4sg = 1.0f / (4.0f * sg);
-    if (__builtin_expect(scale_needs_f64(sg), 0)) {
-        // A tensor scale outside the range in which fp32 quotients are safe: every block the fp64 way, from
+    if (__builtin_expect(scale_out_of_range(sg), 0)) {
+        // A tensor scale outside the range in which fp32 quotients are safe: every block one at a time with the
+        // tensor and its scale shifted back into range, from
         // memory (the smoothed keys re-derive the block from the stored mean, which a lane of this workgroup wrote
         // in pass 1: the fence and the barrier order that store before the loads).  Slow, and only for such tensors.
         if constexpr (SMOOTH) {
@@ -255,6 +256,7 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
             __syncthreads();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         }
+        const float shift = range_shift(sg), sgq = sg * shift;
         for (int slot = 0; slot < nb; ++slot) {
             const int64_t g = block_of(slot);
             if (g >= a.nblk) continue;
@@ -263,8 +265,8 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
             uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
             if constexpr (SMOOTH) smooth_block16(w, __uint_as_float((uint32_t)a.mean_out[g >> a.row_shift] << 16));
             uint32_t sbyte, c0, c1;
-            if constexpr (SEARCH) quantize_block16_4over6_exact(w, sg, inv_6sg, inv_4sg, sbyte, c0, c1);
-            else quantize_block16_exact(w, sg, inv_6sg, sbyte, c0, c1);
+            if constexpr (SEARCH) quantize_block16_4over6_exact(w, shift, sgq, 1.0f / (6.0f * sgq), 1.0f / (4.0f * sgq), sbyte, c0, c1);
+            else quantize_block16_exact(w, shift, sgq, 1.0f / (6.0f * sgq), sbyte, c0, c1);
             *(uint2v *)(a.codes + (g << 3)) = uint2v{c0, c1};
             a.scales[g] = (uint8_t)sbyte;
         }
