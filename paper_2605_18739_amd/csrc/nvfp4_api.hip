@@ -206,6 +206,12 @@ int nvfp4_quantize_for_all_to_all(const void *x_bf16, int64_t T, int64_t H, int6
     const uint16_t *xb = static_cast<const uint16_t *>(x_bf16);
     uint32_t *partial = static_cast<uint32_t *>(workspace);
     int n_partial = 0;
+    if (!global_scale_in && quantize_rows_resident_fits(T * H, d, d, false)) {
+        // small enough to stay on the chip between the maximum and the encoding: one launch
+        hipError_t e1 = launch_quantize_rows_resident(xb, T * H, d, partial, out->codes, out->scales, out->global_scale, false,
+                                                      nullptr, s, (int)H, (int)(H / P));
+        return e1 == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+    }
     if (!global_scale_in)
         if (launch_amax(xb, T * H, d, d, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
     hipError_t e = launch_quantize_rows_slabs(xb, T, H, d, (int)(H / P), global_scale_in, partial, n_partial,

@@ -26,7 +26,7 @@ hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, cons
 bool quantize_rows_resident_fits(int64_t rows, int64_t C, int64_t ld, bool smooth);
 hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_t C, uint32_t *partial, uint8_t *codes,
                                          uint8_t *scales, float *gs_out, bool scale_search, uint16_t *mean_out,
-                                         hipStream_t s);
+                                         hipStream_t s, int heads = 0, int slab_heads = 0);   // slab_heads > 0: all-to-all slab order
 void set_resident_spin_limit(uint32_t ticks);      // bound of the grid-wide wait, 10 ns ticks (0: give up at once)
 uint32_t resident_spin_limit();
 

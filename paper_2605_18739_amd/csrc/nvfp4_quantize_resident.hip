@@ -57,7 +57,20 @@ struct ResidentArgs {
     uint8_t *codes, *scales;
     float *gs_out;
     uint16_t *mean_out;         // SMOOTH: [rows] bf16 row means
+    // slab_heads > 0: the rows are (token, head) pairs of a [T, H, d] tensor and the output is regrouped into
+    // H / slab_heads slabs of slab_heads heads each, [slab][token][head in slab] (the all-to-all send buffers)
+    uint32_t nb_row, heads, slab_heads, tokens;
 };
+
+// output block index of input block g (fewer than 2^32 blocks fit on the chip: 32-bit arithmetic)
+__device__ __forceinline__ uint32_t output_block(uint32_t g, const ResidentArgs &a)
+{
+    if (a.slab_heads == 0) return g;
+    const uint32_t row = g / a.nb_row, b = g - row * a.nb_row;
+    const uint32_t t = row / a.heads, h = row - t * a.heads;
+    const uint32_t slab = h / a.slab_heads, hl = h - slab * a.slab_heads;
+    return ((slab * a.tokens + t) * a.slab_heads + hl) * a.nb_row + b;
+}
 
 // maximum of two pairs of 16-bit patterns, half by half
 __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
@@ -102,7 +115,7 @@ struct Pass2Out {
 // hardware drops, so no branch surrounds the stores and the compiler can schedule across them.
 template <bool SEARCH>
 __device__ __forceinline__ void pair_pass2(const uint32_t (&wa)[8], const uint32_t (&wb)[8], int64_t ga, int64_t gb, int64_t nblk,
-                                           float sg, float inv_6sg, float inv_4sg, const Pass2Out &out)
+                                           float sg, float inv_6sg, float inv_4sg, const Pass2Out &out, const ResidentArgs &a)
 {
     uint32_t sa, a0, a1, sb, b0, b1;
     if constexpr (SEARCH) {
@@ -113,10 +126,11 @@ __device__ __forceinline__ void pair_pass2(const uint32_t (&wa)[8], const uint32
     }
     constexpr uint32_t kDropped = 0x80000000u;
     const bool live_a = ga < nblk, live_b = gb < nblk;
-    __builtin_amdgcn_raw_buffer_store_b64(uint2v{a0, a1}, out.rcodes, live_a ? (uint32_t)ga << 3 : kDropped, 0, 2 /* nontemporal */);
-    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sa, out.rscales, live_a ? (uint32_t)ga : kDropped, 0, 0);
-    __builtin_amdgcn_raw_buffer_store_b64(uint2v{b0, b1}, out.rcodes, live_b ? (uint32_t)gb << 3 : kDropped, 0, 2);
-    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, out.rscales, live_b ? (uint32_t)gb : kDropped, 0, 0);
+    const uint32_t oa = live_a ? output_block((uint32_t)ga, a) : 0u, ob = live_b ? output_block((uint32_t)gb, a) : 0u;
+    __builtin_amdgcn_raw_buffer_store_b64(uint2v{a0, a1}, out.rcodes, live_a ? oa << 3 : kDropped, 0, 2 /* nontemporal */);
+    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sa, out.rscales, live_a ? oa : kDropped, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b64(uint2v{b0, b1}, out.rcodes, live_b ? ob << 3 : kDropped, 0, 2);
+    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)sb, out.rscales, live_b ? ob : kDropped, 0, 0);
 }
 
 template <bool SEARCH, bool SMOOTH>
@@ -267,8 +281,9 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
             uint32_t sbyte, c0, c1;
             if constexpr (SEARCH) quantize_block16_4over6_exact(w, shift, sgq, 1.0f / (6.0f * sgq), 1.0f / (4.0f * sgq), sbyte, c0, c1);
             else quantize_block16_exact(w, shift, sgq, 1.0f / (6.0f * sgq), sbyte, c0, c1);
-            *(uint2v *)(a.codes + (g << 3)) = uint2v{c0, c1};
-            a.scales[g] = (uint8_t)sbyte;
+            const int64_t go = output_block((uint32_t)g, a);
+            *(uint2v *)(a.codes + (go << 3)) = uint2v{c0, c1};
+            a.scales[go] = (uint8_t)sbyte;
         }
         return;
     }
@@ -279,7 +294,7 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
             const uint32_t wa[8] = {r0[i].x, r0[i].y, r0[i].z, r0[i].w, r1[i].x, r1[i].y, r1[i].z, r1[i].w};
             const uint32_t wb[8] = {r0[i + 1].x, r0[i + 1].y, r0[i + 1].z, r0[i + 1].w, r1[i + 1].x, r1[i + 1].y, r1[i + 1].z, r1[i + 1].w};
             // (slot i + 1 beyond the slots in use holds zeros and lies past the end of the tensor)
-            pair_pass2<SEARCH>(wa, wb, block_of(i), i + 1 < nr ? block_of(i + 1) : a.nblk, a.nblk, sg, inv_6sg, inv_4sg, out);
+            pair_pass2<SEARCH>(wa, wb, block_of(i), i + 1 < nr ? block_of(i + 1) : a.nblk, a.nblk, sg, inv_6sg, inv_4sg, out, a);
         }
     });
     // The blocks in LDS belong to no wave in particular, so they are handed out from a queue: 64 lanes x 2 slots per
@@ -299,7 +314,7 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
         const uint32_t wa[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
         const uint32_t wb[8] = {v2.x, v2.y, v2.z, v2.w, v3.x, v3.y, v3.z, v3.w};
         const int64_t ga = wg_first + (int64_t)(kResRegSlots + s) * kResThreads + t;
-        pair_pass2<SEARCH>(wa, wb, ga, two ? ga + kResThreads : a.nblk, a.nblk, sg, inv_6sg, inv_4sg, out);
+        pair_pass2<SEARCH>(wa, wb, ga, two ? ga + kResThreads : a.nblk, a.nblk, sg, inv_6sg, inv_4sg, out, a);
     }
 }
 
@@ -343,7 +358,7 @@ static hipError_t launch_resident(const ResidentArgs &a, int grid, hipStream_t s
 
 hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_t C, uint32_t *partial, uint8_t *codes,
                                          uint8_t *scales, float *gs_out, bool scale_search, uint16_t *mean_out,
-                                         hipStream_t s)
+                                         hipStream_t s, int heads, int slab_heads)
 {
     ResidentArgs a{};
     a.x = x;
@@ -360,6 +375,10 @@ hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_
     a.scales = scales;
     a.gs_out = gs_out;
     a.mean_out = mean_out;
+    a.nb_row = (uint32_t)(C >> 4);
+    a.heads = (uint32_t)heads;
+    a.slab_heads = (uint32_t)slab_heads;
+    a.tokens = heads > 0 ? (uint32_t)(rows / heads) : 0u;
     if (mean_out) return launch_resident<true, true>(a, grid, s);       // smoothed keys always take the scale search
     return scale_search ? launch_resident<true, false>(a, grid, s) : launch_resident<false, false>(a, grid, s);
 }
