@@ -510,7 +510,49 @@ __device__ __forceinline__ void rht_block16(uint32_t (&w)[8], uint32_t sign_mask
             }
 #pragma unroll
     for (int i = 0; i < 8; ++i)
-        w[i] = bf16_rne_signed_from_f64(0.25 * v[2 * i]) | (bf16_rne_signed_from_f64(0.25 * v[2 * i + 1]) << 16);
+        // (+ 0.0: a sum that is zero is +0, as when the terms are added up from zero; only groups of negative zeros differ)
+        w[i] = bf16_rne_signed_from_f64(0.25 * v[2 * i] + 0.0) | (bf16_rne_signed_from_f64(0.25 * v[2 * i + 1] + 0.0) << 16);
+}
+
+// The same transform in fp32, and the test that tells when it returns the same bits.  With all non-zero
+// magnitudes of the group within 12 binades of the largest, every value is a multiple of 2^(e_min - 7) and every
+// partial sum stays below 2^(e_max + 5): at most 24 significant bits, so the fp32 butterflies are exact and the one
+// rounding to bf16 (v_cvt_pk_bf16_f32, nearest even) is the rounding of the exact value, as in the fp64 form.
+// Groups near the ends of the exponent range (sums that could overflow, results that could be subnormal) and
+// all-zero groups are left to the fp64 form as well.  Gaussian data fails the test in about 1 % of the groups.
+__device__ __forceinline__ bool rht_fp32_is_exact(const uint32_t (&w)[8])
+{
+    const ushort2v one = {1, 1};
+    ushort2v mx = {0, 0}, mn = {0xFFFF, 0xFFFF};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const ushort2v a = __builtin_bit_cast(ushort2v, w[i]) << one;          // sign dropped: exponent in bits 15..8
+        mx = __builtin_elementwise_max(mx, a);
+        mn = __builtin_elementwise_min(mn, a - one);                            // zeros wrap to 0xFFFF and never win
+    }
+    const uint32_t hmax = max((uint32_t)mx.x, (uint32_t)mx.y), hmin = min((uint32_t)mn.x, (uint32_t)mn.y) + 1u;
+    const int emax = (int)(hmax >> 8), emin = max((int)(hmin >> 8), 1);
+    return emax >= 40 && emax <= 240 && emax - emin <= 12;
+}
+__device__ __forceinline__ void rht_block16_f32(uint32_t (&w)[8], uint32_t sign_mask)
+{
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        v[2 * i] = __uint_as_float((w[i] << 16) ^ (((sign_mask >> (2 * i)) & 1u) << 31));
+        v[2 * i + 1] = __uint_as_float((w[i] & 0xFFFF0000u) ^ (((sign_mask >> (2 * i + 1)) & 1u) << 31));
+    }
+#pragma unroll
+    for (int h = 1; h < 16; h <<= 1)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if ((i & h) == 0) {
+                const float a = v[i], b = v[i + h];
+                v[i] = a + b;
+                v[i + h] = a - b;
+            }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i] = pack_bf16x2(__builtin_fmaf(0.25f, v[2 * i], 0.0f), __builtin_fmaf(0.25f, v[2 * i + 1], 0.0f));   // (zero sums are +0)
 }
 
 // global scale from the tensor's largest |bf16| pattern: RN_fp32(amax / 2688), 1 if zero

@@ -238,6 +238,19 @@ __device__ __forceinline__ void column_of(const uint4v (&v)[16], int j, uint32_t
     }
 }
 
+// the same for a column index known only at run time (the rare path of the Hadamard kernels)
+__device__ __forceinline__ void column_of_dyn(const uint4v (&v)[16], int j, uint32_t (&w)[8])
+{
+    const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;     // high halves / low halves of (a, b)
+    const bool c1 = (j & 2) != 0, c2 = (j & 4) != 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint4v va = v[2 * i], vb = v[2 * i + 1];
+        const uint32_t a = c2 ? (c1 ? va.w : va.z) : (c1 ? va.y : va.x), b = c2 ? (c1 ? vb.w : vb.z) : (c1 ? vb.y : vb.x);
+        w[i] = __builtin_amdgcn_perm(b, a, sel);
+    }
+}
+
 // Pass 1 for a weight-gradient operand that is Hadamard-transformed along its rows before it is
 // quantized (Sec. 2.2): partial amax of the TRANSFORMED values, same tiles and thread layout as
 // the pass-2 kernel below, tiles dealt over at most kMaxPartials workgroups.
@@ -255,10 +268,25 @@ __global__ __launch_bounds__(256) void amax_rht_kernel(const uint16_t *__restric
             uint4v v[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) v[i] = *(const uint4v *)(x + (r + i) * ld + c);
+            // the fp32 transform for every group; the few groups it is not exact for are noted and redone in fp64
+            uint32_t redo = 0;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 uint32_t w[8];
                 column_of(v, j, w);
+                const bool exact = rht_fp32_is_exact(w);
+                rht_block16_f32(w, sign_mask);
+                uint32_t a = 0;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) a = pk_absmax_u16(a, w[i]);
+                acc = exact ? pk_absmax_u16(acc, a) : acc;
+                redo |= exact ? 0u : (1u << j);
+            }
+            while (redo != 0u) {
+                const int j = __builtin_ctz(redo);
+                redo &= redo - 1u;
+                uint32_t w[8];
+                column_of_dyn(v, j, w);
                 rht_block16(w, sign_mask);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
@@ -301,11 +329,7 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__re
     const float shift = range_shift(sg), sgq = sg * shift;      // (1 and s_g unless the tensor scale is out of the fp32-safe range)
     const float inv_6sg = 1.0f / (6.0f * sgq);
     if (live) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {      // column c + j: element j of every loaded vector
-            uint32_t w[8];
-            column_of(v, j, w);
-            if constexpr (RHT) rht_block16(w, sign_mask);
+        auto encode_column = [&](uint32_t (&w)[8], int j) {     // transformed group -> codes and scale of column c + j
             if (__builtin_expect(shift != 1.0f, 0)) rescale_block16(w, shift);
             uint32_t acc = 0;
 #pragma unroll
@@ -317,6 +341,27 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__re
             uint2v cc = {k0, k1};
             lds_codes[cg * 8 + j][rb] = cc;
             lds_scales[cg * 8 + j][rb] = (uint8_t)sbyte;
+        };
+        uint32_t redo = 0;                 // RHT: groups whose fp32 transform is not exact, redone in fp64 below
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {      // column c + j: element j of every loaded vector
+            uint32_t w[8];
+            column_of(v, j, w);
+            if constexpr (RHT) {
+                redo |= rht_fp32_is_exact(w) ? 0u : (1u << j);
+                rht_block16_f32(w, sign_mask);
+            }
+            encode_column(w, j);
+        }
+        if constexpr (RHT) {
+            while (redo != 0u) {
+                const int j = __builtin_ctz(redo);
+                redo &= redo - 1u;
+                uint32_t w[8];
+                column_of_dyn(v, j, w);
+                rht_block16(w, sign_mask);
+                encode_column(w, j);
+            }
         }
     }
     __syncthreads();

@@ -600,6 +600,31 @@ def test_quantize_rht(oracle, R, C, mask):
     assert_q_equal(got, oracle.quantize(oracle.rht_rows(xb, mask), block_axis=1, global_scale_in=0.0125), "rht, given scale")
 
 
+def test_quantize_rht_groups_of_every_exponent_spread(oracle):
+    """The transform runs in fp32 where that is exact (a group's non-zero magnitudes within 12 binades, away from
+    the ends of the exponent range) and in fp64 elsewhere.  Groups on both sides of every condition: spreads of
+    0..40 binades, all-zero groups, groups of zeros and one value, signed zeros, magnitudes near 2^-120 and 2^120
+    (alone: the tensor scale is shared), exact cancellations (equal values with alternating signs)."""
+    g = np.random.default_rng(77)
+    R, C = 256, 96
+    x = g.standard_normal((R, C)).astype(np.float64)
+    spread = g.integers(0, 41, size=(R // 16, 1, C))                    # per group of 16 rows and column
+    expo = -(g.random((R // 16, 16, C)) * (spread + 1)).astype(np.int64)
+    x = (x.reshape(R // 16, 16, C) * 2.0 ** expo).reshape(R, C)
+    x[0:16, 0:8] = 0.0
+    x[16:32, 0:8] = 0.0
+    x[20, 3] = 1.5
+    x[32:48, 0:8] = -0.0
+    x[48:64, 0:8] = 0.75 * (1 - 2 * (np.arange(16) % 2))[:, None]       # cancels in most outputs
+    x[64:80, 0:8] = 3.0
+    for scale, tag in ((1.0, "unit"), (2.0 ** -118, "tiny"), (2.0 ** 112, "huge")):
+        xb = wl.to_bf16_bits((x * scale).astype(np.float32))
+        for mask in (0x0000, 0xA53C):
+            say(f"[rht] spreads, {tag} magnitudes, mask {mask:#06x}")
+            want = oracle.quantize(oracle.rht_rows(xb, mask), block_axis=1)
+            assert_q_equal(nv.nvfp4_quantize_rht(dev_bf16(xb), mask), want, f"rht spreads {tag} {mask:#x}")
+
+
 def test_wgrad_with_rht(oracle):
     """dW = dY^T X with both operands transformed by the same signs: the GEMM equals the oracle's on
     the oracle's transformed operands; both quantized products approximate the unquantized one (the
