@@ -28,21 +28,31 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_partial_kernel(const uint16
     __shared__ uint32_t wave_max[kAmaxThreads / 64];
     const int64_t vec_per_row = C >> 3;
     const int64_t nvec = R * vec_per_row;
-    const int64_t stride = (int64_t)gridDim.x * kAmaxThreads;
+    // a workgroup reads one contiguous stretch of the tensor, four vectors per lane in flight (contiguous stretches
+    // per workgroup stream about a fifth faster than a grid-wide stride)
+    const int64_t per = (nvec + gridDim.x - 1) / gridDim.x, begin = per * blockIdx.x, end = min(nvec, begin + per);
+    auto offset_of = [&](int64_t i) {
+        if (CONTIG) return i << 3;
+        const int64_t r = i / vec_per_row;
+        return r * ld + ((i - r * vec_per_row) << 3);
+    };
     uint32_t acc = 0;
-    for (int64_t i = (int64_t)blockIdx.x * kAmaxThreads + threadIdx.x; i < nvec; i += stride) {
-        int64_t off;
-        if (CONTIG) off = i << 3;
-        else {
-            int64_t r = i / vec_per_row;
-            off = r * ld + ((i - r * vec_per_row) << 3);
-        }
-        uint4v v = *(const uint4v *)(x + off);    // ordinary load: pass 2 re-reads x, let the caches keep it
+    auto take = [&](uint4v v) {
         acc = pk_absmax_u16(acc, v.x);
         acc = pk_absmax_u16(acc, v.y);
         acc = pk_absmax_u16(acc, v.z);
         acc = pk_absmax_u16(acc, v.w);
+    };
+    int64_t i = begin + threadIdx.x;
+    for (; i + 3 * kAmaxThreads < end; i += 4 * kAmaxThreads) {       // ordinary loads: pass 2 re-reads x, let the caches keep it
+        const uint4v a = *(const uint4v *)(x + offset_of(i)), b = *(const uint4v *)(x + offset_of(i + kAmaxThreads));
+        const uint4v c = *(const uint4v *)(x + offset_of(i + 2 * kAmaxThreads)), d = *(const uint4v *)(x + offset_of(i + 3 * kAmaxThreads));
+        take(a);
+        take(b);
+        take(c);
+        take(d);
     }
+    for (; i < end; i += kAmaxThreads) take(*(const uint4v *)(x + offset_of(i)));
     uint32_t m = wave_max_u32(pk_hmax_u16(acc));
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
     __syncthreads();
