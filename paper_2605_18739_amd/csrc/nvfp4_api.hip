@@ -92,7 +92,7 @@ int quantize_impl(const void *x, int64_t R, int64_t C, int64_t ld, int block_axi
     int n_partial = 0;
     if (!gs_in && block_axis == 0 && quantize_rows_resident_fits(R, C, ld, false)) {
         // the tensor fits on the chip: one launch, one pass over the input
-        hipError_t e = launch_quantize_rows_resident(xb, R, C, partial, out->codes, out->scales, out->global_scale,
+        hipError_t e = launch_quantize_rows_resident(xb, R, C, out->codes, out->scales, out->global_scale,
                                                      scale_search, nullptr, s);
         return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
     }
@@ -208,7 +208,7 @@ int nvfp4_quantize_for_all_to_all(const void *x_bf16, int64_t T, int64_t H, int6
     int n_partial = 0;
     if (!global_scale_in && quantize_rows_resident_fits(T * H, d, d, false)) {
         // small enough to stay on the chip between the maximum and the encoding: one launch
-        hipError_t e1 = launch_quantize_rows_resident(xb, T * H, d, partial, out->codes, out->scales, out->global_scale, false,
+        hipError_t e1 = launch_quantize_rows_resident(xb, T * H, d, out->codes, out->scales, out->global_scale, false,
                                                       nullptr, s, (int)H, (int)(H / P));
         return e1 == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
     }
@@ -292,7 +292,7 @@ int nvfp4_kv_quant_k(const void *k_bf16, int64_t T, int64_t H, int64_t d, nvfp4_
     uint32_t *partial = static_cast<uint32_t *>(workspace);
     int n_partial = 0;
     if (quantize_rows_resident_fits(T * H, d, d, true)) {
-        hipError_t e = launch_quantize_rows_resident(x, T * H, d, partial, out->codes, out->scales, out->global_scale, true,
+        hipError_t e = launch_quantize_rows_resident(x, T * H, d, out->codes, out->scales, out->global_scale, true,
                                                      mean, s);
         return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
     }

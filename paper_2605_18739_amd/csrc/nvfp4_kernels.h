@@ -21,10 +21,10 @@ hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, cons
                                int64_t K, uint16_t *out, hipStream_t s);
 
 // One-launch variant for contiguous tensors that fit on the chip (registers + LDS of 256 compute units): every
-// workgroup loads its slice once, the tensor maximum crosses the grid through `partial` and a bounded wait, the
+// workgroup loads its slice once, the tensor maximum crosses the grid through library-owned words and a bounded wait, the
 // codes are produced from the on-chip copy.  mean_out != nullptr: the smoothed-key path (row means removed, scale search).
 bool quantize_rows_resident_fits(int64_t rows, int64_t C, int64_t ld, bool smooth);
-hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_t C, uint32_t *partial, uint8_t *codes,
+hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_t C, uint8_t *codes,
                                          uint8_t *scales, float *gs_out, bool scale_search, uint16_t *mean_out,
                                          hipStream_t s, int heads = 0, int slab_heads = 0);   // slab_heads > 0: all-to-all slab order
 void set_resident_spin_limit(uint32_t ticks);      // bound of the grid-wide wait, 10 ns ticks (0: give up at once)

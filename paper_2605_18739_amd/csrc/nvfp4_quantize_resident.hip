@@ -48,9 +48,7 @@ __device__ __forceinline__ void static_for_slots(F &&f)
 struct ResidentArgs {
     const uint16_t *x;          // [rows, C] contiguous
     int64_t nblk;               // rows * C / 16
-    int nb;                     // slots in use per lane: ceil(nblk / (grid * 512))
     int row_shift;              // SMOOTH: log2(C / 16)
-    uint32_t *partial;          // (the caller's workspace: unused by this path except by timing builds)
     int sync_slot;
     uint32_t epoch;             // of this call on its slot, never 0
     uint32_t spin_limit;        // bound of the grid-wide wait in 10 ns ticks
@@ -147,7 +145,7 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
     // workgroup move about a fifth more bytes per second through HBM than a grid-wide stride does.)
     const int64_t n_units = (a.nblk + kResThreads - 1) / kResThreads;
     const int64_t unit0 = n_units * blockIdx.x / G, unit1 = n_units * (blockIdx.x + 1) / G;
-    const int nb = (int)(unit1 - unit0);                               // slots this workgroup uses, <= a.nb
+    const int nb = (int)(unit1 - unit0);                               // slots this workgroup uses (at most kResSlots)
     const int64_t wg_first = unit0 * kResThreads;
     const int nr = min(nb, kResRegSlots), nl = nb - nr;                // register slots / LDS slots in use
     auto block_of = [&](int slot) { return wg_first + (int64_t)slot * kResThreads + tid; };
@@ -356,7 +354,7 @@ static hipError_t launch_resident(const ResidentArgs &a, int grid, hipStream_t s
     return hipGetLastError();
 }
 
-hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_t C, uint32_t *partial, uint8_t *codes,
+hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_t C, uint8_t *codes,
                                          uint8_t *scales, float *gs_out, bool scale_search, uint16_t *mean_out,
                                          hipStream_t s, int heads, int slab_heads)
 {
@@ -364,9 +362,7 @@ hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_
     a.x = x;
     a.nblk = rows * (C >> 4);
     const int grid = (int)std::min<int64_t>(kResMaxGrid, (a.nblk + kResThreads - 1) / kResThreads);
-    a.nb = (int)((a.nblk + (int64_t)grid * kResThreads - 1) / ((int64_t)grid * kResThreads));
     a.row_shift = mean_out ? __builtin_ctzll((unsigned long long)(C >> 4)) : 0;
-    a.partial = partial;
     a.sync_slot = (int)(g_next_sync_slot++ % kSyncSlots);
     if (++g_sync_epoch[a.sync_slot] == 0) ++g_sync_epoch[a.sync_slot];
     a.epoch = g_sync_epoch[a.sync_slot];
