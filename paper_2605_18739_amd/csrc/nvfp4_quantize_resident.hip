@@ -30,11 +30,17 @@ constexpr int kResMaxGrid = 256;          // one workgroup per compute unit
 
 // The grid-wide exchange of the workgroups' maxima: one 64-bit word per workgroup and call in flight,
 // (epoch << 32) | maximum, in memory the library owns.  A workgroup publishes its word with one store
-// and then watches the others' words until each carries the epoch of this call; epochs of a slot never
-// repeat (32 bits, counted on the host), so words left by earlier calls are never mistaken for this
-// call's, nothing has to be cleared, and there is no counter for 256 workgroups to queue up on.
+// and then watches the others' words until each carries the epoch of this launch; epochs of a slot never
+// repeat (32 bits), so words left by earlier launches are never mistaken for this one's, nothing has to be
+// cleared, and no workgroup waits on a counter.
+// The epoch is counted ON THE DEVICE, so that a launch replayed from a captured graph (the same kernel
+// arguments every time) still gets a fresh one: every workgroup reads the slot's counter and then registers
+// itself; the last to register advances the counter for the NEXT launch on the slot, which stream order
+// places after this one.  Launches that overlap on one slot (more than 64 calls in flight at once, or one
+// captured graph replayed concurrently with itself) would race.
 constexpr int kSyncSlots = 64;
 static __device__ unsigned long long g_grid_words[kSyncSlots][kResMaxGrid];
+static __device__ uint32_t g_slot_epoch[kSyncSlots], g_slot_arrivals[kSyncSlots];
 
 template <int First, int Last, class F>
 __device__ __forceinline__ void static_for_slots(F &&f)
@@ -50,7 +56,6 @@ struct ResidentArgs {
     int64_t nblk;               // rows * C / 16
     int row_shift;              // SMOOTH: log2(C / 16)
     int sync_slot;
-    uint32_t epoch;             // of this call on its slot, never 0
     uint32_t spin_limit;        // bound of the grid-wide wait in 10 ns ticks
     uint8_t *codes, *scales;
     float *gs_out;
@@ -150,7 +155,12 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
     const int nr = min(nb, kResRegSlots), nl = nb - nr;                // register slots / LDS slots in use
     auto block_of = [&](int slot) { return wg_first + (int64_t)slot * kResThreads + tid; };
     uint32_t *queue_head = lds_red + 12;                               // tickets for the LDS slots in pass 2
-    if (tid == 0) *queue_head = 0;
+    uint32_t epoch = 0, arrival = 0;                                   // (lane 0 of the workgroup only)
+    if (tid == 0) {
+        *queue_head = 0;
+        epoch = __hip_atomic_load(&g_slot_epoch[a.sync_slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+        if (epoch == 0u) epoch = 1u;                                   // (0 is what never-written words hold)
+    }
 
     // ---- pass 1: load every block once; registers first (all loads in flight together), then LDS slots
     uint4v r0[kResRegSlots], r1[kResRegSlots];
@@ -167,6 +177,13 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
             }
         }
     });
+    if (tid == 0) {
+        // register only once the counter has been read (the empty asm makes the increment depend on the value read;
+        // the wait it costs is for that one load, the oldest in flight, not for the data loads issued since)
+        uint32_t one = 1;
+        asm volatile("" : "+v"(one) : "v"(epoch));
+        arrival = atomicAdd(&g_slot_arrivals[a.sync_slot], one);
+    }
     uint32_t amax = 0;                       // two running maxima of |bf16| patterns, one per half
     {   // LDS slots, two blocks in flight
         uint4v n0 = {0, 0, 0, 0}, n1 = {0, 0, 0, 0};
@@ -207,13 +224,21 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
     // bypass the per-XCD caches by themselves): no cache write-back or invalidation is needed around them.
     uint32_t m = wave_max_u32(pk_hmax_u16(amax));
     if ((tid & 63) == 0) lds_red[tid >> 6] = m;
+    if (tid == 0) {
+        lds_red[11] = epoch;
+        if (arrival == (uint32_t)G - 1u) {          // every workgroup of this launch has read the counter: advance it
+            __hip_atomic_store(&g_slot_arrivals[a.sync_slot], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&g_slot_epoch[a.sync_slot], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
     __syncthreads();
+    epoch = lds_red[11];
     unsigned long long *words = g_grid_words[a.sync_slot];
     if (tid == 0) {
         uint32_t all = 0;
 #pragma unroll
         for (int w = 0; w < kResThreads / 64; ++w) all = max(all, lds_red[w]);
-        __hip_atomic_store(&words[blockIdx.x], ((unsigned long long)a.epoch << 32) | all, __ATOMIC_RELAXED,
+        __hip_atomic_store(&words[blockIdx.x], ((unsigned long long)epoch << 32) | all, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     }
     // lane t watches workgroup t's word; the wait is bounded
@@ -224,7 +249,7 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
         seen = false;
         for (;;) {
             const unsigned long long v = __hip_atomic_load(&words[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((uint32_t)(v >> 32) == a.epoch) {
+            if ((uint32_t)(v >> 32) == epoch) {
                 tmax = (uint32_t)v;
                 seen = true;
                 break;
@@ -319,7 +344,6 @@ __global__ __launch_bounds__(kResThreads) void quantize_rows_resident_kernel(Res
 // ---- host side ------------------------------------------------------------------------------------
 static uint32_t g_spin_limit = 200000;        // 2 ms in 10 ns ticks
 static unsigned g_next_sync_slot = 0;
-static uint32_t g_sync_epoch[kSyncSlots] = {};   // per device would be finer; one count serves all devices (epochs only have to differ)
 
 void set_resident_spin_limit(uint32_t ticks) { g_spin_limit = ticks; }
 uint32_t resident_spin_limit() { return g_spin_limit; }
@@ -364,8 +388,6 @@ hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_
     const int grid = (int)std::min<int64_t>(kResMaxGrid, (a.nblk + kResThreads - 1) / kResThreads);
     a.row_shift = mean_out ? __builtin_ctzll((unsigned long long)(C >> 4)) : 0;
     a.sync_slot = (int)(g_next_sync_slot++ % kSyncSlots);
-    if (++g_sync_epoch[a.sync_slot] == 0) ++g_sync_epoch[a.sync_slot];
-    a.epoch = g_sync_epoch[a.sync_slot];
     a.spin_limit = g_spin_limit;
     a.codes = codes;
     a.scales = scales;

@@ -996,6 +996,62 @@ def test_ffn_step_replays_from_a_hip_graph():
         del A2
 
 
+def test_one_launch_quantizer_replayed_from_a_graph_on_changing_data(oracle):
+    """The one-launch quantizer tells the maxima of this launch from those of earlier ones by an epoch.  A
+    captured launch is replayed with identical kernel arguments, so the epoch is counted on the device: every
+    replay below quantizes NEW contents of the same buffer (tensor maximum moved to another workgroup's slice,
+    larger, then much smaller than before), with eager calls of the same entry points in between, and must
+    return the oracle's bytes each time.  Plain rule, scale search, smoothed keys and the allocation-free entry."""
+    g = np.random.default_rng(404)
+    R, C = 3000, 1040                                   # several register slots on 256 workgroups, ragged tail
+    x = torch.empty((R, C), dtype=torch.bfloat16, device="cuda")
+    kv = torch.empty((200, 24, 128), dtype=torch.bfloat16, device="cuda")
+    q6, q46 = nv.NVFP4Tensor(R, C, "cuda"), nv.NVFP4Tensor(R, C, "cuda")
+    qk, qn = nv.NVFP4Tensor(200 * 24, 128, "cuda"), nv.NVFP4Tensor(200 * 24, 128, "cuda")
+    mean = torch.empty(200 * 24, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(max(nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE, R, C), nv.nvfp4_workspace_bytes(nv.OP_KV_QUANT_K, 200, 24, 128)),
+                     dtype=torch.uint8, device="cuda")
+
+    def fill(rep):
+        xs = g.standard_normal((R, C)).astype(np.float32) * np.float32([1.0, 3.0, 0.01, 40.0][rep])
+        xs[g.integers(0, R), g.integers(0, C)] = np.float32([50.0, 900.0, 0.5, 7000.0][rep])
+        ks = wl.bf16_bits_to_f32(wl.kv_tensor(200, 24, 128, 8, rep)) * np.float32([1.0, 0.02, 30.0, 4.0][rep]) + np.float32(0.75)
+        xb, kb = wl.to_bf16_bits(xs), wl.to_bf16_bits(ks.astype(np.float32))
+        x.copy_(dev_bf16(xb))
+        kv.copy_(dev_bf16(kb).reshape(200, 24, 128))
+        return xb, kb.reshape(4800, 128)
+
+    def step():
+        nv.nvfp4_quantize(x, out=q6, workspace=ws)
+        nv.nvfp4_quantize_4over6(x, out=q46, workspace=ws)
+        nv.nvfp4_kv_quant_k(kv, out=qk, row_mean=mean, workspace=ws)
+        nv.nvfp4_kv_quant_noalloc(kv, out=qn)
+
+    fill(0)
+    step()                                              # eager: first use of every kernel variant
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        xb, kb = fill(rep)
+        other = nv.nvfp4_quantize(dev_bf16(xb[:500]))   # eager launches between the replays use the same slots in turn
+        torch.cuda.synchronize()
+        say(f"[graph] one-launch quantizer, replay {rep}")
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_q_equal(q6, oracle.quantize(xb), f"plain, replay {rep}")
+        assert_q_equal(q46, oracle.quantize(xb, four_over_six=True), f"search, replay {rep}")
+        want_mean, want_k = _oracle_k_path(oracle, kb)
+        assert (nv.bits_from_bf16(mean) == want_mean).all(), f"row means, replay {rep}"
+        assert_q_equal(qk, want_k, f"smoothed keys, replay {rep}")
+        assert_q_equal(qn, oracle.quantize(kb), f"allocation-free entry, replay {rep}")
+        del other
+
+
 def test_full_size_ffn_pair_config3(oracle):
     cfg = wl.config3()
     M, D, F = wl.TOKENS_INFER, wl.D_MODEL, wl.D_FFN
