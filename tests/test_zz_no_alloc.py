@@ -23,13 +23,16 @@ def _same(a, b, what):
 
 
 def test_kv_quant_noalloc_matches_kv_quant_two_calls_in_a_row():
-    """Two calls in a row on the library's own scratch array, the second with a smaller input (fewer
-    partial maxima than the first call left behind), each bit for bit what nvfp4_kv_quant gives."""
+    """Calls in a row on the library's own scratch array, each with a smaller input than the one before and each
+    bit for bit what nvfp4_kv_quant gives.  The first two windows (141 MB and 126 MB of bf16) are too large to stay
+    on the chip, so they take the two-pass kernels, whose partial maxima live in the scratch array; the third is
+    small and takes the one-launch kernel, which leaves the array alone."""
     H, d = 24, 128
-    shapes = [(2200, H, d), (37, H, d)]           # 256 partial maxima, then 14
+    shapes = [(23000, H, d), (20500, H, d), (37, H, d)]
     kvs = [dev_bf16(wl.kv_tensor(T, h, dd, 4, i)) for i, (T, h, dd) in enumerate(shapes)]
-    # the second tensor is much smaller in magnitude, so a stale maximum of the first call would show
+    # every tensor is much smaller in magnitude than the one before, so a stale maximum of an earlier call would show
     kvs[1] = (kvs[1].float() * 2.0 ** -6).to(torch.bfloat16)
+    kvs[2] = (kvs[2].float() * 2.0 ** -12).to(torch.bfloat16)
     want = [nv.nvfp4_kv_quant(kv) for kv in kvs]
     outs = [nv.NVFP4Tensor(T * h, dd, "cuda") for (T, h, dd) in shapes]
     for o in outs:
