@@ -229,7 +229,9 @@ int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_t
  * hipMalloc.  Same arguments and the same bytes as nvfp4_kv_quant, minus the workspace: the
  * partial maxima live in a fixed array inside the library's device image (4 KB on every GPU
  * the library runs on, held until the process ends; its address is looked up on the first
- * call on a device).  The call allocates nothing, frees nothing and calls no allocating
+ * call on a device).  Windows that fit on the chip (up to ~120 MB of bf16) take the one-launch
+ * kernel, which needs no partial maxima and leaves the array alone; larger ones take the two
+ * passes that use it.  The call allocates nothing, frees nothing and calls no allocating
  * routine; launch timing does not record it.
  * Limit: T * H * d <= NVFP4_NOALLOC_MAX_ELEMENTS, NVFP4_ERR_SHAPE beyond it.
  * All calls on one GPU share that array, and it keeps the last call's contents (every slot a
@@ -339,7 +341,11 @@ int  nvfp4_timing_read(int op, int *calls, float *total_ms);
  * workgroups through a grid-wide wait that is bounded: a workgroup that has waited longer than this
  * many 10 ns ticks stops waiting and derives the maximum from the tensor itself (slow, same result).
  * Default 200000 (2 ms); 0 makes every workgroup give up at once, which is how the tests exercise
- * that path; 0xFFFFFFFF restores the default.  Applies to calls made afterwards. */
+ * that path; 0xFFFFFFFF restores the default.  Applies to calls made afterwards.
+ * The exchange runs through 64 slots of library-owned device memory taken in turn, and tells one
+ * launch from the next by an epoch counted on the device, so a call captured into a HIP graph can
+ * be replayed; more than 64 such launches in flight at once on one GPU, or one graph replayed
+ * concurrently with itself, would race. */
 void nvfp4_set_sync_spin_limit(uint32_t ticks_10ns);
 
 /* Every recorded duration of entry point `op`, in call order: up to max_records values in ms_out
@@ -348,7 +354,7 @@ int  nvfp4_timing_read_all(int op, float *ms_out, int max_records);
 
 /* Ceiling probes for benchmarks (no part of the NVFP4 path): what the GPU sustains on plain
  * streaming kernels and on back-to-back matrix instructions, to set the library's kernels against.
- *   kind 0: read `bytes` of a once (b: a sink of >= 8 KB, practically never written)
+ *   kind 0: read `bytes` of a once (b: a sink of >= 16 KB, practically never written)
  *   kind 1: write `bytes` to b          kind 2: copy `bytes` from a to b
  *   kind 3: 256 workgroups x 4 waves, each `iters` x 64 v_mfma_f32_32x32x16_f16 on register-resident
  *           pseudo-random operands (b: a sink of >= 256 KB, practically never written);
