@@ -1,6 +1,6 @@
 // Block-scaled FP4 GEMM for gfx950 (Sec. 2.2 / 3.1; Appendix "Implementation Details"): the host
-// side (launch plan, chunking, dispatch to the tile shapes of nvfp4_gemm_tile.h), the untiled
-// fallback kernel, and the down projection of the LoRA side branch.
+// side (launch plan, chunking, dispatch to the tile shapes of nvfp4_gemm_tile.h), the fallback
+// kernel for odd shapes, and the down projection of the LoRA side branch.
 #include "nvfp4_gemm_tile.h"
 #include "nvfp4_gemm_plan.h"
 
@@ -116,31 +116,128 @@ __global__ __launch_bounds__(256) void lora_down_reduce_kernel(const float *__re
     *(uint2v *)(t + i) = uint2v{pack_bf16x2(sum.x, sum.y), pack_bf16x2(sum.z, sum.w)};
 }
 
-// Any K % 16 == 0, any M, N: one output per thread, plain loop.  Only used for
-// shapes the tiled kernel does not take (K not a multiple of 64, N not a
-// multiple of 8); not a performance path.
-__global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g)
+// ============================================================================
+// Shapes the register-dequantizing kernels do not take (K not a multiple of 64, N not a multiple
+// of 8): any M, N and any K % 16 == 0.  128 x 128 tiles, 2 x 2 waves of 64 x 64, 64-k steps.  Operands
+// are staged through registers: a thread fetches four (row, 16-element block) items per step -- eight
+// bytes of codes and one scale byte each -- expands them to f16 (code x block scale is exact in f16)
+// and writes 32 bytes to LDS (same swizzle as the kernels above), one step ahead of the MFMAs; rows
+// past the end of an operand and blocks past the end of K are staged as zeros.  Outputs are stored
+// straight from the accumulator layout with a guard per element.  A fallback for odd shapes, bound by
+// its LDS traffic (about a quarter of the main kernels' rate), not the performance path.
+// ============================================================================
+constexpr int kEdgeTile = 128;
+__global__ __launch_bounds__(256) void gemm_edge_kernel(GemmArgs g)
 {
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= g.M * g.N) return;
-    const int64_t m = idx / g.N, n = idx - m * g.N;
-    const uint8_t *ca = g.codesA + m * (g.K >> 1), *cw = g.codesW + n * (g.K >> 1);
-    const uint8_t *sa = g.scalesA + m * (g.K >> 4), *sw = g.scalesW + n * (g.K >> 4);
-    float acc = 0.0f;
-    for (int64_t b = 0; b < (g.K >> 4); ++b) {
-        float part = 0.0f;
-        for (int j = 0; j < 8; ++j) {
-            typedef float float2v __attribute__((ext_vector_type(2)));
-            float2v x = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4((uint32_t)ca[b * 8 + j], 1.0f, 0);
-            float2v y = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4((uint32_t)cw[b * 8 + j], 1.0f, 0);
-            part += x.x * y.x + x.y * y.y;     // multiples of 1/4, |sum| <= 576: exact
-        }
-        acc += part * (e4m3_to_f32(sa[b] & 0x7Fu) * e4m3_to_f32(sw[b] & 0x7Fu));   // scale product: 8 bits, exact
+    constexpr int ROWS = 2 * kEdgeTile;                           // staged rows: A rows first, then W rows
+    constexpr int STAGE = ROWS * ROW_BYTES;                       // 32 KB
+    constexpr int ITEMS = ROWS * 4 / 256;                         // (row, block) items per thread and step
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * STAGE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int64_t tiles_n = (g.N + kEdgeTile - 1) / kEdgeTile;
+    const int64_t m0 = (int64_t)(blockIdx.x / tiles_n) * kEdgeTile, n0 = (int64_t)(blockIdx.x % tiles_n) * kEdgeTile;
+    const int64_t kbytes = g.K >> 1, kblocks = g.K >> 4;
+    const int nsteps = (int)((g.K + 63) >> 6);
+    // this thread's items: q = tid + 256 i -> staged row q / 4, block q % 4 of the step
+    const uint8_t *csrc[ITEMS], *ssrc[ITEMS];
+    bool live[ITEMS];
+    int dst[ITEMS][2], blk[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int q = tid + 256 * i, row = q >> 2, b = q & 3;
+        const bool isA = row < kEdgeTile;
+        const int64_t gr = isA ? m0 + row : n0 + (row - kEdgeTile);
+        live[i] = gr < (isA ? g.M : g.N);
+        const int64_t r = live[i] ? gr : 0;                      // (dead rows point at row 0 and are never read)
+        csrc[i] = (isA ? g.codesA : g.codesW) + r * kbytes + 8 * b;
+        ssrc[i] = (isA ? g.scalesA : g.scalesW) + r * kblocks + b;
+        dst[i][0] = lds_chunk_off(row, 2 * b);
+        dst[i][1] = lds_chunk_off(row, 2 * b + 1);
+        blk[i] = b;
     }
-    float y = acc * ((*g.gsA) * (*g.gsW));
-    if (g.ep.act == 1) y = gelu_tanh_f32(y);
-    if (g.ep.out_dtype == 0) ((float *)g.ep.Y)[m * g.ep.ldy + n] = y;
-    else ((uint16_t *)g.ep.Y)[m * g.ep.ldy + n] = (uint16_t)f32_to_bf16_rne(y);
+    uint2v codes[ITEMS];
+    uint32_t scale[ITEMS];
+    auto fetch = [&](int step) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const bool in = live[i] && (int64_t)step * 4 + blk[i] < kblocks;
+            codes[i] = in ? *(const uint2v *)(csrc[i] + (int64_t)step * 32) : uint2v{0u, 0u};
+            scale[i] = in ? (uint32_t)ssrc[i][(int64_t)step * 4] & 0x7Fu : 0u;
+        }
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const _Float16 sc = e4m3_to_f16(scale[i]);
+            const half2v p = {sc, sc};
+            uint32_t x[8];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t w = h ? codes[i].y : codes[i].x;
+                x[4 * h + 0] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 0) * p);
+                x[4 * h + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 1) * p);
+                x[4 * h + 2] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 2) * p);
+                x[4 * h + 3] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(w, 1.0f, 3) * p);
+            }
+            *(uint4v *)(lds + buf * STAGE + dst[i][0]) = uint4v{x[0], x[1], x[2], x[3]};
+            *(uint4v *)(lds + buf * STAGE + dst[i][1]) = uint4v{x[4], x[5], x[6], x[7]};
+        }
+    };
+    float16v acc[2][2];                                           // [column tile][row tile] of this wave's 64 x 64
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[c][j][r] = 0.0f;
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    for (int st = 0; st < nsteps; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < nsteps) fetch(st + 1);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            uint4v fa[2], fw[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                fa[j] = *(const uint4v *)(lds + buf * STAGE + lds_chunk_off(64 * wm + 32 * j + lrow, 2 * kk + lhalf));
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                fw[c] = *(const uint4v *)(lds + buf * STAGE + lds_chunk_off(kEdgeTile + 64 * wn + 32 * c + lrow, 2 * kk + lhalf));
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[c][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, fw[c]),
+                                                                       __builtin_bit_cast(half8v, fa[j]), acc[c][j], 0, 0, 0);
+        }
+        if (st + 1 < nsteps) stage(buf ^ 1);         // the other stage was last read before the previous barrier
+        __syncthreads();
+    }
+    // lane = output row, register r = column 8 (r / 4) + 4 lhalf + r % 4 of the 32-column tile
+    const float alpha = (*g.gsA) * (*g.gsW);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int64_t m = m0 + 64 * wm + 32 * j + lrow;
+        if (m >= g.M) continue;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t n = n0 + 64 * wn + 32 * c + 8 * q + 4 * lhalf;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (n + e >= g.N) continue;
+                    float y = acc[c][j][4 * q + e] * alpha;
+                    if (g.ep.act == 1) y = gelu_tanh_f32(y);
+                    if (g.ep.out_dtype == 0) ((float *)g.ep.Y)[m * g.ep.ldy + n + e] = y;
+                    else ((uint16_t *)g.ep.Y)[m * g.ep.ldy + n + e] = (uint16_t)f32_to_bf16_rne(y);
+                }
+            }
+    }
 }
 
 
@@ -200,8 +297,8 @@ hipError_t launch_gemm(const uint8_t *codesA, const uint8_t *scalesA, const floa
     if (!tiled_ok(M, N, K)) {
         if (with_lora) return hipErrorInvalidValue;      // the untiled fallback has no LoRA phase (callers check gemm_is_tiled)
         if (n_wg) *n_wg = 0;
-        int64_t total = M * N;
-        gemm_generic_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(g);
+        const int64_t tiles = ((M + kEdgeTile - 1) / kEdgeTile) * ((N + kEdgeTile - 1) / kEdgeTile);
+        gemm_edge_kernel<<<(unsigned)tiles, 256, 0, s>>>(g);
         return hipGetLastError();
     }
     // (the tiled fp32 output never carries an activation: nvfp4_gemm has none and the fused call emits bf16)

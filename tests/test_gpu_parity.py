@@ -313,7 +313,10 @@ def test_gemm_config1(oracle):
 
 @pytest.mark.parametrize("M,N,K", [(1, 4, 64), (100, 136, 192), (130, 260, 128), (300, 520, 64),
                                    (513, 1028, 320),
-                                   (1100, 2048, 320)])     # 128x128 tiles, odd number of 64-k steps
+                                   (1100, 2048, 320),      # 128x128 tiles, odd number of 64-k steps
+                                   # shapes of the fallback kernel: K not a multiple of 64 (16, 48, 80: one block,
+                                   # a partial step, one step and a bit), N not a multiple of 8, several tiles each way
+                                   (5, 12, 16), (130, 260, 48), (257, 132, 208), (64, 68, 1040), (300, 264, 80)])
 def test_gemm_ragged_tiles(oracle, M, N, K):
     say(f"[gemm] ragged {M}x{N}x{K}: {nv.nvfp4_gemm_plan(M, N, K)}")
     g = np.random.default_rng(M + N + K)
