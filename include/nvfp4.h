@@ -314,7 +314,7 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c);
 /* The kernel launches nvfp4_gemm (and the GEMM inside nvfp4_gemm_act_quant) issues
  * for an [M, K] x [N, K] problem, as text: one "BMxBN:workgroups" item per launch in
  * launch order, separated by spaces (tile shape and number of workgroups; "generic"
- * for shapes only the untiled fallback kernel takes).  The plan is this library's own
+ * for shapes only the fallback kernel for odd shapes takes: about a third of the tiled rate).  The plan is this library's own
  * (a small cost model over its tile shapes and the 256 compute units): whole waves, or
  * whole tile rows, of large tiles, then the leftover rectangles on tiles that suit them.
  * Host pointers; nothing is launched.

@@ -12,7 +12,7 @@
 // bulk of a problem, 128x128 and 64x64 for small problems and the leftover rectangle of
 // a launch plan): the operands stay 4-bit through LDS (filled by buffer loads that write
 // LDS directly) and are expanded in registers in the shadow of the MFMAs that precede
-// their use.  gemm_generic_kernel takes the shapes the tiles cannot (K or N not a
+// their use.  gemm_edge_kernel (nvfp4_gemm.hip) takes the shapes the tiles cannot (K or N not a
 // multiple of 64 / 8).  plan_gemm picks tile shapes and splits a problem into whole waves
 // of large tiles plus the leftover on small ones.
 //
