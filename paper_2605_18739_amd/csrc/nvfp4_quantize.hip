@@ -569,8 +569,14 @@ struct GatherTable {
 __global__ __launch_bounds__(256) void dequant_gather_kernel(GatherTable t, uint16_t *__restrict__ out)
 {
     __shared__ uint4v table[128];
-    int c = 0;
-    while (c + 1 < t.n_chunks && (int)blockIdx.x >= t.wg_start[c + 1]) ++c;      // uniform
+    // this workgroup's chunk: the last c with wg_start[c] <= blockIdx.x, by bisection (uniform; a linear walk over
+    // the table costs a dependent scalar load per chunk before the first byte of data is requested)
+    int c = 0, hi = t.n_chunks - 1;
+    while (c < hi) {
+        const int mid = (c + hi + 1) >> 1;
+        if ((int)blockIdx.x >= t.wg_start[mid]) c = mid;
+        else hi = mid - 1;
+    }
     const uint8_t *__restrict__ codes = t.codes[c];
     const uint8_t *__restrict__ scales = t.scales[c];
     const uint16_t *__restrict__ mean = t.mean[c];
