@@ -513,6 +513,14 @@ def _rows_train(ctx, res, ws):
     gtime(("dY", 1), ("X", 1), "wgrad_14336x3072x17600")
     gtime(("X", 0), ("W", 0), "fprop_17600x14336x3072_bf16_out", nv.OUT_BF16)
     gtime(("dY", 0), ("W", 1), "dgrad_17600x3072x14336_bf16_out", nv.OUT_BF16)
+    # the same fprop returning the NVFP4 tensor scale of its [17600, 14336] output from the epilogue: what a quantizer
+    # of that output then takes as given (row quantize_dY_given_scale is that call at this size), instead of an amax pass
+    ga, gb = kept[("X", 0)], kept[("W", 0)]
+    y = torch.empty((ga.rows, gb.rows), dtype=torch.bfloat16, device=dev)
+    sc = torch.empty(1, dtype=torch.float32, device=dev)
+    wsg = torch.empty(nv.nvfp4_workspace_bytes(nv.OP_GEMM_SCALE_OUT, ga.rows, gb.rows), dtype=torch.uint8, device=dev)
+    s = ctx.time_op(nv.OP_GEMM_SCALE_OUT, lambda i: nv.nvfp4_gemm_scale_out(ga, gb, Y=y, scale_out=sc, workspace=wsg), 12, warm=4)
+    res["fprop_17600x14336x3072_bf16_out_plus_tensor_scale"] = gemm_row(s, 2.0 * ga.rows * gb.rows * ga.K)
 
 
 def cpu_baseline(cfg, wl, np):

@@ -76,7 +76,7 @@ enum { NVFP4_OP_QUANTIZE = 0, NVFP4_OP_KV_QUANT = 1, NVFP4_OP_GEMM_ACT_QUANT = 2
        NVFP4_OP_KV_DEQUANT_GATHER = 9, NVFP4_OP_QUANTIZE_2D = 10,
        NVFP4_OP_QUANTIZE_RHT = 11, NVFP4_OP_QUANTIZE_A2A = 12,
        NVFP4_OP_LORA_DOWN = 13, NVFP4_OP_GEMM_LORA = 14,
-       NVFP4_OP_PROBE = 15 /* timing only: nvfp4_probe */ };
+       NVFP4_OP_PROBE = 15 /* timing only: nvfp4_probe */, NVFP4_OP_GEMM_SCALE_OUT = 16 };
 
 /*
  * Quantizer (Sec. 2.2, Eq. 2; Eq. 12 with target magnitude 6).
@@ -195,6 +195,21 @@ int nvfp4_lora_down(const void *x_bf16, int64_t M, int64_t K, int64_t ldx, const
 int nvfp4_gemm_lora(const nvfp4_tensor *A, const nvfp4_tensor *W, const void *t_bf16,
                     const void *b_bf16, float lora_scale, void *Y, int64_t ldy, int out_dtype,
                     void *stream);
+
+/*
+ * nvfp4_gemm with bf16 output that also returns the NVFP4 tensor scale of its output,
+ * y_global_scale_out = RN_fp32(max|Y| / 2688) (Sec. 2.2, Eq. 2; 1.0 for an all-zero Y), one float in
+ * device memory.  The quantizer needs a tensor's largest magnitude before it can write the first
+ * code; for tensors too large to stay on the chip that is a pass over the tensor of its own.  A
+ * tensor produced by a GEMM (an activation, a gradient) gets the maximum from the GEMM's epilogue
+ * instead -- one maximum per workgroup, reduced by a small second launch -- so that the calls that
+ * quantize Y afterwards (either axis, with the scale search or the Hadamard transform) take the
+ * scale as given and read Y once each.
+ * Y: [M, ldy] bf16, 16-byte aligned, ldy >= N a multiple of 8.
+ * workspace: nvfp4_workspace_bytes(NVFP4_OP_GEMM_SCALE_OUT, M, N, 0) bytes, 16-byte aligned.
+ */
+int nvfp4_gemm_scale_out(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y_bf16, int64_t ldy,
+                         float *y_global_scale_out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * GEMM with fused activation and re-quantization of the result along N

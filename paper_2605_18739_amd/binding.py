@@ -21,6 +21,7 @@ OP_QUANTIZE_4OVER6, OP_KV_QUANT_4OVER6, OP_KV_QUANT_K, OP_KV_DEQUANT_GATHER = 6,
 KV_MAX_CHUNKS = 64
 NOALLOC_MAX_ELEMENTS = 1 << 32
 OP_QUANTIZE_2D, OP_QUANTIZE_RHT, OP_QUANTIZE_A2A, OP_LORA_DOWN, OP_GEMM_LORA, OP_PROBE = 10, 11, 12, 13, 14, 15
+OP_GEMM_SCALE_OUT = 16
 LORA_RANK = 128
 
 
@@ -52,6 +53,8 @@ def lib():
         L.nvfp4_quantize.argtypes = [vp, i64, i64, i64, c.c_int, vp, tp, vp, sz, vp]
         L.nvfp4_gemm.restype = c.c_int
         L.nvfp4_gemm.argtypes = [tp, tp, vp, i64, c.c_int, vp]
+        L.nvfp4_gemm_scale_out.restype = c.c_int
+        L.nvfp4_gemm_scale_out.argtypes = [tp, tp, vp, i64, vp, vp, sz, vp]
         L.nvfp4_lora_down.restype = c.c_int
         L.nvfp4_lora_down.argtypes = [vp, i64, i64, i64, vp, vp, vp, sz, vp]
         L.nvfp4_gemm_lora.restype = c.c_int
@@ -169,6 +172,21 @@ def nvfp4_gemm(A, W, out_dtype=OUT_F32, Y=None, stream=None):
     _check(lib().nvfp4_gemm(ctypes.byref(ca), ctypes.byref(cw), _ptr(Y), Y.stride(0), out_dtype,
                             _stream(stream)))
     return Y
+
+
+def nvfp4_gemm_scale_out(A, W, Y=None, scale_out=None, workspace=None, stream=None):
+    """bf16 Y = A W^T together with the NVFP4 tensor scale of Y (one float on the device).  Returns (Y, scale_out)."""
+    M, N = A.rows, W.rows
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=A.codes.device)
+    if scale_out is None:
+        scale_out = torch.empty(1, dtype=torch.float32, device=A.codes.device)
+    if workspace is None:
+        workspace = _workspace(nvfp4_workspace_bytes(OP_GEMM_SCALE_OUT, M, N), A.codes.device)
+    ca, cw = A.c(), W.c()
+    _check(lib().nvfp4_gemm_scale_out(ctypes.byref(ca), ctypes.byref(cw), _ptr(Y), Y.stride(0), _ptr(scale_out),
+                                      _ptr(workspace), workspace.numel(), _stream(stream)))
+    return Y, scale_out
 
 
 def nvfp4_lora_down(x, a, out=None, workspace=None, stream=None):

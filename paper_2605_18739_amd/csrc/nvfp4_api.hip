@@ -362,6 +362,38 @@ int nvfp4_gemm(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y, int64_t ld
     return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
 }
 
+int nvfp4_gemm_scale_out(const nvfp4_tensor *A, const nvfp4_tensor *W, void *Y_bf16, int64_t ldy,
+                         float *y_global_scale_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Y_bf16 || !y_global_scale_out) return NVFP4_ERR_NULL;
+    if (int rc = check_gemm(A, W)) return rc;
+    const int64_t M = A->rows, N = W->rows;
+    if (ldy < N) return NVFP4_ERR_SHAPE;
+    const bool tiled = gemm_is_tiled(M, N, A->K);
+    if (!aligned16(Y_bf16) || (ldy & 7) != 0 || (reinterpret_cast<uintptr_t>(y_global_scale_out) & 3u)) return NVFP4_ERR_ALIGN;
+    if (!workspace || workspace_bytes < fused_partial_bytes(M, N)) return NVFP4_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return NVFP4_ERR_ALIGN;
+    std::lock_guard<std::mutex> lk(g_mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Timed t(s, NVFP4_OP_GEMM_SCALE_OUT);
+    uint32_t *partial = static_cast<uint32_t *>(workspace);
+    GemmEpilogue ep{};
+    ep.out_dtype = NVFP4_OUT_BF16;
+    ep.act = NVFP4_ACT_NONE;
+    ep.Y = Y_bf16;
+    ep.ldy = ldy;
+    ep.amax_partial = tiled ? partial : nullptr;        // the tiled kernels' epilogue leaves one maximum per workgroup
+    int n_partial = 0;
+    if (launch_gemm(A->codes, A->scales, A->global_scale, W->codes, W->scales, W->global_scale, M, N, A->K, ep,
+                    &n_partial, s) != hipSuccess)
+        return NVFP4_ERR_LAUNCH;
+    if (n_partial == 0) {                               // odd shape: the fallback kernel has no such epilogue, one pass over Y
+        if (launch_amax(static_cast<const uint16_t *>(Y_bf16), M, N, ldy, partial, &n_partial, s) != hipSuccess)
+            return NVFP4_ERR_LAUNCH;
+    }
+    return launch_scale_from_partials(partial, n_partial, y_global_scale_out, s) == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
+}
+
 int nvfp4_lora_down(const void *x_bf16, int64_t M, int64_t K, int64_t ldx, const void *a_bf16,
                     void *t_bf16, void *workspace, size_t workspace_bytes, void *stream)
 {
@@ -471,6 +503,7 @@ int nvfp4_gemm_act_quant(const nvfp4_tensor *A, const nvfp4_tensor *W, int act,
 size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
 {
     switch (op) {
+    case NVFP4_OP_GEMM_SCALE_OUT: return fused_partial_bytes(a, b);
     case NVFP4_OP_QUANTIZE:
     case NVFP4_OP_KV_QUANT:
     case NVFP4_OP_QUANTIZE_4OVER6:

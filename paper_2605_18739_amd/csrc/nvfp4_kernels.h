@@ -17,6 +17,8 @@ hipError_t launch_quantize_rows(const uint16_t *x, int64_t R, int64_t C, int64_t
 hipError_t launch_quantize_cols(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,
                                 const uint32_t *partial, int n_partial, uint8_t *codes, uint8_t *scales,
                                 float *gs_out, hipStream_t s);
+// gs_out = RN_fp32(max of the partial maxima / 2688) (1 if they are all zero): one small launch
+hipError_t launch_scale_from_partials(const uint32_t *partial, int n_partial, float *gs_out, hipStream_t s);
 hipError_t launch_dequant_bf16(const uint8_t *codes, const uint8_t *scales, const float *gs, int64_t rows,
                                int64_t K, uint16_t *out, hipStream_t s);
 

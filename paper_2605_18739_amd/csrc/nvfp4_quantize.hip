@@ -138,6 +138,15 @@ __device__ __forceinline__ float resolve_global_scale(const float *gs_in, const 
     return sg;
 }
 
+// The tensor scale alone, from partial maxima that something else produced (a GEMM epilogue, an amax pass): one
+// workgroup, one float.  What a later quantizer call takes as its given scale.
+__global__ __launch_bounds__(256) void scale_from_partials_kernel(const uint32_t *__restrict__ partial, int n_partial,
+                                                                  float *__restrict__ gs_out)
+{
+    __shared__ uint32_t lds4[4];
+    (void)resolve_global_scale(nullptr, partial, n_partial, gs_out, lds4);
+}
+
 // --------------------------------------------------------------------------
 // Pass 2, blocks along the contiguous axis: one lane per 16-element block
 // (two 128-bit loads, one 64-bit code store, one scale byte).
@@ -646,6 +655,12 @@ hipError_t launch_amax(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint
     *n_partial = grid;
     if (ld == C) amax_partial_kernel<true><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
     else amax_partial_kernel<false><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_from_partials(const uint32_t *partial, int n_partial, float *gs_out, hipStream_t s)
+{
+    scale_from_partials_kernel<<<1, 256, 0, s>>>(partial, n_partial, gs_out);
     return hipGetLastError();
 }
 

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
             "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6", "nvfp4_kv_quant_k",
             "nvfp4_kv_dequant_gather", "nvfp4_quantize_2d", "nvfp4_quantize_rht",
             "nvfp4_quantize_for_all_to_all", "nvfp4_lora_down", "nvfp4_gemm_lora",
-            "nvfp4_kv_quant_noalloc"} <= set(names)
+            "nvfp4_kv_quant_noalloc", "nvfp4_gemm_scale_out"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -86,6 +86,16 @@ def test_gemm_and_kv_reject_bad_arguments_on_the_host():
     assert L.nvfp4_gemm(ctypes.byref(a), ctypes.byref(w), y, 10, 0, None) == -3                 # ldy % 4
     a64, w64 = _t(rows=4, K=64), _t(rows=8, K=64)                                                 # a shape the tiled kernels take
     assert L.nvfp4_gemm(ctypes.byref(a64), ctypes.byref(w64), y, 12, 1, None) == -3              # bf16 rows must stay 16-byte aligned: ldy % 8
+    # GEMM that also returns the tensor scale of its output
+    gs, ws = ctypes.c_void_p(0x50000), ctypes.c_void_p(0x60000)
+    need = nv.nvfp4_workspace_bytes(nv.OP_GEMM_SCALE_OUT, 4, 8)
+    assert need >= 4096 and need % 256 == 0
+    assert L.nvfp4_gemm_scale_out(ctypes.byref(a64), ctypes.byref(w64), None, 8, gs, ws, need, None) == -1
+    assert L.nvfp4_gemm_scale_out(ctypes.byref(a64), ctypes.byref(w64), y, 8, None, ws, need, None) == -1
+    assert L.nvfp4_gemm_scale_out(ctypes.byref(a64), ctypes.byref(w64), y, 4, gs, ws, need, None) == -2       # ldy < N
+    assert L.nvfp4_gemm_scale_out(ctypes.byref(a64), ctypes.byref(w64), y, 12, gs, ws, need, None) == -3      # ldy % 8
+    assert L.nvfp4_gemm_scale_out(ctypes.byref(a64), ctypes.byref(w64), y, 8, gs, ws, need - 1, None) == -4   # workspace
+    assert L.nvfp4_gemm_scale_out(ctypes.byref(a64), ctypes.byref(w64), y, 8, gs, None, need, None) == -4
     # LoRA branch: rank-128 operands are required; the fused call only takes tiled shapes
     tb = ctypes.c_void_p(0x80000)
     lw = ctypes.c_void_p(0x90000)

@@ -887,6 +887,33 @@ def test_gemm_act_quant(oracle, given_scale):
     _act_quant_case(oracle, 7040, 5296, 2368, given_scale, "three launches", max_flips=0.005)
 
 
+@pytest.mark.parametrize("M,N,K", [(520, 1040, 128), (1100, 2048, 192), (4200, 3072, 128), (300, 272, 80)])
+def test_gemm_scale_out_feeds_the_given_scale_quantizers(oracle, M, N, K):
+    """nvfp4_gemm_scale_out: bf16 Y bit for bit what nvfp4_gemm gives, and the tensor scale of Y from the GEMM's
+    epilogue equal to the oracle's amax / 2688 of those bits.  The calls that quantize Y afterwards take the scale as
+    given (one read of Y each) and return the oracle's bytes along both axes and with the scale search.  Tiled
+    shapes with one and with several launches, and an odd shape that takes the fallback kernel."""
+    say(f"[gemm+scale] {M}x{N}x{K}: {nv.nvfp4_gemm_plan(M, N, K)}")
+    g = np.random.default_rng(M + N + K)
+    ga = nv.nvfp4_quantize(dev_bf16(wl.to_bf16_bits(g.standard_normal((M, K)).astype(np.float32))))
+    gw = nv.nvfp4_quantize(dev_bf16(wl.to_bf16_bits((g.standard_normal((N, K)) * 0.02).astype(np.float32))))
+    y_ref = nv.nvfp4_gemm(ga, gw, nv.OUT_BF16)
+    y = _nan_filled(M, N, torch.bfloat16)
+    scale = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
+    nv.nvfp4_gemm_scale_out(ga, gw, Y=y, scale_out=scale)
+    torch.cuda.synchronize()
+    yb = nv.bits_from_bf16(y)
+    assert (yb == nv.bits_from_bf16(y_ref)).all(), "Y differs from nvfp4_gemm's"
+    want_gs = oracle.global_scale(yb)
+    assert np.float32(scale.item()).view(np.uint32) == np.float32(want_gs).view(np.uint32), "tensor scale of Y"
+    assert_q_equal(nv.nvfp4_quantize(y, global_scale_in=scale), oracle.quantize(yb), "rows, given scale")
+    assert_q_equal(nv.nvfp4_quantize_4over6(y, global_scale_in=scale), oracle.quantize(yb, four_over_six=True), "search")
+    if True:
+        Mt = M - M % 16                                   # blocks along the rows need whole groups of 16 rows
+        assert_q_equal(nv.nvfp4_quantize(y[:Mt], block_axis=1, global_scale_in=scale),
+                       oracle.quantize(yb[:Mt], block_axis=1, global_scale_in=float(want_gs)), "columns, given scale")
+
+
 # -------------------------------------------------------- full benchmark sizes
 
 def test_full_size_projection_config2(oracle):
