@@ -44,3 +44,83 @@ def test_fp32_difference_of_bf16_rounds_like_the_exact_one():
                     bad += int((fast != exact).sum())
                     total += fast.size
     assert total > 10_000_000 and bad == 0
+
+
+def _hadamard16(v):
+    """Butterflies of the 16-point Walsh-Hadamard transform along axis 1, in the dtype of v (one rounding per add)."""
+    v = v.copy()
+    h = 1
+    while h < 16:
+        for i in range(16):
+            if (i & h) == 0:
+                a, b = v[:, i].copy(), v[:, i + h].copy()
+                v[:, i], v[:, i + h] = a + b, a - b
+        h <<= 1
+    return v
+
+
+def _fp32_test_passes(bits):
+    """The kernels' test on the packed exponents of a group of 16 bf16 values (rows of `bits`): all non-zero
+    magnitudes within 12 binades of the largest, the largest exponent field in [40, 240]."""
+    a = (bits.astype(np.uint32) << 1) & 0xFFFF
+    emax = (a.max(axis=1) >> 8).astype(np.int64)
+    am1 = np.where(a == 0, 0xFFFF, a - 1)
+    emin = np.maximum(((am1.min(axis=1) + 1) >> 8).astype(np.int64), 1)
+    return (emax >= 40) & (emax <= 240) & (emax - emin <= 12)
+
+
+def test_fp32_hadamard_of_bf16_groups_is_exact_when_the_exponent_test_passes():
+    """The random Hadamard transform (Sec. 2.2) runs its butterflies in fp32 for groups that pass the exponent
+    test and in fp64 otherwise.  For groups that pass, the fp32 sums carry no rounding at all (equal to the fp64
+    sums, which are exact there), so the one rounding to bf16 that follows is that of the exact value; the test
+    is not vacuous (groups one binade wider do lose bits in fp32), and it lets most Gaussian groups through."""
+    g = np.random.default_rng(12)
+    n = 200_000
+    mant = g.integers(0, 128, size=(n, 16), dtype=np.uint32)
+    sign = g.integers(0, 2, size=(n, 16), dtype=np.uint32)
+    top = g.integers(41, 240, size=(n, 1), dtype=np.uint32)
+    spread = g.integers(0, 16, size=(n, 1))
+    expo = (top - np.minimum(g.integers(0, 16, size=(n, 16)), spread).astype(np.uint32)).astype(np.uint32)
+    bits = (sign << 15) | (expo << 7) | mant
+    bits[g.random((n, 16)) < 0.05] = 0                          # some zeros, which the test ignores
+    x32 = _bf16_to_f32(bits.ravel()).reshape(n, 16)
+    ok = _fp32_test_passes(bits)
+    f32 = _hadamard16(x32.astype(np.float32))
+    f64 = _hadamard16(x32.astype(np.float64))
+    same = (f32.astype(np.float64) == f64).all(axis=1)
+    assert ok.sum() > n // 4 and (~ok).sum() > n // 20
+    assert same[ok].all(), "an fp32 butterfly rounded inside a group that passed the test"
+    assert not same[~ok].all(), "the test rejects nothing that fp32 would get wrong"
+    gauss = g.standard_normal((50_000, 16)).astype(np.float32)
+    gb = _rne_f32_to_bf16(gauss.ravel()).reshape(-1, 16)
+    assert _fp32_test_passes(gb).mean() > 0.97
+
+
+def test_near_tie_difference_is_an_exact_fp32_number():
+    """Near-ties of the E2M1 rounding are settled by the sign of fma(c, s_g, -|x|) in fp32, c = midpoint x block
+    scale.  The claim behind it: when |x| lies within 2^-19 of c s_g, the exact difference c s_g - |x| is itself an
+    fp32 number (c has at most 7 significant bits, s_g 24, |x| 8, and the leading bits cancel), so the one rounding of
+    the fused multiply-add changes nothing and the sign it returns is the sign of the exact difference.  Checked in
+    exact rationals for every midpoint and every E4M3 mantissa: near-ties are made by choosing the tensor scale as
+    the fp32 number nearest to |x| / c, and up to 12 ulps to either side of it (2^-19 is 16 ulps)."""
+    from fractions import Fraction
+    g = np.random.default_rng(5)
+    mids = [Fraction(1, 4), Fraction(3, 4), Fraction(5, 4), Fraction(7, 4), Fraction(5, 2), Fraction(7, 2), Fraction(5)]
+    checked = zero = 0
+    for _ in range(40):
+        xbits = np.uint32((int(g.integers(60, 200)) << 7 | int(g.integers(0, 128))) << 16)
+        x = Fraction(float(xbits.view(np.float32)))
+        for m3 in range(8):
+            sb = Fraction(8 + m3, 8) * Fraction(2) ** int(g.integers(-6, 9))
+            for t in mids:
+                c = t * sb
+                assert np.float32(float(c)) == float(c)                      # c itself is exact in fp32
+                centre = int(np.float32(float(x / c)).view(np.uint32))
+                for off in (-12, -5, -1, 0, 1, 2, 7, 12):
+                    sg = Fraction(float(np.uint32(centre + off).view(np.float32)))
+                    d = c * sg - x
+                    assert abs(d) <= Fraction(1, 2 ** 19) * x                  # a near-tie by construction
+                    assert Fraction(float(np.float32(float(d)))) == d, (float(c), float(sg), float(x))
+                    checked += 1
+                    zero += d == 0
+    assert checked > 10_000 and 0 < zero < checked // 4                        # exact ties occur, most cases are not
