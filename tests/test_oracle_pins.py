@@ -186,6 +186,23 @@ def test_quantize_given_global_scale_brute(oracle):
         assert q.global_scale == sg and (q.scales == scales).all() and (q.codes == codes).all()
 
 
+@pytest.mark.parametrize("k", [-96, -24, 7, 96])
+def test_quantize_commutes_with_power_of_two_scaling(oracle, k):
+    """Eq. 2 / Eq. 12-13 only compare ratios: multiplying the tensor AND its scale by 2^k leaves every scale byte and
+    every code unchanged (plain rule, scale search, both block axes).  The GPU uses this for tensor scales outside the
+    range where fp32 quotients are safe.  Magnitudes chosen so that nothing overflows or becomes subnormal."""
+    g = np.random.default_rng(300 + k)
+    x = (g.standard_normal((48, 64)) * 3.0).astype(np.float32)
+    x[g.random((48, 64)) < 0.1] *= np.float32(2.0 ** -9)                  # some blocks far below the maximum
+    xb = wl.to_bf16_bits(x)
+    xs = wl.to_bf16_bits((wl.bf16_bits_to_f32(xb).astype(np.float64) * 2.0 ** k).astype(np.float32))   # exact in bf16
+    base_gs = oracle.global_scale(xb)
+    assert np.float32(oracle.global_scale(xs)) == np.float32(np.float64(base_gs) * 2.0 ** k)
+    for kw in ({}, {"four_over_six": True}, {"block_axis": 1}):
+        a, b = oracle.quantize(xb, **kw), oracle.quantize(xs, **kw)
+        assert (a.codes == b.codes).all() and (a.scales == b.scales).all(), kw
+
+
 def test_global_scale_closed_forms(oracle):
     x = np.zeros((2, 16), np.float32)
     assert oracle.global_scale(bits(x)) == np.float32(1.0)        # all-zero tensor
