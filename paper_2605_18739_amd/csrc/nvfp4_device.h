@@ -401,8 +401,9 @@ __device__ __forceinline__ void quantize_block16_4over6_inline(const uint32_t (&
     NVFP4_STEP(0, 0) NVFP4_STEP(1, 1) NVFP4_STEP(2, 2) NVFP4_STEP(3, 3)
     NVFP4_STEP(4, 0) NVFP4_STEP(5, 1) NVFP4_STEP(6, 2) NVFP4_STEP(7, 3)
 #undef NVFP4_STEP
-    resolve_codes(w, sb6, sg, l6[0], l6[1], h6[0], h6[1]);
-    resolve_codes(w, sb4, sg, l4[0], l4[1], h4[0], h4[1]);
+    // The errors are taken with the codes of the lower bracket end; only the winner is settled afterwards.  A nibble
+    // on which the two ends disagree lies within 2^-19 of a midpoint T between magnitudes T -+ h, so its squared
+    // error changes by the factor 1 +- 4 (T / h) 2^-19 at most when the nibble flips, and T / h <= 7: below 2^-14.
     const float den6 = sb6 * sg, den4 = sb4 * sg;
     float e6a = 0.0f, e6b = 0.0f, e4a = 0.0f, e4b = 0.0f;
 #define NVFP4_STEP(K, SEL)                                                                                        \
@@ -421,17 +422,26 @@ __device__ __forceinline__ void quantize_block16_4over6_inline(const uint32_t (&
 #undef NVFP4_STEP
     const float e6 = e6a + e6b, e4 = e4a + e4b;
     const float u6 = 0x1p-22f * (bmax + 6.0f * den6), u4 = 0x1p-22f * (bmax + 6.0f * den4);
-    const float r6 = u6 * (8.02f * __builtin_amdgcn_sqrtf(e6) + 16.0f * u6) + 0x1p-19f * e6;   // (eight fused steps and one
-    const float r4 = u4 * (8.02f * __builtin_amdgcn_sqrtf(e4) + 16.0f * u4) + 0x1p-19f * e4;   //  addition: below 2^-19 as well)
+    float r6 = u6 * (8.02f * __builtin_amdgcn_sqrtf(e6) + 16.0f * u6) + 0x1p-19f * e6;   // (eight fused steps and one
+    float r4 = u4 * (8.02f * __builtin_amdgcn_sqrtf(e4) + 16.0f * u4) + 0x1p-19f * e4;   //  addition: below 2^-19 as well)
+    const bool open6 = ((l6[0] ^ h6[0]) | (l6[1] ^ h6[1])) != 0u, open4 = ((l4[0] ^ h4[0]) | (l4[1] ^ h4[1])) != 0u;
+    r6 = open6 ? __builtin_fmaf(0x1p-14f, e6, 1.0001f * r6) : r6;      // the settled codes' error lies within
+    r4 = open4 ? __builtin_fmaf(0x1p-14f, e4, 1.0001f * r4) : r4;      // 2^-14 (e + r) of e as well
     const bool tiny = fminf(e4, e6) < 0x1p-100f;
     const bool same = s4 == s6;                    // (saturated scales, zero blocks: same codes, same error, 6 is kept)
     bool pick4 = e4 + r4 < e6 - r6;
-    if (__builtin_expect(!same & (tiny | !(pick4 | (e4 - r4 > e6 + r6))), 0))
+    if (__builtin_expect(!same & (tiny | !(pick4 | (e4 - r4 > e6 + r6))), 0)) {
+        resolve_codes(w, sb6, sg, l6[0], l6[1], h6[0], h6[1]);
+        resolve_codes(w, sb4, sg, l4[0], l4[1], h4[0], h4[1]);
+        h6[0] = l6[0]; h6[1] = l6[1];
+        h4[0] = l4[0]; h4[1] = l4[1];
         pick4 = block_error_f64(w, l4[0], l4[1], sb4, sg) < block_error_f64(w, l6[0], l6[1], sb6, sg);
+    }
     pick4 &= !same;
     sbyte = pick4 ? s4 : s6;
     c0 = pick4 ? l4[0] : l6[0];
     c1 = pick4 ? l4[1] : l6[1];
+    resolve_codes(w, pick4 ? sb4 : sb6, sg, c0, c1, pick4 ? h4[0] : h6[0], pick4 ? h4[1] : h6[1]);
 }
 #undef NVFP4_CVT4
 
