@@ -470,10 +470,11 @@ def _rows_train(ctx, res, ws):
     ncd, ncw = len(dYs), len(Ws)
     # weight-gradient operand with the random Hadamard transform in front of the transposed quantizer
     qrht = [nv.NVFP4Tensor(F, Mt, dev) for _ in range(ncd)]
-    s = ctx.time_op(nv.OP_QUANTIZE_RHT, lambda i: nv.nvfp4_quantize_rht(dYs[i % ncd], 0x9A3C, out=qrht[i % ncd], workspace=ws), 3 * ncd)
+    ws_rht = ctx.torch.empty(nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE_RHT, Mt, F), dtype=ctx.torch.uint8, device="cuda")
+    s = ctx.time_op(nv.OP_QUANTIZE_RHT, lambda i: nv.nvfp4_quantize_rht(dYs[i % ncd], 0x9A3C, out=qrht[i % ncd], workspace=ws_rht), 3 * ncd)
     res["quantize_rht_T_dY_17600x14336"] = bw_row(
         s, B_PER_ELEM * Mt * F, ctx.oracle_seconds(lambda: ora.quantize(ora.rht_rows(host["dY"], 0x9A3C), block_axis=1)), ncd)
-    del qrht
+    del qrht, ws_rht
     # the scale search on the activations
     q46 = [nv.NVFP4Tensor(Mt, D, dev) for _ in range(len(devs["X"]))]
     ncx = len(q46)

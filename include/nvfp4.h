@@ -125,13 +125,18 @@ int nvfp4_quantize_4over6(const void *x_bf16, int64_t R, int64_t C, int64_t ld,
  * column, v = x[16g .. 16g+15, c], is replaced by
  *   y = RN_bf16( (1/4) H16 diag(s) v ),  H16[i][j] = (-1)^popcount(i & j),
  *   s_j = -1 where bit j of sign_mask is set, +1 otherwise
- * (sums in fp64: exact for groups whose values span less than 2^40), and y is
+ * (exact sums: on the matrix pipes in fp32 where the group's magnitudes lie close
+ * enough together for that to be exact, in fp64 otherwise, which is exact for
+ * groups whose values span less than 2^40), and y is
  * quantized along R exactly as nvfp4_quantize(block_axis = 1) would: out has
  * rows = C, K = R, the tensor scale comes from the amax of y.  The transform
  * is orthogonal: applied with the SAME sign_mask to both operands (dY and X) it
  * leaves the product dY^T X unchanged while spreading outliers over 16 tokens.
  * sign_mask: the caller's random draw, low 16 bits.  R % 16 == 0, C % 8 == 0.
- * workspace: nvfp4_workspace_bytes(NVFP4_OP_QUANTIZE_RHT, R, C, 0).
+ * workspace: nvfp4_workspace_bytes(NVFP4_OP_QUANTIZE_RHT, R, C, 0); the part beyond
+ * nvfp4_workspace_bytes(NVFP4_OP_QUANTIZE, R, C, 0) carries, from the amax pass to
+ * the encoding pass, which groups need the slower forms -- a workspace of only
+ * that smaller size is accepted, and the encoding pass then finds them again.
  */
 int nvfp4_quantize_rht(const void *x_bf16, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
                        const float *global_scale_in, nvfp4_tensor *out,

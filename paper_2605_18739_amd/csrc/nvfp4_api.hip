@@ -235,11 +235,14 @@ int nvfp4_quantize_rht(const void *x_bf16, int64_t R, int64_t C, int64_t ld, uin
     Timed t(s, NVFP4_OP_QUANTIZE_RHT);
     const uint16_t *xb = static_cast<const uint16_t *>(x_bf16);
     uint32_t *partial = static_cast<uint32_t *>(workspace);
+    // a workspace of the full size also carries the outcome of pass 1's exactness tests to pass 2
+    uint8_t *inexact = (!global_scale_in && workspace_bytes >= kPartialBytes + rht_inexact_bytes(R, C))
+                           ? static_cast<uint8_t *>(workspace) + kPartialBytes : nullptr;
     int n_partial = 0;
     if (!global_scale_in)
-        if (launch_amax_rht(xb, R, C, ld, sign_mask, partial, &n_partial, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
+        if (launch_amax_rht(xb, R, C, ld, sign_mask, partial, &n_partial, inexact, s) != hipSuccess) return NVFP4_ERR_LAUNCH;
     hipError_t e = launch_quantize_cols_rht(xb, R, C, ld, sign_mask, global_scale_in, partial, n_partial,
-                                            out->codes, out->scales, out->global_scale, s);
+                                            out->codes, out->scales, out->global_scale, inexact, s);
     return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
 }
 
@@ -510,9 +513,10 @@ size_t nvfp4_workspace_bytes(int op, int64_t a, int64_t b, int64_t c)
     case NVFP4_OP_KV_QUANT_4OVER6:
     case NVFP4_OP_KV_QUANT_K:
     case NVFP4_OP_QUANTIZE_2D:
-    case NVFP4_OP_QUANTIZE_RHT:
     case NVFP4_OP_QUANTIZE_A2A:
         return kPartialBytes;
+    case NVFP4_OP_QUANTIZE_RHT:       // a = R, b = C
+        return kPartialBytes + ((a > 0 && b > 0) ? rht_inexact_bytes(a, b) : 0);
     case NVFP4_OP_LORA_DOWN:          // a = M, b = K
         if (a <= 0 || b <= 0) return 0;
         return lora_down_workspace_bytes(a, b);

@@ -12,6 +12,7 @@ typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+typedef short short4v __attribute__((ext_vector_type(4)));
 typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 
@@ -524,13 +525,14 @@ __device__ __forceinline__ void rht_block16(uint32_t (&w)[8], uint32_t sign_mask
         w[i] = bf16_rne_signed_from_f64(0.25 * v[2 * i] + 0.0) | (bf16_rne_signed_from_f64(0.25 * v[2 * i + 1] + 0.0) << 16);
 }
 
-// The same transform in fp32, and the test that tells when it returns the same bits.  With all non-zero
+// The same transform in fp32 arithmetic, and the test that tells when it returns the same bits.  With all non-zero
 // magnitudes of the group within 12 binades of the largest, every value is a multiple of 2^(e_min - 7) and every
-// partial sum stays below 2^(e_max + 5): at most 24 significant bits, so the fp32 butterflies are exact and the one
-// rounding to bf16 (v_cvt_pk_bf16_f32, nearest even) is the rounding of the exact value, as in the fp64 form.
-// Groups near the ends of the exponent range (sums that could overflow, results that could be subnormal) and
-// all-zero groups are left to the fp64 form as well.  Gaussian data fails the test in about 1 % of the groups.
-__device__ __forceinline__ bool rht_fp32_is_exact(const uint32_t (&w)[8])
+// partial sum stays below 2^(e_max + 5): at most 24 significant bits, so fp32 sums of the sixteen terms are exact in
+// any order and the one rounding to bf16 (v_cvt_pk_bf16_f32, nearest even) is the rounding of the exact value, as in
+// the fp64 form.  Groups near the ends of the exponent range (sums that could overflow, results that could be
+// subnormal) fail the test; a group of zeros passes it.  Gaussian data fails it in about 1 % of the groups.
+// e_max and e_min are the largest and the smallest exponent field among the non-zero elements.
+__device__ __forceinline__ void rht_exponent_range(const uint32_t (&w)[8], int &emax, int &emin, bool &all_zero)
 {
     const ushort2v one = {1, 1};
     ushort2v mx = {0, 0}, mn = {0xFFFF, 0xFFFF};
@@ -541,28 +543,109 @@ __device__ __forceinline__ bool rht_fp32_is_exact(const uint32_t (&w)[8])
         mn = __builtin_elementwise_min(mn, a - one);                            // zeros wrap to 0xFFFF and never win
     }
     const uint32_t hmax = max((uint32_t)mx.x, (uint32_t)mx.y), hmin = min((uint32_t)mn.x, (uint32_t)mn.y) + 1u;
-    const int emax = (int)(hmax >> 8), emin = max((int)(hmin >> 8), 1);
-    return emax >= 40 && emax <= 240 && emax - emin <= 12;
+    emax = (int)(hmax >> 8);
+    emin = max((int)(hmin >> 8), 1);
+    all_zero = hmax == 0u;
 }
-__device__ __forceinline__ void rht_block16_f32(uint32_t (&w)[8], uint32_t sign_mask)
+__device__ __forceinline__ bool rht_fp32_is_exact(const uint32_t (&w)[8])
 {
-    float v[16];
+    int emax, emin;
+    bool all_zero;
+    rht_exponent_range(w, emax, emin, all_zero);
+    return all_zero | (emax >= 40 && emax <= 240 && emax - emin <= 12);
+}
+
+// The fp32 sums are taken on the matrix pipes.  v_mfma_f32_4x4x4_16B_bf16 multiplies, for each group of four
+// lanes, a 4x4 matrix A (lane i of the group supplies row i) by a 4x4 matrix B (lane j supplies column j, four bf16
+// in two registers) and adds a 4x4 fp32 matrix whose column j lane j holds: a lane's own four values go in, its own
+// four sums come out, nothing crosses lanes but the constant A.  H16 = H4 (x) H4, so with the group's sixteen values
+// x[4 g + k] and output index 4 a + b,   y[4 a + b] = sum_g sum_k ( (1/4) H4[a][g] H4[b][k] s[4 g + k] ) x[4 g + k]:
+// sixteen instructions (four accumulating chains of four), A = +-(1/4) H4 diag(s) for k-group g.  The products
+// (+-1/4 times a bf16 number) are exact and the sums are the ones the test above covers.  A sum of zero terms and a
+// sum that cancels come out as +0, as in the fp64 form.
+struct RhtRows {
+    uint32_t pos[4][2], neg[4][2];      // row (lane % 4) of (1/4) H4 diag(s_4g .. s_4g+3), and of its negative, as bf16 pairs
+};
+__device__ __forceinline__ RhtRows rht_rows(uint32_t sign_mask, uint32_t lane)
+{
+    RhtRows h;
+    const uint32_t b0 = lane & 1u, b1 = (lane >> 1) & 1u;                 // H4[b][k] = (-1)^popcount(b & k)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        v[2 * i] = __uint_as_float((w[i] << 16) ^ (((sign_mask >> (2 * i)) & 1u) << 31));
-        v[2 * i + 1] = __uint_as_float((w[i] & 0xFFFF0000u) ^ (((sign_mask >> (2 * i + 1)) & 1u) << 31));
+    for (int g = 0; g < 4; ++g) {
+        const uint32_t s = sign_mask >> (4 * g);
+        const uint32_t n0 = s & 1u, n1 = (b0 ^ (s >> 1)) & 1u, n2 = (b1 ^ (s >> 2)) & 1u, n3 = (b0 ^ b1 ^ (s >> 3)) & 1u;
+        h.pos[g][0] = 0x3E803E80u ^ (n0 << 15) ^ (n1 << 31);              // 0x3E80: 1/4 in bf16
+        h.pos[g][1] = 0x3E803E80u ^ (n2 << 15) ^ (n3 << 31);
+        h.neg[g][0] = h.pos[g][0] ^ 0x80008000u;
+        h.neg[g][1] = h.pos[g][1] ^ 0x80008000u;
+    }
+    return h;
+}
+// (no branch around this function may diverge within a wave: matrix instructions are issued for the whole wave)
+__device__ __forceinline__ void rht_block16_mfma(const uint32_t (&w)[8], const RhtRows &h, float (&y)[16])
+{
+    float4v acc[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) acc[a] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const uint2v bw = {w[2 * g], w[2 * g + 1]};
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const bool minus = ((a & g) == 1) | ((a & g) == 2);            // H4[a][g] = -1
+            const uint2v aw = {minus ? h.neg[g][0] : h.pos[g][0], minus ? h.neg[g][1] : h.pos[g][1]};
+            acc[a] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4v, aw), __builtin_bit_cast(short4v, bw),
+                                                            acc[a], 0, 0, 0);
+        }
     }
 #pragma unroll
-    for (int h = 1; h < 16; h <<= 1)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-            if ((i & h) == 0) {
-                const float a = v[i], b = v[i + h];
-                v[i] = a + b;
-                v[i + h] = a - b;
-            }
+        for (int i = 0; i < 4; ++i) y[4 * a + i] = acc[a][i];
+}
+__device__ __forceinline__ void pack16(const float (&y)[16], uint32_t (&w)[8])
+{
 #pragma unroll
-    for (int i = 0; i < 8; ++i) w[i] = pack_bf16x2(__builtin_fmaf(0.25f, v[2 * i], 0.0f), __builtin_fmaf(0.25f, v[2 * i + 1], 0.0f));   // (zero sums are +0)
+    for (int i = 0; i < 8; ++i) w[i] = pack_bf16x2(y[2 * i], y[2 * i + 1]);
+}
+
+// Groups that span up to 25 binades: the elements within 12 binades of the largest and the smaller ones are
+// transformed separately (each set passes the test above on its own), which gives the exact result as the sum of
+// two fp32 numbers L + S.  fl(L + S) lies within half an fp32 ulp of it, and nearest-even rounding to bf16 is
+// constant between consecutive bf16 midpoints, which are fp32 numbers: the two round alike unless fl(L + S) is
+// itself such a midpoint (low sixteen bits 0x8000).  Returns false, and leaves w as it was, for a group it cannot
+// settle this way (a wider span, the ends of the exponent range, a sum on a midpoint): those take the fp64 form.
+__device__ __forceinline__ bool rht_block16_mfma_split(uint32_t (&w)[8], const RhtRows &h)
+{
+    int emax, emin;
+    bool all_zero;
+    rht_exponent_range(w, emax, emin, all_zero);
+    const bool in_range = emax >= 40 && emax <= 240 && emax - emin <= 25;
+    const uint32_t t = ((uint32_t)max(emax - 12, 1) << 8) - 1u;           // keep halves whose (bits << 1) exceed this
+    const ushort2v thr = {(unsigned short)t, (unsigned short)t}, one = {1, 1}, ones = {0xFFFF, 0xFFFF};
+    uint32_t big[8], small[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const ushort2v a = __builtin_bit_cast(ushort2v, w[i]) << one;
+        const ushort2v keep = __builtin_elementwise_min(__builtin_elementwise_sub_sat(a, thr), one) * ones;   // 0xFFFF or 0
+        big[i] = w[i] & __builtin_bit_cast(uint32_t, keep);
+        small[i] = w[i] ^ big[i];
+    }
+    float L[16], S[16];
+    rht_block16_mfma(big, h, L);
+    rht_block16_mfma(small, h, S);
+    uint32_t r[8], hit = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float y0 = L[2 * i] + S[2 * i], y1 = L[2 * i + 1] + S[2 * i + 1];
+        const uint32_t low = __builtin_amdgcn_perm(__float_as_uint(y1), __float_as_uint(y0), 0x05040100u) ^ 0x80008000u;
+        hit = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(ushort2v, hit), __builtin_bit_cast(ushort2v, low)));
+        r[i] = pack_bf16x2(y0, y1);
+    }
+    const bool ok = in_range & ((hit & 0xFFFFu) != 0u) & ((hit >> 16) != 0u);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i] = ok ? r[i] : w[i];
+    return ok;
 }
 
 // global scale from the tensor's largest |bf16| pattern: RN_fp32(amax / 2688), 1 if zero

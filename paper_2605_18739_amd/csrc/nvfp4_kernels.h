@@ -39,11 +39,14 @@ hipError_t launch_quantize_rows_slabs(const uint16_t *x, int64_t T, int64_t H, i
 
 // Weight-gradient operands with the random Hadamard transform along the contraction axis (rows of x,
 // groups of 16) before the transposed quantizer; sign_mask bit j = 1: s_j = -1.
+// inexact (may be null): rht_inexact_bytes(R, C) bytes in which pass 1 leaves, per tile and lane, which groups the fp32
+// transform is not exact for, and pass 2 finds them
+size_t rht_inexact_bytes(int64_t R, int64_t C);
 hipError_t launch_amax_rht(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
-                           uint32_t *partial, int *n_partial, hipStream_t s);
+                           uint32_t *partial, int *n_partial, uint8_t *inexact, hipStream_t s);
 hipError_t launch_quantize_cols_rht(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
                                     const float *gs_in, const uint32_t *partial, int n_partial,
-                                    uint8_t *codes, uint8_t *scales, float *gs_out, hipStream_t s);
+                                    uint8_t *codes, uint8_t *scales, float *gs_out, const uint8_t *inexact, hipStream_t s);
 
 // 2-D block scaling (one scale per 16x16 tile); codes_t / scales_t: the transposed operand, or nullptr
 hipError_t launch_quantize_tiles(const uint16_t *x, int64_t R, int64_t C, int64_t ld, const float *gs_in,

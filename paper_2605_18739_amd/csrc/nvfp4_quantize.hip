@@ -270,49 +270,117 @@ __device__ __forceinline__ void column_of_dyn(const uint4v (&v)[16], int j, uint
     }
 }
 
+// ---- the groups of the Hadamard kernels that the fp32 transform is not exact for -----------------------
+// About one group in a hundred of Gaussian data.  They are not redone where the sweep over a tile finds them, which
+// would hold up the whole wave for the few lanes that have one and keep the loaded tile in registers next to the
+// slower forms' own: they go into a list of the workgroup (eight words and a word that says where the group belongs),
+// and after the sweep the list is worked off with one group per lane, so that a tile's twenty-odd such groups cost
+// one pass of one wave.  When the list is full the lane notes the column (a bit of `noted`) instead; noted columns
+// are read again from memory and listed in further rounds (data that spans many binades within most groups: slow,
+// and as exact).
+constexpr int kRhtQueue = 512;       // groups per round
+struct RhtList {
+    uint32_t q[kRhtQueue * 9];
+    uint32_t n;
+};
+__device__ __forceinline__ bool rht_list(RhtList &l, const uint32_t (&raw)[8], uint32_t place)
+{
+    const uint32_t slot = atomicAdd(&l.n, 1u);
+    if (slot >= (uint32_t)kRhtQueue) return false;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) l.q[slot * 9 + i] = raw[i];
+    l.q[slot * 9 + 8] = place;
+    return true;
+}
+// Every lane of the workgroup calls this after its sweep (l.n was zeroed, behind a barrier, before it).  take(w,
+// place) receives each listed group, transformed.  (r, c): the lane's first row and column, for the noted columns.
+template <class Take>
+__device__ __forceinline__ void rht_work_off(RhtList &l, uint32_t noted, uint32_t place, const RhtRows &h, uint32_t sign_mask,
+                                             const uint16_t *__restrict__ x, int64_t r, int64_t c, int64_t ld, Take take)
+{
+    for (;;) {
+        __syncthreads();
+        const uint32_t n = min(l.n, (uint32_t)kRhtQueue);
+        for (uint32_t e0 = threadIdx.x & ~63u; e0 < n; e0 += 256u) {      // (the same for the whole wave: matrix instructions inside)
+            const uint32_t e = e0 + (threadIdx.x & 63u);
+            const bool mine = e < n;
+            uint32_t w[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[i] = mine ? l.q[e * 9 + i] : 0u;
+            const uint32_t where = mine ? l.q[e * 9 + 8] : 0u;
+            const bool settled = rht_block16_mfma_split(w, h);
+            if (__builtin_expect(mine & !settled, 0)) rht_block16(w, sign_mask);
+            if (mine) take(w, where);
+        }
+        if (!__syncthreads_or(noted != 0u)) break;
+        if (threadIdx.x == 0) l.n = 0u;
+        __syncthreads();
+        if (noted != 0u) {                 // (only lanes inside the tensor note columns)
+            const int j = __builtin_ctz(noted);
+            uint32_t raw[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                raw[i] = (uint32_t)x[(r + 2 * i) * ld + c + j] | ((uint32_t)x[(r + 2 * i + 1) * ld + c + j] << 16);
+            if (rht_list(l, raw, place + (uint32_t)j)) noted &= noted - 1u;
+        }
+    }
+}
+
 // Pass 1 for a weight-gradient operand that is Hadamard-transformed along its rows before it is
 // quantized (Sec. 2.2): partial amax of the TRANSFORMED values, same tiles and thread layout as
 // the pass-2 kernel below, tiles dealt over at most kMaxPartials workgroups.
-__global__ __launch_bounds__(256) void amax_rht_kernel(const uint16_t *__restrict__ x, int64_t R, int64_t C,
+__global__ __launch_bounds__(256, 4) void amax_rht_kernel(const uint16_t *__restrict__ x, int64_t R, int64_t C,
                                                        int64_t ld, uint32_t sign_mask,
-                                                       uint32_t *__restrict__ partial)
+                                                       uint32_t *__restrict__ partial, uint8_t *__restrict__ inexact)
 {
     __shared__ uint32_t wave_max[4];
+    __shared__ RhtList list;
     const int cg = threadIdx.x & 31, rb = threadIdx.x >> 5;
     const int64_t tiles_x = (C + kTC - 1) / kTC, tiles_y = (R + kTR - 1) / kTR;
+    const RhtRows h = rht_rows(sign_mask, threadIdx.x);
     uint32_t acc = 0;
-    for (int64_t tile = blockIdx.x; tile < tiles_x * tiles_y; tile += gridDim.x) {
+    float accf = 0.0f;
+    for (int64_t tile = blockIdx.x; tile < tiles_x * tiles_y; tile += gridDim.x) {      // (as many turns for every lane)
         const int64_t r = (tile / tiles_x) * kTR + rb * 16, c = (tile % tiles_x) * kTC + cg * 8;
+        if (threadIdx.x == 0) list.n = 0u;
+        __syncthreads();
+        // lanes outside the tensor carry zeros through the same instructions (the matrix instructions below are
+        // issued for whole waves); zeros transform to zeros and change no maximum
+        uint4v v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = uint4v{0u, 0u, 0u, 0u};
         if (r < R && c < C) {
-            uint4v v[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) v[i] = *(const uint4v *)(x + (r + i) * ld + c);
-            // the fp32 transform for every group; the few groups it is not exact for are noted and redone in fp64
-            uint32_t redo = 0;
+        }
+        // the fp32 transform for every group; the few groups it is not exact for are listed and redone after the sweep
+        uint32_t inex = 0, noted = 0;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                uint32_t w[8];
-                column_of(v, j, w);
-                const bool exact = rht_fp32_is_exact(w);
-                rht_block16_f32(w, sign_mask);
-                uint32_t a = 0;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) a = pk_absmax_u16(a, w[i]);
-                acc = exact ? pk_absmax_u16(acc, a) : acc;
-                redo |= exact ? 0u : (1u << j);
-            }
-            while (redo != 0u) {
-                const int j = __builtin_ctz(redo);
-                redo &= redo - 1u;
-                uint32_t w[8];
-                column_of_dyn(v, j, w);
-                rht_block16(w, sign_mask);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
+        for (int j = 0; j < 8; ++j) {
+            uint32_t w[8];
+            column_of(v, j, w);
+            const bool exact = rht_fp32_is_exact(w);
+            float y[16];
+            rht_block16_mfma(w, h, y);
+            float m = absmax16_tree(y);            // (rounding to bf16 is monotone: the maximum is rounded once, at the end)
+            // one column at a time, its sixteen sums folded into one number before the next starts: eight columns
+            // in flight would not fit the registers
+            asm volatile("" : "+v"(m));
+            __builtin_amdgcn_sched_barrier(0);
+            accf = exact ? fmaxf(accf, m) : accf;
+            if (__builtin_expect(!exact, 0)) {
+                inex |= 1u << j;
+                if (!rht_list(list, w, 0u)) noted |= 1u << j;
             }
         }
+        // which of the lane's eight groups were inexact: pass 2 (same tiles, same lanes) need not test them again
+        if (inexact) inexact[tile * 256 + threadIdx.x] = (uint8_t)inex;
+        rht_work_off(list, noted, 0u, h, sign_mask, x, r, c, ld, [&](const uint32_t (&w)[8], uint32_t) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
+        });
     }
-    uint32_t m = wave_max_u32(pk_hmax_u16(acc));
+    uint32_t m = wave_max_u32(max(pk_hmax_u16(acc), pack_bf16x2(accf, 0.0f) & 0xFFFFu));
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
     __syncthreads();
     if (threadIdx.x == 0)
@@ -321,24 +389,30 @@ __global__ __launch_bounds__(256) void amax_rht_kernel(const uint16_t *__restric
 
 // RHT: every 16-row group of a column goes through the random Hadamard transform first.
 template <bool RHT = false>
-__global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__restrict__ x, int64_t R,
+__global__ __launch_bounds__(256, 3) void quantize_cols_kernel(const uint16_t *__restrict__ x, int64_t R,
                                                             int64_t C, int64_t ld,
                                                             const float *__restrict__ gs_in,
                                                             const uint32_t *__restrict__ partial,
                                                             int n_partial, uint8_t *__restrict__ codes,
                                                             uint8_t *__restrict__ scales,
                                                             float *__restrict__ gs_out,
-                                                            uint32_t sign_mask = 0)
+                                                            uint32_t sign_mask = 0,
+                                                            const uint8_t *__restrict__ inexact = nullptr)
 {
     __shared__ uint32_t lds4[4];
     __shared__ uint2v lds_codes[kTC][kTR / 16 + 1];     // [column][row block], padded
     __shared__ uint8_t lds_scales[kTC][kTR / 16];
+    __shared__ uint32_t list_words[RHT ? sizeof(RhtList) / 4 : 1];       // RHT: the groups left for after the sweep
     const int cg = threadIdx.x & 31, rb = threadIdx.x >> 5;
     const int64_t r0 = (int64_t)blockIdx.y * kTR, c0 = (int64_t)blockIdx.x * kTC;
     const int64_t r = r0 + rb * 16, c = c0 + cg * 8;
     const bool live = (r < R) && (c < C);      // R % 16 == 0 and C % 8 == 0: whole blocks only
     // the loads do not depend on the tensor scale: they are in flight while the partial maxima are reduced
     uint4v v[16];
+    if constexpr (RHT) {                       // (lanes outside the tensor carry zeros through the transform)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = uint4v{0u, 0u, 0u, 0u};
+    }
     if (live) {
 #pragma unroll
         for (int i = 0; i < 16; ++i)
@@ -347,40 +421,59 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(const uint16_t *__re
     const float sg = resolve_global_scale(gs_in, partial, n_partial, gs_out, lds4);
     const float shift = range_shift(sg), sgq = sg * shift;      // (1 and s_g unless the tensor scale is out of the fp32-safe range)
     const float inv_6sg = 1.0f / (6.0f * sgq);
-    if (live) {
-        auto encode_column = [&](uint32_t (&w)[8], int j) {     // transformed group -> codes and scale of column c + j
-            if (__builtin_expect(shift != 1.0f, 0)) rescale_block16(w, shift);
-            uint32_t acc = 0;
+    auto group_max = [](const uint32_t (&w)[8]) {
+        uint32_t acc = 0;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
-            float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
-            uint32_t sbyte = block_scale_exact(bmax, sgq, inv_6sg);
-            uint32_t k0, k1;
-            encode_block16(w, e4m3_to_f32(sbyte), sgq, k0, k1);
-            uint2v cc = {k0, k1};
-            lds_codes[cg * 8 + j][rb] = cc;
-            lds_scales[cg * 8 + j][rb] = (uint8_t)sbyte;
-        };
-        uint32_t redo = 0;                 // RHT: groups whose fp32 transform is not exact, redone in fp64 below
+        for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
+        return __uint_as_float(pk_hmax_u16(acc) << 16);
+    };
+    // (transformed) group and its largest magnitude -> codes and scale of column c0 + col
+    auto encode_group = [&](uint32_t (&w)[8], float bmax, int col, int rbx) {
+        if (__builtin_expect(shift != 1.0f, 0)) {
+            rescale_block16(w, shift);
+            bmax = group_max(w);
+        }
+        uint32_t sbyte = block_scale_exact(bmax, sgq, inv_6sg);
+        uint32_t k0, k1;
+        encode_block16(w, e4m3_to_f32(sbyte), sgq, k0, k1);
+        uint2v cc = {k0, k1};
+        lds_codes[col][rbx] = cc;
+        lds_scales[col][rbx] = (uint8_t)sbyte;
+    };
+    if constexpr (RHT) {
+        // Every lane of the wave runs the transform (matrix instructions are issued for whole waves; lanes outside
+        // the tensor encode zeros into staging rows that are not stored).
+        RhtList &list = *reinterpret_cast<RhtList *>(list_words);
+        const RhtRows h = rht_rows(sign_mask, threadIdx.x);
+        if (threadIdx.x == 0) list.n = 0u;
+        __syncthreads();
+        // (pass 1, when it ran and had room for them, left the outcome of the exactness test of this lane's groups)
+        const uint32_t known = inexact ? inexact[((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x] : 0u;
+        const uint32_t place = (uint32_t)(cg * 8) | ((uint32_t)rb << 16);
+        uint32_t noted = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {      // column c + j: element j of every loaded vector
+            uint32_t raw[8], w[8];
+            column_of(v, j, raw);
+            const bool exact = inexact ? ((known >> j) & 1u) == 0u : rht_fp32_is_exact(raw);
+            float y[16];
+            rht_block16_mfma(raw, h, y);
+            pack16(y, w);
+            // (rounding to bf16 is monotone: the largest of the rounded values is the rounded largest value.  A group
+            //  that is listed is encoded here all the same, and again, into the same place, after the sweep.)
+            encode_group(w, __uint_as_float(pack_bf16x2(absmax16_tree(y), 0.0f) << 16), cg * 8 + j, rb);
+            if (__builtin_expect(!exact, 0))
+                if (!rht_list(list, raw, place + (uint32_t)j)) noted |= 1u << j;
+        }
+        rht_work_off(list, noted, place, h, sign_mask, x, r, c, ld, [&](uint32_t (&w)[8], uint32_t where) {
+            encode_group(w, group_max(w), (int)(where & 0xFFFFu), (int)(where >> 16));
+        });
+    } else if (live) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {      // column c + j: element j of every loaded vector
             uint32_t w[8];
             column_of(v, j, w);
-            if constexpr (RHT) {
-                redo |= rht_fp32_is_exact(w) ? 0u : (1u << j);
-                rht_block16_f32(w, sign_mask);
-            }
-            encode_column(w, j);
-        }
-        if constexpr (RHT) {
-            while (redo != 0u) {
-                const int j = __builtin_ctz(redo);
-                redo &= redo - 1u;
-                uint32_t w[8];
-                column_of_dyn(v, j, w);
-                rht_block16(w, sign_mask);
-                encode_column(w, j);
-            }
+            encode_group(w, group_max(w), cg * 8 + j, rb);
         }
     }
     __syncthreads();
@@ -694,23 +787,25 @@ hipError_t launch_quantize_cols(const uint16_t *x, int64_t R, int64_t C, int64_t
     return hipGetLastError();
 }
 
+size_t rht_inexact_bytes(int64_t R, int64_t C) { return (size_t)(((C + kTC - 1) / kTC) * ((R + kTR - 1) / kTR)) * 256; }
+
 hipError_t launch_amax_rht(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
-                           uint32_t *partial, int *n_partial, hipStream_t s)
+                           uint32_t *partial, int *n_partial, uint8_t *inexact, hipStream_t s)
 {
     const int64_t tiles = ((C + kTC - 1) / kTC) * ((R + kTR - 1) / kTR);
     const int grid = (int)(tiles < kMaxPartials ? tiles : kMaxPartials);
     *n_partial = grid;
-    amax_rht_kernel<<<grid, 256, 0, s>>>(x, R, C, ld, sign_mask, partial);
+    amax_rht_kernel<<<grid, 256, 0, s>>>(x, R, C, ld, sign_mask, partial, inexact);
     return hipGetLastError();
 }
 
 hipError_t launch_quantize_cols_rht(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint32_t sign_mask,
                                     const float *gs_in, const uint32_t *partial, int n_partial,
-                                    uint8_t *codes, uint8_t *scales, float *gs_out, hipStream_t s)
+                                    uint8_t *codes, uint8_t *scales, float *gs_out, const uint8_t *inexact, hipStream_t s)
 {
     dim3 grid((unsigned)((C + kTC - 1) / kTC), (unsigned)((R + kTR - 1) / kTR));
     quantize_cols_kernel<true><<<grid, 256, 0, s>>>(x, R, C, ld, gs_in, partial, n_partial, codes, scales,
-                                                    gs_out, sign_mask);
+                                                    gs_out, sign_mask, inexact);
     return hipGetLastError();
 }
 

@@ -598,6 +598,10 @@ def test_quantize_rht(oracle, R, C, mask):
     want = oracle.quantize(oracle.rht_rows(xb, mask), block_axis=1)
     got = nv.nvfp4_quantize_rht(dev_bf16(xb), mask)
     assert_q_equal(got, want, "rht")
+    # a workspace that holds the partial maxima only: the encoding pass tests every group again instead of being told
+    small = torch.empty(nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE, R, C), dtype=torch.uint8, device="cuda")
+    assert small.numel() < nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE_RHT, R, C)
+    assert_q_equal(nv.nvfp4_quantize_rht(dev_bf16(xb), mask, workspace=small), want, "rht, small workspace")
     gs = torch.tensor([0.0125], dtype=torch.float32, device="cuda")
     got = nv.nvfp4_quantize_rht(dev_bf16(xb), mask, global_scale_in=gs)
     assert_q_equal(got, oracle.quantize(oracle.rht_rows(xb, mask), block_axis=1, global_scale_in=0.0125), "rht, given scale")
@@ -605,11 +609,12 @@ def test_quantize_rht(oracle, R, C, mask):
 
 def test_quantize_rht_groups_of_every_exponent_spread(oracle):
     """The transform runs in fp32 where that is exact (a group's non-zero magnitudes within 12 binades, away from
-    the ends of the exponent range) and in fp64 elsewhere.  Groups on both sides of every condition: spreads of
+    the ends of the exponent range), as two fp32 halves up to 25 binades, and in fp64 elsewhere; the groups that need
+    the slower forms are listed per workgroup and worked off in rounds.  Groups on both sides of every condition: spreads of
     0..40 binades, all-zero groups, groups of zeros and one value, signed zeros, magnitudes near 2^-120 and 2^120
     (alone: the tensor scale is shared), exact cancellations (equal values with alternating signs)."""
     g = np.random.default_rng(77)
-    R, C = 256, 96
+    R, C = 256, 272                    # a full tile of columns and a ragged one; most groups of a tile need the slower forms
     x = g.standard_normal((R, C)).astype(np.float64)
     spread = g.integers(0, 41, size=(R // 16, 1, C))                    # per group of 16 rows and column
     expo = -(g.random((R // 16, 16, C)) * (spread + 1)).astype(np.int64)
@@ -626,6 +631,8 @@ def test_quantize_rht_groups_of_every_exponent_spread(oracle):
             say(f"[rht] spreads, {tag} magnitudes, mask {mask:#06x}")
             want = oracle.quantize(oracle.rht_rows(xb, mask), block_axis=1)
             assert_q_equal(nv.nvfp4_quantize_rht(dev_bf16(xb), mask), want, f"rht spreads {tag} {mask:#x}")
+            small = torch.empty(nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE, R, C), dtype=torch.uint8, device="cuda")
+            assert_q_equal(nv.nvfp4_quantize_rht(dev_bf16(xb), mask, workspace=small), want, f"rht spreads {tag} {mask:#x}, small workspace")
 
 
 def test_wgrad_with_rht(oracle):

@@ -70,8 +70,8 @@ def _fp32_test_passes(bits):
 
 
 def test_fp32_hadamard_of_bf16_groups_is_exact_when_the_exponent_test_passes():
-    """The random Hadamard transform (Sec. 2.2) runs its butterflies in fp32 for groups that pass the exponent
-    test and in fp64 otherwise.  For groups that pass, the fp32 sums carry no rounding at all (equal to the fp64
+    """The random Hadamard transform (Sec. 2.2) takes its sums in fp32 for groups that pass the exponent
+    test and in fp64 otherwise (here: butterfly order; the next test: the order of the matrix pipes).  For groups that pass, the fp32 sums carry no rounding at all (equal to the fp64
     sums, which are exact there), so the one rounding to bf16 that follows is that of the exact value; the test
     is not vacuous (groups one binade wider do lose bits in fp32), and it lets most Gaussian groups through."""
     g = np.random.default_rng(12)
@@ -94,6 +94,69 @@ def test_fp32_hadamard_of_bf16_groups_is_exact_when_the_exponent_test_passes():
     gauss = g.standard_normal((50_000, 16)).astype(np.float32)
     gb = _rne_f32_to_bf16(gauss.ravel()).reshape(-1, 16)
     assert _fp32_test_passes(gb).mean() > 0.97
+
+
+def _h16_signs():
+    i = np.arange(16)
+    return (1 - 2 * (np.array([[bin(a & b).count("1") & 1 for b in i] for a in i]))).astype(np.float64)
+
+
+def test_fp32_hadamard_sums_are_exact_in_the_order_the_matrix_pipes_take_them():
+    """The kernels take the sixteen-term sums of the transform on the matrix pipes: four chains per group, each adding
+    four products at a time onto an fp32 accumulator (k-groups 0..3, 4..7, ...).  For groups that pass the exponent
+    test every partial sum of +-x/4 terms, in ANY order and grouping, has at most 24 significant bits: checked here for
+    that order with every partial sum rounded to fp32 (a stricter model than hardware that rounds once per four
+    products), against the exact sums."""
+    g = np.random.default_rng(21)
+    n = 100_000
+    mant = g.integers(0, 128, size=(n, 16), dtype=np.uint32)
+    sign = g.integers(0, 2, size=(n, 16), dtype=np.uint32)
+    top = g.integers(40, 241, size=(n, 1), dtype=np.uint32)
+    expo = (top - g.integers(0, 13, size=(n, 16)).astype(np.uint32)).astype(np.uint32)
+    bits = (sign << 15) | (expo << 7) | mant
+    bits[g.random((n, 16)) < 0.05] = 0
+    ok = _fp32_test_passes(bits)
+    assert ok.mean() > 0.9
+    x = _bf16_to_f32(bits[ok].ravel()).reshape(-1, 16).astype(np.float64)
+    n = x.shape[0]
+    H = _h16_signs()
+    exact = 0.25 * (x @ H.T)                                      # fp64: exact here
+    acc = np.zeros((n, 16), dtype=np.float32)
+    for k in range(16):                                           # one product at a time, every partial sum rounded to fp32
+        acc = (acc.astype(np.float64) + 0.25 * H[:, k][None, :] * x[:, k][:, None]).astype(np.float32)
+    assert (acc.astype(np.float64) == exact).all()
+
+
+def test_hadamard_of_a_wide_group_as_two_fp32_halves():
+    """Groups that span 13..25 binades are transformed as two sets -- the elements within 12 binades of the largest,
+    and the rest -- whose fp32 transforms L and S are exact, so that the exact result is L + S.  The kernels round
+    fl32(L + S) to bf16 and fall back to fp64 only when fl32(L + S) has the low sixteen bits 0x8000 (a bf16 midpoint).
+    Checked against the exact sum rounded once: wherever the low bits differ from 0x8000 the two roundings agree, and
+    the rule is not vacuous (without it some results would differ)."""
+    g = np.random.default_rng(22)
+    n = 200_000
+    mant = g.integers(0, 128, size=(n, 16), dtype=np.uint32)
+    sign = g.integers(0, 2, size=(n, 16), dtype=np.uint32)
+    top = g.integers(66, 241, size=(n, 1), dtype=np.uint32)
+    # a few large elements, the rest 13..25 binades below: cancellation among the large ones leaves sums the small ones decide
+    drop = np.where(g.random((n, 16)) < 0.3, g.integers(0, 2, size=(n, 16)), g.integers(13, 26, size=(n, 16)))
+    expo = (top - drop.astype(np.uint32)).astype(np.uint32)
+    mant[g.random((n, 16)) < 0.5] = 0                             # many powers of two: exact cancellations, sums on midpoints
+    bits = (sign << 15) | (expo << 7) | mant
+    x = _bf16_to_f32(bits.ravel()).reshape(n, 16).astype(np.float64)
+    e = (bits >> 7) & 0xFF
+    big = e >= (e.max(axis=1, keepdims=True) - 12)
+    H = _h16_signs()
+    L = (0.25 * ((x * big) @ H.T)).astype(np.float32)
+    S = (0.25 * ((x * ~big) @ H.T)).astype(np.float32)
+    assert (L.astype(np.float64) == 0.25 * ((x * big) @ H.T)).all() and (S.astype(np.float64) == 0.25 * ((x * ~big) @ H.T)).all()
+    exact = L.astype(np.float64) + S.astype(np.float64)           # at most 25 + 8 + 4 bits: exact in fp64
+    y = (L + S)                                                   # fp32, rounded to nearest
+    want = _rne_f64_to_bf16(exact.ravel())
+    got = _rne_f32_to_bf16(y.ravel())
+    midpoint = (y.ravel().view(np.uint32) & 0xFFFF) == 0x8000
+    assert (got[~midpoint] == want[~midpoint]).all()
+    assert midpoint.any() and (got[midpoint] != want[midpoint]).any(), "the midpoint rule guards nothing in this sample"
 
 
 def test_near_tie_difference_is_an_exact_fp32_number():
