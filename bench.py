@@ -14,7 +14,8 @@ The other rows of the path (KV quantize / dequantize, transposed quantize, dgrad
 the training shape, the later variants) are measured after the timed region and reported under
 "rows": median and mean of per-call HIP-event durations recorded by the library on the stream it
 launches on, with inputs and outputs rotating over enough buffer copies to exceed the 256 MB
-Infinity Cache, each next to the seconds the CPU oracle takes for the same operation.  "ceilings"
+Infinity Cache, each next to the seconds the CPU oracle takes for the same operation; "ms_back_to_back" is
+the mean over the same calls issued back to back between one pair of events (no event pair per call).  "ceilings"
 holds what the same GPU sustains on plain streaming kernels and on back-to-back matrix instructions.
 """
 import argparse
@@ -223,8 +224,17 @@ class Ctx:
         for i in range(iters):
             fn(warm + i)
         torch.cuda.synchronize()
-        samples = nv.nvfp4_timing_read_all(op_id)
+        samples = Samples(nv.nvfp4_timing_read_all(op_id))
         nv.nvfp4_set_timing(False)
+        # the same calls once more, issued back to back between ONE pair of events: what a call costs inside a
+        # stream of work, without the event pair of its own around it (a few microseconds on the short kernels)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            fn(warm + i)
+        e1.record()
+        torch.cuda.synchronize()
+        samples.stream_ms = e0.elapsed_time(e1) / iters
         return samples
 
     def oracle_seconds(self, fn):
@@ -236,6 +246,11 @@ class Ctx:
         return round(time.perf_counter() - t0, 3)
 
 
+class Samples(list):
+    """Per-call durations (ms) of one entry point, plus .stream_ms: the mean over the same calls issued back to back."""
+    stream_ms = None
+
+
 def copies_for(nbytes):
     """How many buffer copies a row rotates over so that together they exceed the Infinity Cache."""
     return max(2, -(-int(CACHE_BYTES * 1.25) // int(nbytes)))
@@ -245,6 +260,10 @@ def bw_row(samples, nbytes, oracle_s=None, copies=None, **extra):
     ms = statistics.median(samples)
     row = {"ms": round(ms, 4), "ms_mean": round(sum(samples) / len(samples), 4), "GBs": round(nbytes / ms / 1e6, 1),
            "frac_hbm": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4), "calls": len(samples)}
+    sm = getattr(samples, "stream_ms", None)
+    if sm:
+        row["ms_back_to_back"] = round(sm, 4)
+        row["frac_hbm_back_to_back"] = round(nbytes / sm / 1e6 / PEAK_HBM_GBS, 4)
     if copies is not None:
         row["buffer_copies"] = copies
     if oracle_s is not None:
@@ -257,6 +276,10 @@ def gemm_row(samples, flops, oracle=None):
     ms = statistics.median(samples)
     row = {"ms": round(ms, 4), "ms_mean": round(sum(samples) / len(samples), 4), "tflops": round(flops / ms / 1e9, 1),
            "frac_mfma": round(flops / ms / 1e9 / PEAK_MFMA_F16_TFLOPS, 4), "calls": len(samples)}
+    sm = getattr(samples, "stream_ms", None)
+    if sm:
+        row["ms_back_to_back"] = round(sm, 4)
+        row["frac_mfma_back_to_back"] = round(flops / sm / 1e9 / PEAK_MFMA_F16_TFLOPS, 4)
     if oracle is not None:
         row.update(oracle)
     return row
