@@ -20,7 +20,10 @@ constexpr int kQuantUnroll = 2, kDequantUnroll = 4, kQuantMaxGrid = 16384, kDequ
 // 1024 threads per workgroup: one workgroup per compute unit keeps sixteen waves of loads in
 // flight and leaves at most 256 partial maxima for every pass-2 workgroup to reduce again.
 constexpr int kAmaxThreads = 1024, kAmaxGrid = 256;
-template <bool CONTIG>
+// STREAM: the tensor is larger than the 256 MB Infinity Cache, so nothing pass 2 reads would still be there:
+// the loads bypass the caches (on the 505 MB gradient the transposed quantizer gains 5 %); smaller tensors are read
+// with ordinary loads, and pass 2 finds them in the cache.
+template <bool CONTIG, bool STREAM>
 __global__ __launch_bounds__(kAmaxThreads) void amax_partial_kernel(const uint16_t *__restrict__ x, int64_t R,
                                                                     int64_t C, int64_t ld,
                                                                     uint32_t *__restrict__ partial)
@@ -43,16 +46,19 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_partial_kernel(const uint16
         acc = pk_absmax_u16(acc, v.z);
         acc = pk_absmax_u16(acc, v.w);
     };
+    auto fetch = [&](int64_t k) {
+        const uint4v *p = (const uint4v *)(x + offset_of(k));
+        return STREAM ? __builtin_nontemporal_load(p) : *p;
+    };
     int64_t i = begin + threadIdx.x;
-    for (; i + 3 * kAmaxThreads < end; i += 4 * kAmaxThreads) {       // ordinary loads: pass 2 re-reads x, let the caches keep it
-        const uint4v a = *(const uint4v *)(x + offset_of(i)), b = *(const uint4v *)(x + offset_of(i + kAmaxThreads));
-        const uint4v c = *(const uint4v *)(x + offset_of(i + 2 * kAmaxThreads)), d = *(const uint4v *)(x + offset_of(i + 3 * kAmaxThreads));
+    for (; i + 3 * kAmaxThreads < end; i += 4 * kAmaxThreads) {
+        const uint4v a = fetch(i), b = fetch(i + kAmaxThreads), c = fetch(i + 2 * kAmaxThreads), d = fetch(i + 3 * kAmaxThreads);
         take(a);
         take(b);
         take(c);
         take(d);
     }
-    for (; i < end; i += kAmaxThreads) take(*(const uint4v *)(x + offset_of(i)));
+    for (; i < end; i += kAmaxThreads) take(fetch(i));
     uint32_t m = wave_max_u32(pk_hmax_u16(acc));
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
     __syncthreads();
@@ -329,6 +335,7 @@ __device__ __forceinline__ void rht_work_off(RhtList &l, uint32_t noted, uint32_
 // Pass 1 for a weight-gradient operand that is Hadamard-transformed along its rows before it is
 // quantized (Sec. 2.2): partial amax of the TRANSFORMED values, same tiles and thread layout as
 // the pass-2 kernel below, tiles dealt over at most kMaxPartials workgroups.
+template <bool STREAM>      // as in amax_partial_kernel: tensors beyond the Infinity Cache are read past the caches (-8 % on the 505 MB gradient)
 __global__ __launch_bounds__(256, 4) void amax_rht_kernel(const uint16_t *__restrict__ x, int64_t R, int64_t C,
                                                        int64_t ld, uint32_t sign_mask,
                                                        uint32_t *__restrict__ partial, uint8_t *__restrict__ inexact)
@@ -351,7 +358,10 @@ __global__ __launch_bounds__(256, 4) void amax_rht_kernel(const uint16_t *__rest
         for (int i = 0; i < 16; ++i) v[i] = uint4v{0u, 0u, 0u, 0u};
         if (r < R && c < C) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = *(const uint4v *)(x + (r + i) * ld + c);
+            for (int i = 0; i < 16; ++i) {
+                const uint4v *p = (const uint4v *)(x + (r + i) * ld + c);
+                v[i] = STREAM ? __builtin_nontemporal_load(p) : *p;
+            }
         }
         // the fp32 transform for every group; the few groups it is not exact for are listed and redone after the sweep
         uint32_t inex = 0, noted = 0;
@@ -746,8 +756,14 @@ hipError_t launch_amax(const uint16_t *x, int64_t R, int64_t C, int64_t ld, uint
     const int64_t want = (R * (C >> 3) + kAmaxThreads - 1) / kAmaxThreads;
     const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(want, kAmaxGrid));
     *n_partial = grid;
-    if (ld == C) amax_partial_kernel<true><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
-    else amax_partial_kernel<false><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
+    const bool stream = (uint64_t)R * (uint64_t)C * 2u > (256ull << 20);
+    if (ld == C) {
+        if (stream) amax_partial_kernel<true, true><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
+        else amax_partial_kernel<true, false><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
+    } else {
+        if (stream) amax_partial_kernel<false, true><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
+        else amax_partial_kernel<false, false><<<grid, kAmaxThreads, 0, s>>>(x, R, C, ld, partial);
+    }
     return hipGetLastError();
 }
 
@@ -795,7 +811,8 @@ hipError_t launch_amax_rht(const uint16_t *x, int64_t R, int64_t C, int64_t ld, 
     const int64_t tiles = ((C + kTC - 1) / kTC) * ((R + kTR - 1) / kTR);
     const int grid = (int)(tiles < kMaxPartials ? tiles : kMaxPartials);
     *n_partial = grid;
-    amax_rht_kernel<<<grid, 256, 0, s>>>(x, R, C, ld, sign_mask, partial, inexact);
+    if ((uint64_t)R * (uint64_t)C * 2u > (256ull << 20)) amax_rht_kernel<true><<<grid, 256, 0, s>>>(x, R, C, ld, sign_mask, partial, inexact);
+    else amax_rht_kernel<false><<<grid, 256, 0, s>>>(x, R, C, ld, sign_mask, partial, inexact);
     return hipGetLastError();
 }
 
