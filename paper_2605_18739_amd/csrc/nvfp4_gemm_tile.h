@@ -152,7 +152,11 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
                 const int idx = p * 64 + lane, r = idx / GPR, gi = idx % GPR;
                 float4v o = *(const float4v *)(slab + r * ROWB + ((gi ^ (swz_key(r) & KEYMASK)) << 4));
                 const int64_t m = wave_m0 + j * 32 + r, n = wave_n0 + gi * 4;
-                if (m < g.M && n < g.N) *(float4v *)((float *)ep.Y + m * ep.ldy + n) = o;
+                if (m < g.M && n < g.N) {
+                    float4v *dst = (float4v *)((float *)ep.Y + m * ep.ldy + n);
+                    if (ep.stream_out) __builtin_nontemporal_store(o, dst);
+                    else *dst = o;
+                }
             }
         } else {
             // bf16: slab row = WN * 2 bytes, granule = 8 bf16; lane halves trade their
@@ -195,7 +199,9 @@ __device__ __forceinline__ void gemm_epilogue(float16v (&acc)[TN][TM], const Gem
                             hmax = pk_absmax_u16(hmax, o.z);
                             hmax = pk_absmax_u16(hmax, o.w);
                         }
-                        *(uint4v *)((uint16_t *)ep.Y + m * ep.ldy + n) = o;
+                        uint4v *dst = (uint4v *)((uint16_t *)ep.Y + m * ep.ldy + n);
+                        if (ep.stream_out) __builtin_nontemporal_store(o, dst);
+                        else *dst = o;
                     }
                 }
             }

@@ -79,6 +79,7 @@ struct GemmEpilogue {
     int act;                  // 0 none, 1 gelu-tanh
     void *Y;                  // [M, N] fp32 or bf16, or nullptr
     int64_t ldy;
+    int stream_out;           // 1: Y is written with streaming stores (outputs too large for anything to find them cached)
     uint32_t *amax_partial;   // per-workgroup |bf16(H)| maxima, or nullptr
     const float *q_scale;     // global scale for the fused quantizer, or nullptr (no fused quantize)
     float *q_scale_out;       // receives the scale that was used
