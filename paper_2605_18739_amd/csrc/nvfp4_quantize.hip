@@ -679,6 +679,86 @@ struct GatherTable {
     int row_shift;                                 // log2(nb_row) when that is a power of two, else -1
 };
 
+// One unit of a chunk: 256 * U half blocks from half block h0 (this lane's first) on.  Every load of the unit is
+// issued before the first result is used (indices past the end of the chunk are clamped, their results dropped), so a
+// workgroup waits for memory once.
+template <bool SMOOTH>
+__device__ __forceinline__ void gather_unit(const uint4v *table, const uint8_t *__restrict__ codes,
+                                            const uint8_t *__restrict__ scales, const uint16_t *__restrict__ mean,
+                                            double sg, int64_t nhalf, int64_t h0, int nb_row, int row_shift,
+                                            uint16_t *__restrict__ dst)
+{
+    constexpr int U = 4;                                   // half blocks in flight per lane
+    uint32_t cws[U], sbs[U], mus[U];
+    int64_t hc[U], row[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) hc[u] = min(h0 + u * 256, nhalf - 1);
+    if constexpr (SMOOTH) {                                // row of the half block: its mean (a shift when d / 16 is a power of two)
+        if (row_shift >= 0) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) row[u] = hc[u] >> (row_shift + 1);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) row[u] = (hc[u] >> 1) / nb_row;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        cws[u] = __builtin_nontemporal_load((const uint32_t *)codes + hc[u]);
+        sbs[u] = scales[hc[u] >> 1] & 0x7Fu;
+        if constexpr (SMOOTH) mus[u] = mean[row[u]];
+    }
+    const float sgf = (float)sg;                           // (the chunk's tensor scale is an fp32 number)
+    const bool sg_mid = sgf >= 0x1p-60f && sgf <= 0x1p60f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t h = h0 + u * 256;
+        if (h >= nhalf) continue;
+        const uint32_t cw = cws[u];
+        uint32_t o[4];
+        if constexpr (!SMOOTH) {
+            dequant_half_lookup(cw, table[sbs[u]], o);
+        } else {
+            // RN_bf16(code s_b s_g + mean), the exact sum rounded once.  code s_b is exact in fp32 (2 + 4 bits), and
+            // the fused multiply-add rounds (code s_b) s_g + mean once, to fp32: the result lies within half an
+            // fp32 ulp of the exact sum, and rounding to bf16 is constant between consecutive bf16 midpoints, which
+            // are fp32 numbers -- so the two round alike unless the fp32 result is itself a midpoint (low sixteen
+            // bits 0x8000: one element in 65 536).  With the tensor scale and the mean in [2^-60, 2^60] (or a mean
+            // of zero) every non-zero sum is a multiple of 2^-93 below 2^73: nothing overflows or goes subnormal.
+            // The rest takes the sum in fp64.
+            typedef float float2v __attribute__((ext_vector_type(2)));
+            const float muf = __uint_as_float(mus[u] << 16), amu = fabsf(muf);
+            const float sbf = e4m3_to_f32(sbs[u]);
+            uint32_t hit = 0xFFFFFFFFu;
+#define NVFP4_GATHER_PAIR(I, SEL)                                                                 \
+    {                                                                                             \
+        const float2v q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cw, 1.0f, SEL);                \
+        const float y0 = __builtin_fmaf(q.x * sbf, sgf, muf), y1 = __builtin_fmaf(q.y * sbf, sgf, muf); \
+        const uint32_t low = __builtin_amdgcn_perm(__float_as_uint(y1), __float_as_uint(y0), 0x05040100u) ^ 0x80008000u; \
+        hit = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(ushort2v, hit), __builtin_bit_cast(ushort2v, low))); \
+        o[I] = pack_bf16x2(y0, y1);                                                               \
+    }
+            NVFP4_GATHER_PAIR(0, 0) NVFP4_GATHER_PAIR(1, 1) NVFP4_GATHER_PAIR(2, 2) NVFP4_GATHER_PAIR(3, 3)
+#undef NVFP4_GATHER_PAIR
+            const bool sure = sg_mid & ((hit & 0xFFFFu) != 0u) & ((hit >> 16) != 0u) &
+                              ((amu == 0.0f) | ((amu >= 0x1p-60f) & (amu <= 0x1p60f)));
+            if (__builtin_expect(!sure, 0)) {
+                const double mu = (double)muf;
+                const double den = (double)sbf * sg;                // exact
+#define NVFP4_GATHER_PAIR(I, SEL)                                                                 \
+    {                                                                                             \
+        const float2v q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cw, 1.0f, SEL);                \
+        o[I] = bf16_rne_signed_from_f64((double)q.x * den + mu) |                                 \
+               (bf16_rne_signed_from_f64((double)q.y * den + mu) << 16);                          \
+    }
+                NVFP4_GATHER_PAIR(0, 0) NVFP4_GATHER_PAIR(1, 1) NVFP4_GATHER_PAIR(2, 2) NVFP4_GATHER_PAIR(3, 3)
+#undef NVFP4_GATHER_PAIR
+            }
+        }
+        __builtin_nontemporal_store(uint4v{o[0], o[1], o[2], o[3]}, (uint4v *)(dst + (h << 3)));
+    }
+}
+
 __global__ __launch_bounds__(256) void dequant_gather_kernel(GatherTable t, uint16_t *__restrict__ out)
 {
     __shared__ uint4v table[128];
@@ -697,49 +777,16 @@ __global__ __launch_bounds__(256) void dequant_gather_kernel(GatherTable t, uint
     const int64_t nblk = t.blk_start[c + 1] - t.blk_start[c];
     const int64_t first = (int64_t)((int)blockIdx.x - t.wg_start[c]) * kGatherBlocksPerWg;
     uint16_t *dst = out + (t.blk_start[c] << 4);
+    const int64_t nhalf = nblk << 1;
     if (!mean) {
         build_dequant_table(table, sg);
         __syncthreads();
     }
-    constexpr int U = 4;                                   // half blocks in flight per lane
-    const int64_t nhalf = nblk << 1;
-    for (int it = 0; it < 2 * kGatherBlocksPerWg / (256 * U); ++it) {
-        uint32_t cws[U], sbs[U];
-        uint16_t mus[U];                                   // row means of smoothed chunks, fetched with the codes
-        const int64_t h0 = 2 * first + it * (256 * U) + threadIdx.x;
-        if (h0 >= nhalf) break;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t h = h0 + u * 256;
-            if (h < nhalf) {
-                cws[u] = __builtin_nontemporal_load((const uint32_t *)codes + h);
-                sbs[u] = scales[h >> 1] & 0x7Fu;
-                if (mean) mus[u] = mean[t.row_shift >= 0 ? (h >> (t.row_shift + 1)) : ((h >> 1) / t.nb_row)];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t h = h0 + u * 256;
-            if (h >= nhalf) continue;
-            const uint32_t cw = cws[u];
-            uint32_t o[4];
-            if (!mean) {
-                dequant_half_lookup(cw, table[sbs[u]], o);
-            } else {
-                const double mu = (double)__uint_as_float((uint32_t)mus[u] << 16);
-                const double den = (double)e4m3_to_f32(sbs[u]) * sg;                // exact
-                typedef float float2v __attribute__((ext_vector_type(2)));
-#define NVFP4_GATHER_PAIR(I, SEL)                                                                 \
-    {                                                                                             \
-        const float2v q = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(cw, 1.0f, SEL);                \
-        o[I] = bf16_rne_signed_from_f64((double)q.x * den + mu) |                                 \
-               (bf16_rne_signed_from_f64((double)q.y * den + mu) << 16);                          \
-    }
-                NVFP4_GATHER_PAIR(0, 0) NVFP4_GATHER_PAIR(1, 1) NVFP4_GATHER_PAIR(2, 2) NVFP4_GATHER_PAIR(3, 3)
-#undef NVFP4_GATHER_PAIR
-            }
-            __builtin_nontemporal_store(uint4v{o[0], o[1], o[2], o[3]}, (uint4v *)(dst + (h << 3)));
-        }
+    for (int it = 0; it < 2 * kGatherBlocksPerWg / (256 * 4); ++it) {
+        const int64_t h0 = 2 * first + it * (256 * 4) + threadIdx.x;
+        if (h0 - threadIdx.x >= nhalf) break;             // (the same for the whole workgroup)
+        if (mean) gather_unit<true>(table, codes, scales, mean, sg, nhalf, h0, t.nb_row, t.row_shift, dst);
+        else gather_unit<false>(table, codes, scales, mean, sg, nhalf, h0, t.nb_row, t.row_shift, dst);
     }
 }
 

@@ -799,13 +799,18 @@ def test_kv_dequant_gather_window(oracle):
     """A sink chunk plus a sliding window of chunks of different lengths, keys smoothed and values
     plain, reconstructed by one launch each: every byte equals the per-chunk oracle output."""
     H, d = 24, 128
-    lens = [880, 1, 37, 880, 300]
+    lens = [880, 1, 37, 880, 300, 19, 23]
     k_chunks, v_chunks, want_k, want_v = [], [], [], []
     for i, T in enumerate(lens):
         kb = wl.kv_tensor(T, H, d, 9, 2 * i).reshape(T * H, d)
         vb = wl.kv_tensor(T, H, d, 9, 2 * i + 1).reshape(T * H, d)
         if i == 2:
             kb = wl.to_bf16_bits(wl.bf16_bits_to_f32(kb) * 50.0)       # chunks differ in scale
+        if i == 5:                                                     # a chunk far below and one far above the range in which
+            kb = wl.to_bf16_bits(wl.bf16_bits_to_f32(kb) * np.float32(2.0 ** -100))   # the mean is added back in fp32
+        if i == 6:
+            kb = wl.to_bf16_bits(wl.bf16_bits_to_f32(kb) * np.float32(2.0 ** 90))
+            kb[5 * H:7 * H] = 0                                        # rows of zeros: mean zero, scale bytes zero
         m, q = _oracle_k_path(oracle, kb)
         want_k.append(oracle.dequant_bf16(q, m))
         want_v.append(oracle.dequant_bf16(oracle.quantize(vb)))
