@@ -479,11 +479,25 @@ __global__ __launch_bounds__(256, 3) void quantize_cols_kernel(const uint16_t *_
             encode_group(w, group_max(w), (int)(where & 0xFFFFu), (int)(where >> 16));
         });
     } else if (live) {
+        if (__builtin_expect(shift == 1.0f, 1)) {          // two columns side by side (see quantize_pair16)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {      // column c + j: element j of every loaded vector
-            uint32_t w[8];
-            column_of(v, j, w);
-            encode_group(w, group_max(w), cg * 8 + j, rb);
+            for (int j = 0; j < 8; j += 2) {               // columns c + j, c + j + 1: elements j, j + 1 of every loaded vector
+                uint32_t wa[8], wb[8], sa, a0, a1, sb, b0, b1;
+                column_of(v, j, wa);
+                column_of(v, j + 1, wb);
+                quantize_pair16(wa, wb, sg, inv_6sg, sa, a0, a1, sb, b0, b1);
+                lds_codes[cg * 8 + j][rb] = uint2v{a0, a1};
+                lds_scales[cg * 8 + j][rb] = (uint8_t)sa;
+                lds_codes[cg * 8 + j + 1][rb] = uint2v{b0, b1};
+                lds_scales[cg * 8 + j + 1][rb] = (uint8_t)sb;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                uint32_t w[8];
+                column_of(v, j, w);
+                encode_group(w, group_max(w), cg * 8 + j, rb);
+            }
         }
     }
     __syncthreads();
