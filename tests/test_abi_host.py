@@ -43,6 +43,10 @@ def test_status_strings():
 def test_workspace_sizes():
     assert nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE, 128, 256) == 4096
     assert nv.nvfp4_workspace_bytes(nv.OP_KV_QUANT, 10, 24, 128) == 4096
+    # the Hadamard quantizer: the partial maxima plus one byte per lane of every 128 x 256 tile (pass 1 -> pass 2)
+    assert nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE_RHT, 128, 256) == 4096 + 256
+    assert nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE_RHT, 17600, 14336) == 4096 + 138 * 56 * 256
+    assert nv.nvfp4_workspace_bytes(nv.OP_QUANTIZE_RHT, 144, 264) == 4096 + 2 * 2 * 256
     with_h = nv.nvfp4_workspace_bytes(nv.OP_GEMM_ACT_QUANT, 3520, 14336, 0)
     without_h = nv.nvfp4_workspace_bytes(nv.OP_GEMM_ACT_QUANT, 3520, 14336, 1)
     assert with_h - without_h == 3520 * 14336 * 2
