@@ -635,6 +635,29 @@ def test_quantize_rht_groups_of_every_exponent_spread(oracle):
             assert_q_equal(nv.nvfp4_quantize_rht(dev_bf16(xb), mask, workspace=small), want, f"rht spreads {tag} {mask:#x}, small workspace")
 
 
+def test_quantize_rht_random_sweep(oracle):
+    """Seeded sweep over shapes (ragged tile edges in both directions), sign masks and value distributions for the
+    Hadamard quantizer: Gaussian, a few huge rows, sparse with whole groups of zeros, grid values whose sums cancel
+    and land on bf16 ties, magnitudes that differ by many binades inside a group."""
+    g = np.random.default_rng(4242)
+    for case in range(16):
+        R, C = 16 * int(g.integers(1, 40)), 8 * int(g.integers(1, 90))
+        mask = int(g.integers(0, 1 << 16))
+        kind = case % 4
+        x = g.standard_normal((R, C))
+        if kind == 1:
+            x[g.choice(R, max(1, R // 50), replace=False)] *= 300.0
+        elif kind == 2:
+            x = np.where(g.random((R, C)) < 0.7, 0.0, x)
+            x[: 16 * (R // 32)] = 0.0
+        elif kind == 3:
+            x = g.integers(-6, 7, size=(R, C)) * 2.0 ** g.integers(-20, 4, size=(R, C))
+        xb = wl.to_bf16_bits(np.asarray(x, np.float32))
+        say(f"[rht] sweep {case}: {R}x{C} mask {mask:#06x} kind={kind}")
+        want = oracle.quantize(oracle.rht_rows(xb, mask), block_axis=1)
+        assert_q_equal(nv.nvfp4_quantize_rht(dev_bf16(xb), mask), want, f"rht sweep {case}")
+
+
 def test_wgrad_with_rht(oracle):
     """dW = dY^T X with both operands transformed by the same signs: the GEMM equals the oracle's on
     the oracle's transformed operands; both quantized products approximate the unquantized one (the
