@@ -382,6 +382,12 @@ def _rows_kv(ctx, res, ws):
     k2 = kb.reshape(T * H, d)
     s = ctx.time_op(nv.OP_KV_QUANT, lambda i: nv.nvfp4_kv_quant(kvs[i % nc], out=qs[i % nc], workspace=ws), it)
     res["kv_quant_18480x24x128"] = bw_row(s, B_PER_ELEM * n, ctx.oracle_seconds(lambda: ora.quantize(k2)), nc)
+    # values whose tensor scale the producing GEMM already supplied (nvfp4_gemm_scale_out on the V projection): the
+    # same bytes through the given-scale quantizer, one streaming pass and no maximum to wait for
+    gs = torch.tensor([float(np.float32(np.abs(wl.bf16_bits_to_f32(kb)).max()) / np.float32(2688.0))], dtype=torch.float32, device=dev)
+    s = ctx.time_op(nv.OP_QUANTIZE, lambda i: nv.nvfp4_quantize(kvs[i % nc].view(T * H, d), global_scale_in=gs, out=qs[i % nc], workspace=ws), it)
+    res["kv_quant_given_scale_18480x24x128"] = bw_row(
+        s, B_PER_ELEM * n, ctx.oracle_seconds(lambda: ora.quantize(k2, global_scale_in=float(gs.cpu()[0]))), nc)
     # the same cache with the Four-over-Six scale search (the variant the paper applies to the cache)
     s = ctx.time_op(nv.OP_KV_QUANT_4OVER6, lambda i: nv.nvfp4_kv_quant_4over6(kvs[i % nc], out=qs[i % nc], workspace=ws), it)
     res["kv_quant_4over6_18480x24x128"] = bw_row(s, B_PER_ELEM * n, ctx.oracle_seconds(lambda: ora.quantize(k2, four_over_six=True)), nc)
