@@ -212,6 +212,9 @@ __device__ __forceinline__ float block_error_f32(const uint32_t (&w)[8], uint32_
 // small code, not for speed.)
 __device__ __forceinline__ double block_error_f64(const uint32_t (&w)[8], uint32_t c0, uint32_t c1, float sb, float sg)
 {
+    // (under the default contraction mode the compiler fuses these into multiply-adds: one rounding where the
+    //  definition has two, and a different answer on blocks whose two errors are equal in exact arithmetic)
+#pragma clang fp contract(off)
     typedef float float2v __attribute__((ext_vector_type(2)));
     const double den = (double)sb * (double)sg;     // exact
     double err = 0.0;
@@ -224,8 +227,10 @@ __device__ __forceinline__ double block_error_f64(const uint32_t (&w)[8], uint32
         const double a = (double)__uint_as_float((ww >> ((j & 1u) << 4) << 16) & 0x7FFF0000u);
         const uint32_t idx = ((second ? c1 : c0) >> (4u * (j & 7u))) & 7u;
         const float2v m = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(idx, 1.0f, 0);       // the code's magnitude, exact
-        const double d = __dsub_rn(a, __dmul_rn((double)m.x, den));
-        err = __dadd_rn(err, __dmul_rn(d, d));
+        const double prod = (double)m.x * den;            // (plain operators: contraction is switched off for this function;
+        const double d = a - prod;                         //  the rounding intrinsics are inlined with the contraction mode
+        const double sq = d * d;                           //  of their own header and would be fused all the same)
+        err = err + sq;
     }
     return err;
 }
@@ -397,14 +402,18 @@ __device__ __forceinline__ void quantize_block16_4over6_inline(const uint32_t (&
     block_scale_inline(bmax, sg, inv_6sg, 6.0, s6, sb6, inv6);
     block_scale_inline(bmax, sg, inv_4sg, 4.0, s4, sb4, inv4);
     const float il6 = inv6 * kBracketLo, ih6 = inv6 * kBracketHi, il4 = inv4 * kBracketLo, ih4 = inv4 * kBracketHi;
-    uint32_t l6[2] = {0, 0}, h6[2] = {0, 0}, l4[2] = {0, 0}, h4[2] = {0, 0};
-#define NVFP4_STEP(K, SEL) NVFP4_CVT4(K, SEL, l6, f, il6, h6, f, ih6, l4, f, il4, h4, f, ih4)
+    // The candidates are compared on the codes of the LOWER bracket end alone; the upper end is converted for the
+    // winner only, whose near-ties are then settled.  A nibble on which the two ends would disagree lies within
+    // 2^-19 of a midpoint T between magnitudes T -+ h, so its squared error changes by the factor
+    // 1 +- 4 (T / h) 2^-19 at most when the nibble flips, and T / h <= 7: the settled codes' error lies within
+    // 2^-14 (e + r) of the error e that is computed here, which the uncertainty r below takes in.
+    uint32_t l6[2] = {0, 0}, l4[2] = {0, 0};
+#define NVFP4_STEP(K, SEL)                                                                                              \
+    l6[K >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(l6[K >> 2], f[2 * K] * il6, f[2 * K + 1] * il6, 1.0f, SEL);   \
+    l4[K >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(l4[K >> 2], f[2 * K] * il4, f[2 * K + 1] * il4, 1.0f, SEL);
     NVFP4_STEP(0, 0) NVFP4_STEP(1, 1) NVFP4_STEP(2, 2) NVFP4_STEP(3, 3)
     NVFP4_STEP(4, 0) NVFP4_STEP(5, 1) NVFP4_STEP(6, 2) NVFP4_STEP(7, 3)
 #undef NVFP4_STEP
-    // The errors are taken with the codes of the lower bracket end; only the winner is settled afterwards.  A nibble
-    // on which the two ends disagree lies within 2^-19 of a midpoint T between magnitudes T -+ h, so its squared
-    // error changes by the factor 1 +- 4 (T / h) 2^-19 at most when the nibble flips, and T / h <= 7: below 2^-14.
     const float den6 = sb6 * sg, den4 = sb4 * sg;
     float e6a = 0.0f, e6b = 0.0f, e4a = 0.0f, e4b = 0.0f;
 #define NVFP4_STEP(K, SEL)                                                                                        \
@@ -425,24 +434,33 @@ __device__ __forceinline__ void quantize_block16_4over6_inline(const uint32_t (&
     const float u6 = 0x1p-22f * (bmax + 6.0f * den6), u4 = 0x1p-22f * (bmax + 6.0f * den4);
     float r6 = u6 * (8.02f * __builtin_amdgcn_sqrtf(e6) + 16.0f * u6) + 0x1p-19f * e6;   // (eight fused steps and one
     float r4 = u4 * (8.02f * __builtin_amdgcn_sqrtf(e4) + 16.0f * u4) + 0x1p-19f * e4;   //  addition: below 2^-19 as well)
-    const bool open6 = ((l6[0] ^ h6[0]) | (l6[1] ^ h6[1])) != 0u, open4 = ((l4[0] ^ h4[0]) | (l4[1] ^ h4[1])) != 0u;
-    r6 = open6 ? __builtin_fmaf(0x1p-14f, e6, 1.0001f * r6) : r6;      // the settled codes' error lies within
-    r4 = open4 ? __builtin_fmaf(0x1p-14f, e4, 1.0001f * r4) : r4;      // 2^-14 (e + r) of e as well
+    r6 = __builtin_fmaf(0x1p-14f, e6, 1.0001f * r6);
+    r4 = __builtin_fmaf(0x1p-14f, e4, 1.0001f * r4);
     const bool tiny = fminf(e4, e6) < 0x1p-100f;
     const bool same = s4 == s6;                    // (saturated scales, zero blocks: same codes, same error, 6 is kept)
     bool pick4 = e4 + r4 < e6 - r6;
-    if (__builtin_expect(!same & (tiny | !(pick4 | (e4 - r4 > e6 + r6))), 0)) {
+    auto upper_end = [&](float ih, uint32_t (&h)[2]) {
+        h[0] = h[1] = 0u;
+#define NVFP4_STEP(K, SEL) h[K >> 2] = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(h[K >> 2], f[2 * K] * ih, f[2 * K + 1] * ih, 1.0f, SEL);
+        NVFP4_STEP(0, 0) NVFP4_STEP(4, 0) NVFP4_STEP(1, 1) NVFP4_STEP(5, 1)
+        NVFP4_STEP(2, 2) NVFP4_STEP(6, 2) NVFP4_STEP(3, 3) NVFP4_STEP(7, 3)
+#undef NVFP4_STEP
+    };
+    if (__builtin_expect(!same & (tiny | !(pick4 | (e4 - r4 > e6 + r6))), 0)) {     // too close in fp32: settle both, compare in fp64
+        uint32_t h6[2], h4[2];
+        upper_end(ih6, h6);
+        upper_end(ih4, h4);
         resolve_codes(w, sb6, sg, l6[0], l6[1], h6[0], h6[1]);
         resolve_codes(w, sb4, sg, l4[0], l4[1], h4[0], h4[1]);
-        h6[0] = l6[0]; h6[1] = l6[1];
-        h4[0] = l4[0]; h4[1] = l4[1];
         pick4 = block_error_f64(w, l4[0], l4[1], sb4, sg) < block_error_f64(w, l6[0], l6[1], sb6, sg);
     }
     pick4 &= !same;
     sbyte = pick4 ? s4 : s6;
     c0 = pick4 ? l4[0] : l6[0];
     c1 = pick4 ? l4[1] : l6[1];
-    resolve_codes(w, pick4 ? sb4 : sb6, sg, c0, c1, pick4 ? h4[0] : h6[0], pick4 ? h4[1] : h6[1]);
+    uint32_t hw[2];
+    upper_end(pick4 ? ih4 : ih6, hw);
+    resolve_codes(w, pick4 ? sb4 : sb6, sg, c0, c1, hw[0], hw[1]);   // (settled codes pass through unchanged)
 }
 #undef NVFP4_CVT4
 

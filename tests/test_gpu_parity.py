@@ -495,6 +495,28 @@ def test_quantize_four_over_six(oracle):
     _assert_search_equal(oracle, wl.to_bf16_bits(np.zeros((16, 64), np.float32)), "all zero")
 
 
+def test_four_over_six_errors_that_tie_in_exact_arithmetic(oracle):
+    """Blocks whose two candidates have EQUAL squared error in exact arithmetic (grid-like values, block scales in the
+    ratio 3 : 2) while the tensor scale has a full mantissa: the comparison then hangs on how the fp64 sums round, each
+    multiplication, subtraction and addition on its own, and a fused multiply-add anywhere in it changes the answer.
+    The first block is one that a randomized comparison against the oracle turned up; the rest are of its kind."""
+    bits = [0xbe40, 0x3d80, 0x3e40, 0xbd80, 0x3f10, 0x0, 0xbf00, 0x3f70, 0xbf88, 0x3ec0, 0xbf30, 0xbfe0, 0x3fa8, 0x3f50, 0x3d80, 0x3d80]
+    xb = np.zeros((2, 16), np.uint16)
+    xb[0] = bits
+    xb[1, 0] = 0x409C                                   # 4.875: the tensor scale 4.875 / 2688
+    want = _assert_search_equal(oracle, xb, "the block that was found")
+    assert want.scales[0, 0] == 0x77                    # the 4-target scale: its fp64 sum comes out one ulp smaller
+    _assert_search_equal(oracle, xb, "the same, scale given", gs=float(want.global_scale))
+    g = np.random.default_rng(755)
+    for amax in (4.875, 7.3125, 2.40625, 13.25):
+        x = (g.integers(-30, 31, size=(256, 512)) / 16.0).astype(np.float32)
+        x[g.random((256, 512)) < 0.15] = 0.0
+        x[0, 0] = amax
+        xb = wl.to_bf16_bits(x)
+        want = _assert_search_equal(oracle, xb, f"sixteenths, amax {amax}")
+        _assert_search_equal(oracle, xb, f"sixteenths, amax {amax}, scale given", gs=float(want.global_scale))
+
+
 def test_kv_quant_four_over_six(oracle):
     T, H, d = 129, 24, 128
     kb = wl.kv_tensor(T, H, d, 4, 0)
