@@ -4,6 +4,7 @@
     python tests/randomized_parity.py --what quantizers --seed 7 --cases 1000 [--scale 3] [--extreme]
     python tests/randomized_parity.py --what fused --seed 7 --cases 3000
     python tests/randomized_parity.py --what gemm --seed 7 --cases 300
+    python tests/randomized_parity.py --what lora --seed 7 --cases 300
 
 Every case draws a shape, a value distribution and the method's parameters from a seeded generator, runs the entry
 points through the C ABI and compares with the oracle: bit for bit for codes, scales, tensor scales, means and
@@ -150,16 +151,46 @@ def gemm(g, what, scale, extreme):
         assert (nv.bits_from_bf16(y16) == nv.bits_from_bf16(y32.to(torch.bfloat16))).all(), what + " bf16 output"
 
 
+def lora(g, what, scale, extreme):
+    """Rank-128 side branch: the down projection on unquantized activations, then the quantized GEMM with the branch
+    fused in, against the oracle fed the T the GPU produced (tiled shapes: K a multiple of 64, N of 8)."""
+    M, N, K = int(g.integers(1, 900)), 8 * int(g.integers(1, 120)), 64 * int(g.integers(1, 10))
+    lscale = float(g.choice([0.25, 0.5, 1.0, 2.0]))
+    what += f" {M}x{N}x{K} scale {lscale}"
+    r = nv.LORA_RANK
+    f32 = lambda a: wl.bf16_bits_to_f32(a).astype(np.float64)
+    xb = wl.to_bf16_bits((g.standard_normal((M, K)) * 2.0 ** g.integers(-3, 4)).astype(np.float32))
+    wb = wl.to_bf16_bits((g.standard_normal((N, K)) * 0.02).astype(np.float32))
+    ab = wl.to_bf16_bits((g.standard_normal((r, K)) * 0.02).astype(np.float32))
+    bb = wl.to_bf16_bits((g.standard_normal((N, r)) * 0.05).astype(np.float32))
+    t = nv.nvfp4_lora_down(dev_bf16(xb), dev_bf16(ab))
+    torch.cuda.synchronize()
+    tb = nv.bits_from_bf16(t)
+    want_t = ora.lora_down(xb, ab)
+    bound = np.abs(f32(xb)) @ np.abs(f32(ab)).T
+    assert (np.abs(f32(tb) - f32(want_t)) <= 2.0 ** -7 * np.abs(f32(want_t)) + 2.0 ** -15 * bound).all(), what + " down projection"
+    oa, ow = ora.quantize(xb), ora.quantize(wb)
+    ga, gw = nv.nvfp4_quantize(dev_bf16(xb)), nv.nvfp4_quantize(dev_bf16(wb))
+    Y, S = ora.gemm_lora(oa, ow, tb, bb, lscale)
+    y32 = nv.nvfp4_gemm_lora(ga, gw, t, dev_bf16(bb), lscale, nv.OUT_F32)
+    torch.cuda.synchronize()
+    assert_gemm_close(y32.cpu().numpy(), Y, S, what + " fused GEMM")
+    y16 = nv.nvfp4_gemm_lora(ga, gw, t, dev_bf16(bb), lscale, nv.OUT_BF16)
+    assert (nv.bits_from_bf16(y16) == nv.bits_from_bf16(y32.to(torch.bfloat16))).all(), what + " bf16 output"
+    zero = nv.nvfp4_gemm_lora(ga, gw, t, torch.zeros_like(dev_bf16(bb)), lscale, nv.OUT_F32)
+    assert torch.equal(zero, nv.nvfp4_gemm(ga, gw, nv.OUT_F32)), what + " zero adapter"
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--what", choices=("quantizers", "fused", "gemm"), default="quantizers")
+    ap.add_argument("--what", choices=("quantizers", "fused", "gemm", "lora"), default="quantizers")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cases", type=int, default=100)
     ap.add_argument("--scale", type=int, default=1, help="multiplies the tensor sides of the quantizer cases (up to 1600 x scale)")
     ap.add_argument("--extreme", action="store_true", help="quantizer cases at magnitudes 2^+-85 .. 2^+-118")
     args = ap.parse_args()
     ora.build()
-    run = {"quantizers": quantizers, "fused": fused, "gemm": gemm}[args.what]
+    run = {"quantizers": quantizers, "fused": fused, "gemm": gemm, "lora": lora}[args.what]
     t0 = time.time()
     for case in range(args.cases):
         g = np.random.default_rng([args.seed, case])
