@@ -249,9 +249,8 @@ int nvfp4_kv_quant(const void *kv_bf16, int64_t T, int64_t H, int64_t d, nvfp4_t
  * hipMalloc.  Same arguments and the same bytes as nvfp4_kv_quant, minus the workspace: the
  * partial maxima live in a fixed array inside the library's device image (4 KB on every GPU
  * the library runs on, held until the process ends; its address is looked up on the first
- * call on a device).  Windows that fit on the chip (up to ~120 MB of bf16) take the one-launch
- * kernel, which needs no partial maxima and leaves the array alone; larger ones take the two
- * passes that use it.  The call allocates nothing, frees nothing and calls no allocating
+ * call on a device).  Windows for which the one-launch kernel is taken (see nvfp4_set_one_launch) need
+ * no partial maxima and leave the array alone; the others take the two passes that use it.  The call allocates nothing, frees nothing and calls no allocating
  * routine; launch timing does not record it.
  * Limit: T * H * d <= NVFP4_NOALLOC_MAX_ELEMENTS, NVFP4_ERR_SHAPE beyond it.
  * All calls on one GPU share that array, and it keeps the last call's contents (every slot a
@@ -367,6 +366,16 @@ int  nvfp4_timing_read(int op, int *calls, float *total_ms);
  * be replayed; more than 64 such launches in flight at once on one GPU, or one graph replayed
  * concurrently with itself, would race. */
 void nvfp4_set_sync_spin_limit(uint32_t ticks_10ns);
+
+/* Which form the row quantizers (nvfp4_quantize with block_axis 0, the scale search, nvfp4_kv_quant*,
+ * nvfp4_quantize_for_all_to_all; no scale given) take for a tensor that fits on the chip.  The one-launch form
+ * fetches the tensor from HBM once, the two-pass form twice; in time they are within a few per cent of each
+ * other for large tensors, and the two passes are faster for middle sizes.  AUTO (the default) goes by
+ * measured sizes: one launch below 0.4 M blocks of 16 (plain rule only) and from 2.5 M blocks on, two passes in
+ * between; ALWAYS takes the one-launch form whenever the tensor fits (least HBM traffic); NEVER always streams.
+ * The bytes are the same either way.  Applies to calls made afterwards; NVFP4_ERR_SHAPE for another value. */
+enum { NVFP4_ONE_LAUNCH_AUTO = 0, NVFP4_ONE_LAUNCH_ALWAYS = 1, NVFP4_ONE_LAUNCH_NEVER = 2 };
+int nvfp4_set_one_launch(int mode);
 
 /* Every recorded duration of entry point `op`, in call order: up to max_records values in ms_out
  * (host pointer); returns how many were written, or a negative status.  Waits for the events. */

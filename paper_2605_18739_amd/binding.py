@@ -95,6 +95,8 @@ def lib():
         L.nvfp4_timing_read.argtypes = [c.c_int, c.POINTER(c.c_int), c.POINTER(c.c_float)]
         L.nvfp4_timing_read_all.restype = c.c_int
         L.nvfp4_timing_read_all.argtypes = [c.c_int, c.POINTER(c.c_float), c.c_int]
+        L.nvfp4_set_one_launch.restype = c.c_int
+        L.nvfp4_set_one_launch.argtypes = [c.c_int]
         L.nvfp4_set_sync_spin_limit.restype = None
         L.nvfp4_set_sync_spin_limit.argtypes = [c.c_uint32]
         L.nvfp4_probe.restype = c.c_int
@@ -394,6 +396,14 @@ def nvfp4_timing_read(op):
     n, ms = ctypes.c_int(0), ctypes.c_float(0)
     _check(lib().nvfp4_timing_read(op, ctypes.byref(n), ctypes.byref(ms)))
     return n.value, ms.value
+
+
+ONE_LAUNCH_AUTO, ONE_LAUNCH_ALWAYS, ONE_LAUNCH_NEVER = 0, 1, 2
+
+
+def nvfp4_set_one_launch(mode=ONE_LAUNCH_AUTO):
+    """Form of the row quantizers for tensors that fit on the chip (see include/nvfp4.h)."""
+    _check(lib().nvfp4_set_one_launch(int(mode)))
 
 
 def nvfp4_set_sync_spin_limit(ticks_10ns=0xFFFFFFFF):

@@ -90,8 +90,9 @@ int quantize_impl(const void *x, int64_t R, int64_t C, int64_t ld, int block_axi
     const uint16_t *xb = static_cast<const uint16_t *>(x);
     uint32_t *partial = static_cast<uint32_t *>(ws);
     int n_partial = 0;
-    if (!gs_in && block_axis == 0 && quantize_rows_resident_fits(R, C, ld, false)) {
-        // the tensor fits on the chip: one launch, one pass over the input
+    if (!gs_in && block_axis == 0 && quantize_rows_resident_fits(R, C, ld, false) &&
+        quantize_rows_resident_pays(R * (C >> 4), scale_search)) {
+        // the tensor fits on the chip (and is of a size at which that pays): one launch, one pass over the input
         hipError_t e = launch_quantize_rows_resident(xb, R, C, out->codes, out->scales, out->global_scale,
                                                      scale_search, nullptr, s);
         return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
@@ -206,7 +207,7 @@ int nvfp4_quantize_for_all_to_all(const void *x_bf16, int64_t T, int64_t H, int6
     const uint16_t *xb = static_cast<const uint16_t *>(x_bf16);
     uint32_t *partial = static_cast<uint32_t *>(workspace);
     int n_partial = 0;
-    if (!global_scale_in && quantize_rows_resident_fits(T * H, d, d, false)) {
+    if (!global_scale_in && quantize_rows_resident_fits(T * H, d, d, false) && quantize_rows_resident_pays(T * H * (d >> 4), false)) {
         // small enough to stay on the chip between the maximum and the encoding: one launch
         hipError_t e1 = launch_quantize_rows_resident(xb, T * H, d, out->codes, out->scales, out->global_scale, false,
                                                       nullptr, s, (int)H, (int)(H / P));
@@ -294,7 +295,7 @@ int nvfp4_kv_quant_k(const void *k_bf16, int64_t T, int64_t H, int64_t d, nvfp4_
     uint16_t *mean = static_cast<uint16_t *>(row_mean_bf16_out);
     uint32_t *partial = static_cast<uint32_t *>(workspace);
     int n_partial = 0;
-    if (quantize_rows_resident_fits(T * H, d, d, true)) {
+    if (quantize_rows_resident_fits(T * H, d, d, true) && quantize_rows_resident_pays(T * H * (d >> 4), true)) {
         hipError_t e = launch_quantize_rows_resident(x, T * H, d, out->codes, out->scales, out->global_scale, true,
                                                      mean, s);
         return e == hipSuccess ? NVFP4_OK : NVFP4_ERR_LAUNCH;
@@ -578,6 +579,14 @@ void nvfp4_set_timing_ops(uint32_t op_mask)
     std::lock_guard<std::mutex> lk(g_mu);
     g_timing = op_mask;
     g_used = 0;
+}
+
+int nvfp4_set_one_launch(int mode)
+{
+    if (mode < NVFP4_ONE_LAUNCH_AUTO || mode > NVFP4_ONE_LAUNCH_NEVER) return NVFP4_ERR_SHAPE;
+    std::lock_guard<std::mutex> lk(g_mu);
+    set_one_launch_mode(mode);
+    return NVFP4_OK;
 }
 
 void nvfp4_set_sync_spin_limit(uint32_t ticks_10ns)

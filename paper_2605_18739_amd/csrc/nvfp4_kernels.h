@@ -29,6 +29,8 @@ bool quantize_rows_resident_fits(int64_t rows, int64_t C, int64_t ld, bool smoot
 hipError_t launch_quantize_rows_resident(const uint16_t *x, int64_t rows, int64_t C, uint8_t *codes,
                                          uint8_t *scales, float *gs_out, bool scale_search, uint16_t *mean_out,
                                          hipStream_t s, int heads = 0, int slab_heads = 0);   // slab_heads > 0: all-to-all slab order
+bool quantize_rows_resident_pays(int64_t nblk, bool search_or_smooth);   // the dispatch rule on top of ..._fits
+void set_one_launch_mode(int mode);               // 0: by that rule, 1: whenever the tensor fits, 2: never
 void set_resident_spin_limit(uint32_t ticks);      // bound of the grid-wide wait, 10 ns ticks (0: give up at once)
 uint32_t resident_spin_limit();
 

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = nv.lib()
     names = _declared_symbols()
     assert {"nvfp4_quantize", "nvfp4_gemm", "nvfp4_gemm_act_quant", "nvfp4_kv_quant",
-            "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string",
+            "nvfp4_kv_dequant", "nvfp4_workspace_bytes", "nvfp4_status_string", "nvfp4_set_one_launch",
             "nvfp4_quantize_4over6", "nvfp4_kv_quant_4over6", "nvfp4_kv_quant_k",
             "nvfp4_kv_dequant_gather", "nvfp4_quantize_2d", "nvfp4_quantize_rht",
             "nvfp4_quantize_for_all_to_all", "nvfp4_lora_down", "nvfp4_gemm_lora",
@@ -38,6 +38,14 @@ def test_status_strings():
     for rc in (-1, -2, -3, -4, -5):
         assert len(L.nvfp4_status_string(rc)) > 5
     assert L.nvfp4_status_string(-99) == b"unknown status"
+
+
+def test_one_launch_mode_is_validated_on_the_host():
+    L = nv.lib()
+    for mode in (nv.ONE_LAUNCH_ALWAYS, nv.ONE_LAUNCH_NEVER, nv.ONE_LAUNCH_AUTO):
+        assert L.nvfp4_set_one_launch(mode) == 0
+    assert L.nvfp4_set_one_launch(3) == -2 and L.nvfp4_set_one_launch(-1) == -2         # NVFP4_ERR_SHAPE
+    assert L.nvfp4_set_one_launch(nv.ONE_LAUNCH_AUTO) == 0
 
 
 def test_workspace_sizes():

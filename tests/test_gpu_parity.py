@@ -197,6 +197,7 @@ def test_quantize_one_launch_path_with_and_without_the_grid_wide_wait(oracle):
     want_k = _oracle_k_path(oracle, kb)
     for limit in (None, 0):
         say(f"[one launch] wait bound {'default' if limit is None else limit}")
+        nv.nvfp4_set_one_launch(nv.ONE_LAUNCH_ALWAYS)          # at these sizes the default rule would partly take two passes
         if limit is not None:
             nv.nvfp4_set_sync_spin_limit(limit)
         try:
@@ -208,6 +209,32 @@ def test_quantize_one_launch_path_with_and_without_the_grid_wide_wait(oracle):
             assert_q_equal(gq, want_k[1], f"smoothed keys limit {limit}")
         finally:
             nv.nvfp4_set_sync_spin_limit()                     # back to the default bound
+            nv.nvfp4_set_one_launch()                          # and to the default rule
+
+
+def test_one_launch_and_two_pass_forms_return_the_same_bytes(oracle):
+    """Which form a tensor that fits on the chip takes is a matter of speed (nvfp4_set_one_launch): always, never
+    and the default rule give the oracle's bytes for the plain rule, the scale search, the smoothed keys and the
+    all-to-all packer, at a small, a middle and a large size."""
+    for T, H, d in ((40, 4, 64), (4620, 24, 128), (14000, 24, 128)):
+        kb = wl.kv_tensor(T, H, d, 31, T).reshape(T * H, d)
+        want, want46 = oracle.quantize(kb), oracle.quantize(kb, four_over_six=True)
+        want_mean, want_k = _oracle_k_path(oracle, kb)
+        kv = dev_bf16(kb).reshape(T, H, d)
+        for mode in (nv.ONE_LAUNCH_ALWAYS, nv.ONE_LAUNCH_NEVER, nv.ONE_LAUNCH_AUTO):
+            say(f"[one launch] mode {mode}, {T}x{H}x{d}")
+            nv.nvfp4_set_one_launch(mode)
+            try:
+                assert_q_equal(nv.nvfp4_kv_quant(kv), want, f"plain, mode {mode}")
+                assert_q_equal(nv.nvfp4_kv_quant_4over6(kv), want46, f"search, mode {mode}")
+                gq, gm = nv.nvfp4_kv_quant_k(kv)
+                assert (nv.bits_from_bf16(gm) == want_mean).all()
+                assert_q_equal(gq, want_k, f"smoothed keys, mode {mode}")
+                codes, scales, gs = host_q(nv.nvfp4_quantize_for_all_to_all(kv, 2))
+                slabs = lambda a: a.reshape(T, 2, H // 2, -1).transpose(1, 0, 2, 3).reshape(T * H, -1)
+                assert (codes == slabs(want.codes)).all() and (scales == slabs(want.scales)).all(), f"all-to-all, mode {mode}"
+            finally:
+                nv.nvfp4_set_one_launch()
 
 
 @pytest.mark.parametrize("magnitude", [1e-33, 1e-36, 3e-39, 1e30, 3e37])
@@ -1114,6 +1141,7 @@ def test_one_launch_quantizer_replayed_from_a_graph_on_changing_data(oracle):
         nv.nvfp4_kv_quant_k(kv, out=qk, row_mean=mean, workspace=ws)
         nv.nvfp4_kv_quant_noalloc(kv, out=qn)
 
+    nv.nvfp4_set_one_launch(nv.ONE_LAUNCH_ALWAYS)       # (the default rule would take two passes for some of these sizes)
     fill(0)
     step()                                              # eager: first use of every kernel variant
     torch.cuda.synchronize()
@@ -1137,6 +1165,7 @@ def test_one_launch_quantizer_replayed_from_a_graph_on_changing_data(oracle):
         assert_q_equal(qk, want_k, f"smoothed keys, replay {rep}")
         assert_q_equal(qn, oracle.quantize(kb), f"allocation-free entry, replay {rep}")
         del other
+    nv.nvfp4_set_one_launch()                           # back to the default rule
 
 
 def test_full_size_ffn_pair_config3(oracle):
