@@ -370,9 +370,10 @@ void nvfp4_set_sync_spin_limit(uint32_t ticks_10ns);
 /* Which form the row quantizers (nvfp4_quantize with block_axis 0, the scale search, nvfp4_kv_quant*,
  * nvfp4_quantize_for_all_to_all; no scale given) take for a tensor that fits on the chip.  The one-launch form
  * fetches the tensor from HBM once, the two-pass form twice; in time they are within a few per cent of each
- * other for large tensors, and the two passes are faster for middle sizes.  AUTO (the default) goes by
- * measured sizes: one launch below 0.4 M blocks of 16 (plain rule only) and from 2.5 M blocks on, two passes in
- * between; ALWAYS takes the one-launch form whenever the tensor fits (least HBM traffic); NEVER always streams.
+ * other for the plain rule on large tensors, and the two passes are faster for middle sizes and for the scale
+ * search and the smoothed keys.  AUTO (the default) goes by what was measured: one launch for the plain rule below
+ * 0.4 M blocks of 16 and from 2.5 M blocks on, two passes otherwise; ALWAYS takes the one-launch form whenever
+ * the tensor fits (least HBM traffic); NEVER always streams.
  * The bytes are the same either way.  Applies to calls made afterwards; NVFP4_ERR_SHAPE for another value. */
 enum { NVFP4_ONE_LAUNCH_AUTO = 0, NVFP4_ONE_LAUNCH_ALWAYS = 1, NVFP4_ONE_LAUNCH_NEVER = 2 };
 int nvfp4_set_one_launch(int mode);

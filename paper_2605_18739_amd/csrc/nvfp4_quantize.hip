@@ -217,16 +217,21 @@ void quantize_rows_kernel(const uint16_t *__restrict__ x, int64_t R,
                 // SMOOTH: C / 16 = 1 << row_shift blocks per row
                 if constexpr (SMOOTH) smooth_block16(w, __uint_as_float((uint32_t)row_mean[g >> row_shift] << 16));
                 if (__builtin_expect(shift != 1.0f, 0)) rescale_block16(w, shift);
-                uint32_t acc = 0;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
-                float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
                 uint32_t sbyte, c0, c1;
-                if constexpr (SEARCH) {
-                    encode_block16_4over6(w, bmax, sgq, inv_6sg, inv_4sg, sbyte, c0, c1);
+                if (SEARCH && __builtin_expect(shift == 1.0f, 1)) {
+                    // the straight-line form: the candidates compared on one bracket end, the winner settled
+                    quantize_block16_4over6_inline(w, sgq, inv_6sg, inv_4sg, sbyte, c0, c1);
                 } else {
-                    sbyte = block_scale_exact(bmax, sgq, inv_6sg);
-                    encode_block16(w, e4m3_to_f32(sbyte), sgq, c0, c1);
+                    uint32_t acc = 0;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc = pk_absmax_u16(acc, w[i]);
+                    const float bmax = __uint_as_float(pk_hmax_u16(acc) << 16);
+                    if constexpr (SEARCH) {
+                        encode_block16_4over6(w, bmax, sgq, inv_6sg, inv_4sg, sbyte, c0, c1);
+                    } else {
+                        sbyte = block_scale_exact(bmax, sgq, inv_6sg);
+                        encode_block16(w, e4m3_to_f32(sbyte), sgq, c0, c1);
+                    }
                 }
                 uint2v cc = {c0, c1};
                 int64_t go = g;                       // output block index

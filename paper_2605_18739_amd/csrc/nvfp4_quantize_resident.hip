@@ -363,11 +363,12 @@ bool quantize_rows_resident_fits(int64_t rows, int64_t C, int64_t ld, bool smoot
 }
 
 // Whether the one-launch form is taken for a tensor that fits.  It fetches the tensor once where the two passes
-// fetch it twice, but its encoding runs at two waves per SIMD where the streaming pass has eight, and measured
-// back to back on cache-like data the two passes are the faster form in between: by 5-11 % for the plain rule from
-// about 0.5 M to 2.5 M blocks, by 5-18 % for the scale search and the smoothed keys up to 2.5 M blocks; below 0.4 M
-// blocks the plain rule gains the second launch it does not make, and from 2.5 M blocks (80 MB) on the forms take
-// the same time and the single fetch decides.  mode 1: whenever it fits; mode 2: never.
+// fetch it twice, but its encoding runs at two waves per SIMD where the streaming pass has six to eight, and
+// measured back to back on cache-like data: for the scale search and the smoothed keys, whose encoding is the
+// heavier, the two passes are faster at every size (by 7-14 % from 1 M blocks up to the largest tensor that
+// fits); for the plain rule they are faster by 5-11 % from about 0.5 M to 2.5 M blocks, below 0.4 M blocks the
+// one launch gains the second launch it does not make, and from 2.5 M blocks (80 MB) on the two forms take the
+// same time and the single fetch decides.  mode 1: whenever it fits; mode 2: never.
 static int g_one_launch_mode = 0;
 void set_one_launch_mode(int mode) { g_one_launch_mode = mode; }
 bool quantize_rows_resident_pays(int64_t nblk, bool search_or_smooth)
@@ -375,7 +376,7 @@ bool quantize_rows_resident_pays(int64_t nblk, bool search_or_smooth)
     if (g_one_launch_mode == 1) return true;
     if (g_one_launch_mode == 2) return false;
     constexpr int64_t kSmall = 400000, kLarge = 2500000;
-    return nblk >= kLarge || (!search_or_smooth && nblk < kSmall);
+    return !search_or_smooth && (nblk >= kLarge || nblk < kSmall);
 }
 
 template <bool SEARCH, bool SMOOTH>
